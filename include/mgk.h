@@ -1,0 +1,142 @@
+/* mgk.h - C ABI of the MI355X marginalized-graph-kernel solver.
+ *
+ * The library evaluates the marginalized graph kernel between labeled graphs
+ * (paper Section II-B, Eq. 1)
+ *
+ *     K(G,G') = p_x^T ( D_x V_x^{-1} - A_x (.) E_x )^{-1} D_x q_x
+ *
+ * by running the Jacobi-preconditioned conjugate-gradient iteration of
+ * Alg. 1 on the tensor-product system of each requested pair, with the
+ * off-diagonal product (A (x) A') (.) (E (x)k E') p regenerated on the fly from
+ * the two graphs (Alg. 2, Section III) instead of being stored.  Graphs are
+ * held on the device as coordinate lists of non-empty 8x8 tiles ("octiles",
+ * Section III-D) with a 64-bit occupancy bitmap and packed nonzeros per tile
+ * (Section IV-A/B), after an optional partition-based vertex reordering
+ * (Section IV-A, Eq. 3).
+ *
+ * Conventions
+ *  - Every entry point returns an mgk_status and never throws or aborts across
+ *    the ABI.  mgk_last_error() gives a message for the last failure on a ctx.
+ *  - "host" pointers are ordinary CPU memory, read before the call returns and
+ *    never retained.  "device" pointers are GPU global memory on the ctx's
+ *    device (for example a torch tensor's data_ptr()); the caller owns them.
+ *  - Kernels are enqueued on the HIP stream passed as `stream` (a hipStream_t
+ *    cast to void*, NULL = the null stream).  Results are valid once the caller
+ *    has synchronised that stream.
+ *  - A ctx is bound to one device and is not thread-safe.  Batches belong to
+ *    the ctx that loaded them.
+ *  - Non-convergence is data, not an error: the pair's flag is set to 1 and the
+ *    value of the last iterate is still written.
+ *  - Precision: fp32 on the device.  Product index of (i,i') is i*n'+i'.
+ */
+#ifndef MGK_H
+#define MGK_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mgk_ctx mgk_ctx;     /* opaque: parameters, device scratch, error text */
+typedef struct mgk_batch mgk_batch; /* opaque: a packed (and reordered) set of graphs  */
+
+typedef enum {
+    MGK_OK = 0,
+    MGK_EINVAL = 1,  /* bad argument or invalid graph                     */
+    MGK_ENOMEM = 2,  /* host or device allocation failed                  */
+    MGK_EDEVICE = 3, /* a HIP call failed                                 */
+    MGK_ESTATE = 4,  /* object used with the wrong ctx / after free       */
+    MGK_ELIMIT = 5   /* a pair is larger than this build can solve        */
+} mgk_status;
+
+/* vertex reordering applied when a batch is loaded (Section IV-A) */
+enum { MGK_REORDER_NONE = 0, MGK_REORDER_PBR = 1, MGK_REORDER_RCM = 2 };
+/* tile-pair primitive selection (Section IV-B, "hybrid dense-sparse") */
+enum { MGK_TILE_AUTO = 0, MGK_TILE_SPARSE = 1, MGK_TILE_DENSE = 2 };
+
+/* Create a context on HIP device `device`.  *out is NULL on failure.
+ * device = -1 creates a host-only context: graphs can be loaded, reordered,
+ * packed and inspected, nothing is copied to a GPU, and the solve calls
+ * return MGK_ESTATE. */
+mgk_status mgk_create(mgk_ctx** out, int device);
+void mgk_destroy(mgk_ctx* ctx);
+/* Message of the last failed call on ctx (ctx-owned, valid until the next call). */
+const char* mgk_last_error(const mgk_ctx* ctx);
+
+/* ---- base kernels and solver parameters (Section II-B, Alg. 1) -------------
+ * Vertex kernel: kappa_v(v,v') = 1 if v == v' else h, 0 < h <= 1.
+ * Edge kernel, square exponential (Appendix B): exp(-(e-e')^2 / (2 l^2)), l > 0.
+ * Edge kernel, constant: kappa_e == c, 0 <= c <= 1 (c = 1, h = 1 gives Eq. 2).
+ * Stopping probability q > 0, the same on every vertex; d_i = sum_j A_ij + q.
+ * Solver: stop when r^T r <= rtol^2 b^T b (b = D_x q_x) or after max_iter
+ * iterations (max_iter <= 0: 2 N capped at 1000).  Defaults: h = 1, constant
+ * edge kernel c = 1, q = 0.05, rtol = 1e-6. */
+mgk_status mgk_set_vertex_kernel_delta(mgk_ctx* ctx, float h);
+mgk_status mgk_set_edge_kernel_se(mgk_ctx* ctx, float length_scale);
+mgk_status mgk_set_edge_kernel_const(mgk_ctx* ctx, float c);
+mgk_status mgk_set_stop_prob(mgk_ctx* ctx, float q);
+mgk_status mgk_set_solver(mgk_ctx* ctx, float rtol, int32_t max_iter);
+/* Force the sparse or the dense tile-pair primitive, or choose per tile pair. */
+mgk_status mgk_set_tile_path(mgk_ctx* ctx, int32_t mode);
+/* Tuning knobs, safe to leave alone.  waves_per_pair: wavefronts of the
+ * workgroup that solves one on-chip pair (1, 2, 4, 8 or 16; 0 = automatic). */
+mgk_status mgk_set_launch(mgk_ctx* ctx, int32_t waves_per_pair);
+
+/* ---- graphs -----------------------------------------------------------------
+ * Load n_graphs graphs given in flat host arrays (all caller-owned, copied):
+ *   vtx_off[n_graphs+1]   prefix offsets into the per-vertex arrays
+ *   vtx_label[sum n]      integer vertex labels
+ *   start_prob[sum n]     starting probabilities p, or NULL for 1/n
+ *   edge_off[n_graphs+1]  prefix offsets into the per-edge arrays
+ *   src, dst              endpoints, ids local to the graph; each undirected
+ *                         edge listed once in either orientation
+ *   weight                A_ij > 0, or NULL for 1
+ *   edge_label            E_ij, or NULL for 0 (unlabeled)
+ * Rejected with MGK_EINVAL: empty graph, endpoint out of range, self loop,
+ * duplicate edge, weight that is not finite and positive, non-finite label
+ * or probability.  The graphs are reordered (`reorder`), cut into octiles,
+ * empty octiles dropped, and copied to the device. */
+mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs,
+                           const int64_t* vtx_off, const int32_t* vtx_label,
+                           const float* start_prob,
+                           const int64_t* edge_off, const int32_t* src, const int32_t* dst,
+                           const float* weight, const float* edge_label,
+                           int32_t reorder, mgk_batch** out);
+void mgk_free_batch(mgk_ctx* ctx, mgk_batch* batch);
+
+/* Totals over the batch (any pointer may be NULL): graphs, vertices, stored
+ * nonzeros (2 per edge), non-empty octiles, and non-empty off-diagonal
+ * octiles (twice the objective of Eq. 3 for the ordering in use). */
+mgk_status mgk_batch_stats(const mgk_batch* batch, int64_t* n_graphs, int64_t* n_vertices,
+                           int64_t* nnz, int64_t* n_tiles, int64_t* n_offdiag_tiles);
+/* perm[vtx_off[g] + old_id] = new (stored) id of that vertex in graph g. */
+mgk_status mgk_batch_permutation(const mgk_batch* batch, int32_t* perm_host);
+/* Host copy of graph g's packed form, for inspection and tests.  tile_row,
+ * tile_col, bitmap: [*n_tiles]; w, e: [*nnz] packed tile by tile in bit order
+ * (bit 8*r+c of the bitmap <-> row 8*tile_row+r, column 8*tile_col+c).
+ * Pass NULL arrays to query the counts only. */
+mgk_status mgk_batch_get_tiles(const mgk_batch* batch, int32_t g, int32_t* n_tiles, int32_t* nnz,
+                               int32_t* tile_row, int32_t* tile_col, uint64_t* bitmap,
+                               float* w, float* e);
+
+/* ---- kernel values ----------------------------------------------------------
+ * mgk_gram: all pairs of one batch.  K_dev[G*G] row-major, both triangles
+ * written (K[i][j] == K[j][i] bit for bit: each unordered pair is solved
+ * once).  iters_dev / flag_dev: optional [G*G] int32 arrays receiving the
+ * number of PCG iterations and 0 (converged) / 1 (stopped at max_iter).
+ * The job list of the batch is built on the first call and kept. */
+mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev,
+                    int32_t* iters_dev, int32_t* flag_dev, void* stream);
+
+/* mgk_pairs: K_dev[k] = K(X[i_host[k]], Y[j_host[k]]), k < n_pairs.  Y may be
+ * the same batch as X.  i_host / j_host are host arrays.  Outputs as above,
+ * length n_pairs. */
+mgk_status mgk_pairs(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
+                     const int32_t* i_host, const int32_t* j_host, float* K_dev,
+                     int32_t* iters_dev, int32_t* flag_dev, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MGK_H */

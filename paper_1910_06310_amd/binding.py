@@ -1,0 +1,242 @@
+"""Thin ctypes binding of the C ABI declared in ``include/mgk.h``.
+
+Argument marshalling only: every step of the solve runs in the HIP library.
+torch supplies device memory for the outputs and the stream.  There is no CPU
+fallback: if ``libmgk.so`` is missing the import of :func:`load_library` raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmgk.so")
+_lib = None
+
+OK, EINVAL, ENOMEM, EDEVICE, ESTATE, ELIMIT = range(6)
+REORDER_NONE, REORDER_PBR, REORDER_RCM = 0, 1, 2
+TILE_AUTO, TILE_SPARSE, TILE_DENSE = 0, 1, 2
+
+EXPORTS = [
+    "mgk_create", "mgk_destroy", "mgk_last_error",
+    "mgk_set_vertex_kernel_delta", "mgk_set_edge_kernel_se", "mgk_set_edge_kernel_const",
+    "mgk_set_stop_prob", "mgk_set_solver", "mgk_set_tile_path", "mgk_set_launch",
+    "mgk_load_graphs", "mgk_free_batch", "mgk_batch_stats", "mgk_batch_permutation",
+    "mgk_batch_get_tiles", "mgk_gram", "mgk_pairs",
+]
+
+
+class MgkError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("mgk status %d: %s" % (status, message))
+        self.status = status
+
+
+def load_library(path: Optional[str] = None):
+    """dlopen the HIP library.  torch is imported first so that both share one
+    HIP runtime (the stream handle passed across the ABI belongs to it)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = path or _LIB_PATH
+    if not os.path.exists(path):
+        raise ImportError(
+            "HIP library %s is not built; run `python -m paper_1910_06310_amd.build`" % path)
+    import torch  # noqa: F401
+    lib = ctypes.CDLL(path)
+    c = ctypes
+    vp, i32, i64, f32 = c.c_void_p, c.c_int32, c.c_int64, c.c_float
+    lib.mgk_create.argtypes = [c.POINTER(vp), c.c_int]
+    lib.mgk_destroy.argtypes = [vp]
+    lib.mgk_destroy.restype = None
+    lib.mgk_last_error.argtypes = [vp]
+    lib.mgk_last_error.restype = c.c_char_p
+    lib.mgk_set_vertex_kernel_delta.argtypes = [vp, f32]
+    lib.mgk_set_edge_kernel_se.argtypes = [vp, f32]
+    lib.mgk_set_edge_kernel_const.argtypes = [vp, f32]
+    lib.mgk_set_stop_prob.argtypes = [vp, f32]
+    lib.mgk_set_solver.argtypes = [vp, f32, i32]
+    lib.mgk_set_tile_path.argtypes = [vp, i32]
+    lib.mgk_set_launch.argtypes = [vp, i32]
+    lib.mgk_load_graphs.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, c.POINTER(vp)]
+    lib.mgk_free_batch.argtypes = [vp, vp]
+    lib.mgk_free_batch.restype = None
+    lib.mgk_batch_stats.argtypes = [vp] + [c.POINTER(i64)] * 5
+    lib.mgk_batch_permutation.argtypes = [vp, vp]
+    lib.mgk_batch_get_tiles.argtypes = [vp, i32, c.POINTER(i32), c.POINTER(i32), vp, vp, vp, vp, vp]
+    lib.mgk_gram.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.mgk_pairs.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp, vp]
+    for name in EXPORTS:
+        fn = getattr(lib, name)
+        if name not in ("mgk_destroy", "mgk_free_batch", "mgk_last_error"):
+            fn.restype = c.c_int
+    _lib = lib
+    return lib
+
+
+def _host(a, dtype):
+    if a is None:
+        return None, None
+    arr = np.ascontiguousarray(a, dtype=dtype)
+    return arr, arr.ctypes.data_as(ctypes.c_void_p)
+
+
+def _dev_ptr(t, dtype_name: str, numel: int):
+    import torch
+    if t is None:
+        return None
+    want = getattr(torch, dtype_name)
+    if not t.is_cuda or t.dtype != want or not t.is_contiguous() or t.numel() < numel:
+        raise ValueError("output must be a contiguous cuda %s tensor with >= %d elements"
+                         % (dtype_name, numel))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+class Batch:
+    """A set of graphs packed and resident on the device (mgk_batch)."""
+
+    def __init__(self, solver: "Solver", handle, vtx_off: np.ndarray):
+        self._solver = solver
+        self._h = handle
+        self.vtx_off = vtx_off
+        self.n_graphs = len(vtx_off) - 1
+
+    def stats(self) -> dict:
+        lib = load_library()
+        vals = [ctypes.c_int64(0) for _ in range(5)]
+        self._solver._check(lib.mgk_batch_stats(self._h, *[ctypes.byref(v) for v in vals]))
+        keys = ["n_graphs", "n_vertices", "nnz", "n_tiles", "n_offdiag_tiles"]
+        return {k: int(v.value) for k, v in zip(keys, vals)}
+
+    def permutation(self) -> np.ndarray:
+        lib = load_library()
+        perm = np.zeros(int(self.vtx_off[-1]), dtype=np.int32)
+        self._solver._check(lib.mgk_batch_permutation(self._h, perm.ctypes.data_as(ctypes.c_void_p)))
+        return perm
+
+    def get_tiles(self, g: int) -> dict:
+        lib = load_library()
+        nt, nz = ctypes.c_int32(0), ctypes.c_int32(0)
+        self._solver._check(lib.mgk_batch_get_tiles(self._h, g, ctypes.byref(nt), ctypes.byref(nz),
+                                                    None, None, None, None, None))
+        tr = np.zeros(nt.value, np.int32); tc = np.zeros(nt.value, np.int32)
+        bm = np.zeros(nt.value, np.uint64)
+        w = np.zeros(nz.value, np.float32); e = np.zeros(nz.value, np.float32)
+        p = lambda a: a.ctypes.data_as(ctypes.c_void_p)
+        self._solver._check(lib.mgk_batch_get_tiles(self._h, g, ctypes.byref(nt), ctypes.byref(nz),
+                                                    p(tr), p(tc), p(bm), p(w), p(e)))
+        return {"tile_row": tr, "tile_col": tc, "bitmap": bm, "w": w, "e": e}
+
+    def free(self):
+        if self._h is not None and self._solver._h is not None:
+            load_library().mgk_free_batch(self._solver._h, self._h)
+        self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+class Solver:
+    """One mgk_ctx.  Method names follow the C ABI without the ``mgk_`` prefix."""
+
+    def __init__(self, device: int = 0):
+        lib = load_library()
+        h = ctypes.c_void_p()
+        st = lib.mgk_create(ctypes.byref(h), device)
+        if st != OK:
+            raise MgkError(st, "mgk_create failed (is a HIP device %d visible?)" % device)
+        self._h = h
+        self.device = device
+
+    def _check(self, st: int):
+        if st != OK:
+            msg = load_library().mgk_last_error(self._h)
+            raise MgkError(st, msg.decode() if msg else "")
+
+    def destroy(self):
+        if self._h is not None:
+            load_library().mgk_destroy(self._h)
+            self._h = None
+
+    def set_vertex_kernel_delta(self, h: float):
+        self._check(load_library().mgk_set_vertex_kernel_delta(self._h, h))
+
+    def set_edge_kernel_se(self, length_scale: float):
+        self._check(load_library().mgk_set_edge_kernel_se(self._h, length_scale))
+
+    def set_edge_kernel_const(self, c: float):
+        self._check(load_library().mgk_set_edge_kernel_const(self._h, c))
+
+    def set_stop_prob(self, q: float):
+        self._check(load_library().mgk_set_stop_prob(self._h, q))
+
+    def set_solver(self, rtol: float = 1e-6, max_iter: int = 0):
+        self._check(load_library().mgk_set_solver(self._h, rtol, max_iter))
+
+    def set_tile_path(self, mode: int):
+        self._check(load_library().mgk_set_tile_path(self._h, mode))
+
+    def set_launch(self, waves_per_pair: int = 0):
+        self._check(load_library().mgk_set_launch(self._h, waves_per_pair))
+
+    def load_graphs(self, vtx_off, vtx_label, edge_off, src, dst, weight=None, edge_label=None,
+                    start_prob=None, reorder: int = REORDER_PBR) -> Batch:
+        lib = load_library()
+        vo, pvo = _host(vtx_off, np.int64)
+        vl, pvl = _host(vtx_label, np.int32)
+        sp, psp = _host(start_prob, np.float32)
+        eo, peo = _host(edge_off, np.int64)
+        s, ps = _host(src, np.int32)
+        d, pd = _host(dst, np.int32)
+        w, pw = _host(weight, np.float32)
+        e, pe = _host(edge_label, np.float32)
+        h = ctypes.c_void_p()
+        self._check(lib.mgk_load_graphs(self._h, len(vo) - 1, pvo, pvl, psp, peo, ps, pd, pw, pe,
+                                        reorder, ctypes.byref(h)))
+        return Batch(self, h, vo.copy())
+
+    def load_batch(self, batch, reorder: int = REORDER_PBR, start_prob=None) -> Batch:
+        """Convenience for objects with the flat arrays as attributes."""
+        return self.load_graphs(batch.vtx_off, batch.vtx_label, batch.edge_off, batch.src,
+                                batch.dst, batch.weight, batch.edge_label, start_prob, reorder)
+
+    def gram(self, batch: Batch, K, iters=None, flags=None, stream=None):
+        G = batch.n_graphs
+        self._check(load_library().mgk_gram(
+            self._h, batch._h, _dev_ptr(K, "float32", G * G), _dev_ptr(iters, "int32", G * G),
+            _dev_ptr(flags, "int32", G * G), _stream_ptr(stream)))
+
+    def pairs(self, X: Batch, Y: Batch, i_idx: Sequence[int], j_idx: Sequence[int], K,
+              iters=None, flags=None, stream=None):
+        ii, pi = _host(i_idx, np.int32)
+        jj, pj = _host(j_idx, np.int32)
+        n = len(ii)
+        if len(jj) != n:
+            raise ValueError("index arrays differ in length")
+        self._check(load_library().mgk_pairs(
+            self._h, X._h, Y._h, n, pi, pj, _dev_ptr(K, "float32", n),
+            _dev_ptr(iters, "int32", n), _dev_ptr(flags, "int32", n), _stream_ptr(stream)))
+
+    def configure(self, params):
+        """Apply q, h and the square-exponential length scale of a workload."""
+        self.set_stop_prob(params.q)
+        self.set_vertex_kernel_delta(params.h)
+        self.set_edge_kernel_se(params.length_scale)
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

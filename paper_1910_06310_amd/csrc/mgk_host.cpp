@@ -1,0 +1,611 @@
+// C ABI of the solver: contexts, graph loading (validate, reorder, cut into
+// octiles, bitmap-pack, upload), job lists and kernel launches.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <numeric>
+#include <string>
+#include <vector>
+
+#include "../../include/mgk.h"
+#include "mgk_internal.h"
+#include "mgk_launch.h"
+#include "mgk_reorder.h"
+
+namespace {
+
+constexpr int kTile = 8;
+
+struct JobBin {
+    int64_t first = 0;   // index of the bin's first job in the job array
+    int64_t count = 0;
+    size_t lds_bytes = 0;
+};
+
+struct JobList {
+    MgkJob* dev = nullptr;
+    int64_t n = 0;
+    std::vector<JobBin> bins;
+};
+
+}  // namespace
+
+struct mgk_batch {
+    mgk_ctx* owner = nullptr;
+    int32_t n_graphs = 0;
+    int64_t n_vertices = 0, nnz = 0, n_tiles = 0, n_offdiag = 0;
+    bool weighted = false;
+    double label_mean = 0.0;
+    // host copies
+    std::vector<MgkGraphDesc> graphs;
+    std::vector<MgkTile> tiles;
+    std::vector<float> w, e;
+    std::vector<int32_t> perm;     // [n_vertices], perm[voff + old] = new
+    std::vector<int64_t> vtx_off;  // [G+1]
+    // device
+    void* blob = nullptr;
+    MgkBatchDev dev{};
+    JobList gram_jobs;
+};
+
+struct mgk_ctx {
+    int device = 0;
+    std::string err;
+    float q = 0.05f, h = 1.0f, length_scale = 1.0f, ke_const = 1.0f, rtol = 1e-6f;
+    int edge_kernel = MGK_EK_CONST;
+    int max_iter = 0;
+    int tile_path = MGK_TILE_AUTO;
+    int waves = 0;
+    JobList pair_jobs;          // reused by mgk_pairs
+    int64_t pair_jobs_cap = 0;
+    hipStream_t pair_jobs_stream = nullptr;
+    bool pair_jobs_busy = false;
+};
+
+namespace {
+
+mgk_status fail(mgk_ctx* ctx, mgk_status st, const char* fmt, ...) {
+    if (ctx) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        ctx->err = buf;
+    }
+    return st;
+}
+
+#define MGK_HIP(ctx, call)                                                              \
+    do {                                                                                \
+        hipError_t e_ = (call);                                                         \
+        if (e_ != hipSuccess)                                                           \
+            return fail(ctx, MGK_EDEVICE, "%s failed: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+template <class T>
+size_t append_bytes(std::vector<char>& blob, const std::vector<T>& v) {
+    size_t off = (blob.size() + 255) & ~(size_t)255;
+    blob.resize(off + std::max<size_t>(v.size() * sizeof(T), 16));
+    if (!v.empty()) memcpy(blob.data() + off, v.data(), v.size() * sizeof(T));
+    return off;
+}
+
+MgkParams make_params(const mgk_ctx* ctx, const mgk_batch* X) {
+    MgkParams p{};
+    p.q = ctx->q;
+    p.h = ctx->h;
+    const double alpha = 1.0 / (2.0 * (double)ctx->length_scale * (double)ctx->length_scale);
+    p.e_scale = (float)std::sqrt(alpha * 1.4426950408889634);  // exp(-a d^2) = exp2(-(d sqrt(a log2 e))^2)
+    p.e_shift = (float)X->label_mean;
+    p.ke_const = ctx->ke_const;
+    p.rtol2 = ctx->rtol * ctx->rtol;
+    p.max_iter = ctx->max_iter;
+    p.edge_kernel = ctx->edge_kernel;
+    return p;
+}
+
+// Orientation and cost of one pair for the on-chip solver.  The inner graph's
+// nonzeros are spread over lanes in chunks of 64, the outer graph's are
+// streamed, so the work is z_outer * ceil(z_inner / 64) wave iterations.
+struct PairPlan {
+    bool swap;       // true: Y's graph is the outer one
+    int64_t cost;
+    int64_t lds_words;
+};
+
+PairPlan plan_pair(const MgkGraphDesc& a, const MgkGraphDesc& b, bool may_swap) {
+    auto passes = [](int64_t zo, int64_t zi) { return zo * ((zi + 63) / 64); };
+    PairPlan pl;
+    const int64_t keep = passes(a.nnz, b.nnz), swp = passes(b.nnz, a.nnz);
+    pl.swap = may_swap && swp < keep;
+    const int64_t N = (int64_t)a.n * b.n;
+    pl.cost = std::min(keep, pl.swap ? swp : keep) * 64 + 16 * N;
+    pl.lds_words = pl.swap ? mgk_small_lds_words(b.n, a.n, b.nnz, a.nnz)
+                           : mgk_small_lds_words(a.n, b.n, a.nnz, b.nnz);
+    return pl;
+}
+
+// LDS size classes: k pairs resident per compute unit.
+const int kResident[] = {16, 12, 10, 8, 6, 5, 4, 3, 2, 1};
+
+struct HostJob {
+    MgkJob job;
+    int64_t cost;
+    int32_t cls;
+};
+
+mgk_status build_job_list(mgk_ctx* ctx, const mgk_batch* X, const mgk_batch* Y,
+                          std::vector<HostJob>& jobs, JobList& out, hipStream_t stream,
+                          int64_t* capacity) {
+    // class of each job, then order by (class, cost descending): big pairs start first
+    std::stable_sort(jobs.begin(), jobs.end(), [](const HostJob& a, const HostJob& b) {
+        return a.cls != b.cls ? a.cls > b.cls : a.cost > b.cost;
+    });
+    out.bins.clear();
+    out.n = (int64_t)jobs.size();
+    std::vector<MgkJob> flat(jobs.size());
+    const int n_cls = (int)(sizeof kResident / sizeof kResident[0]);
+    for (size_t k = 0; k < jobs.size(); ++k) {
+        flat[k] = jobs[k].job;
+        if (out.bins.empty() || jobs[k].cls != jobs[k - 1].cls) {
+            JobBin b;
+            b.first = (int64_t)k;
+            b.count = 0;
+            const int res = kResident[std::min(jobs[k].cls, n_cls - 1)];
+            b.lds_bytes = (size_t)(MGK_LDS_LIMIT_BYTES / res) & ~(size_t)255;
+            out.bins.push_back(b);
+        }
+        out.bins.back().count++;
+    }
+    (void)X; (void)Y;
+    if (capacity == nullptr || *capacity < out.n) {
+        if (out.dev) MGK_HIP(ctx, hipFree(out.dev));
+        out.dev = nullptr;
+        const int64_t cap = std::max<int64_t>(out.n, 1);
+        MGK_HIP(ctx, hipMalloc((void**)&out.dev, (size_t)cap * sizeof(MgkJob)));
+        if (capacity) *capacity = cap;
+    }
+    if (out.n) {
+        MGK_HIP(ctx, hipMemcpyAsync(out.dev, flat.data(), (size_t)out.n * sizeof(MgkJob),
+                                    hipMemcpyHostToDevice, stream));
+        MGK_HIP(ctx, hipStreamSynchronize(stream));  // `flat` is pageable and dies here
+    }
+    return MGK_OK;
+}
+
+int lds_class(int64_t lds_words) {
+    const int64_t bytes = lds_words * 4;
+    const int n_cls = (int)(sizeof kResident / sizeof kResident[0]);
+    for (int c = 0; c < n_cls; ++c)
+        if (bytes <= (int64_t)((MGK_LDS_LIMIT_BYTES / kResident[c]) & ~255)) return c;
+    return -1;
+}
+
+mgk_status launch_jobs(mgk_ctx* ctx, const mgk_batch* X, const mgk_batch* Y, const JobList& jl,
+                       float* K, int32_t* iters, int32_t* flags, hipStream_t stream) {
+    const MgkParams prm = make_params(ctx, X);
+    const bool weighted = X->weighted || Y->weighted;
+    const int waves = ctx->waves > 0 ? ctx->waves : 4;
+    for (const JobBin& b : jl.bins) {
+        int64_t done = 0;
+        while (done < b.count) {  // grid dimension limit
+            const int64_t chunk = std::min<int64_t>(b.count - done, (int64_t)1 << 30);
+            hipError_t e = mgk_launch_small(waves, weighted, X->dev, Y->dev, jl.dev + b.first + done,
+                                            (int)chunk, prm, b.lds_bytes, K, iters, flags, stream);
+            if (e != hipSuccess)
+                return fail(ctx, MGK_EDEVICE, "kernel launch failed: %s", hipGetErrorString(e));
+            done += chunk;
+        }
+    }
+    return MGK_OK;
+}
+
+}  // namespace
+
+// ============================================================================
+extern "C" {
+
+mgk_status mgk_create(mgk_ctx** out, int device) {
+    if (!out) return MGK_EINVAL;
+    *out = nullptr;
+    if (device < -1) return MGK_EINVAL;
+    if (device >= 0) {
+        int count = 0;
+        if (hipGetDeviceCount(&count) != hipSuccess || device >= count) return MGK_EDEVICE;
+    }
+    mgk_ctx* ctx = new (std::nothrow) mgk_ctx();
+    if (!ctx) return MGK_ENOMEM;
+    ctx->device = device;
+    if (device >= 0 && hipSetDevice(device) != hipSuccess) { delete ctx; return MGK_EDEVICE; }
+    *out = ctx;
+    return MGK_OK;
+}
+
+void mgk_destroy(mgk_ctx* ctx) {
+    if (!ctx) return;
+    if (ctx->pair_jobs.dev) (void)hipFree(ctx->pair_jobs.dev);
+    delete ctx;
+}
+
+const char* mgk_last_error(const mgk_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+mgk_status mgk_set_vertex_kernel_delta(mgk_ctx* ctx, float h) {
+    if (!ctx) return MGK_EINVAL;
+    if (!(h > 0.f && h <= 1.f)) return fail(ctx, MGK_EINVAL, "vertex kernel h must be in (0, 1], got %g", h);
+    ctx->h = h;
+    return MGK_OK;
+}
+
+mgk_status mgk_set_edge_kernel_se(mgk_ctx* ctx, float length_scale) {
+    if (!ctx) return MGK_EINVAL;
+    if (!(length_scale > 0.f) || !std::isfinite(length_scale))
+        return fail(ctx, MGK_EINVAL, "length scale must be positive and finite, got %g", length_scale);
+    ctx->length_scale = length_scale;
+    ctx->edge_kernel = MGK_EK_SE;
+    return MGK_OK;
+}
+
+mgk_status mgk_set_edge_kernel_const(mgk_ctx* ctx, float c) {
+    if (!ctx) return MGK_EINVAL;
+    if (!(c >= 0.f && c <= 1.f)) return fail(ctx, MGK_EINVAL, "constant edge kernel must be in [0, 1], got %g", c);
+    ctx->ke_const = c;
+    ctx->edge_kernel = MGK_EK_CONST;
+    return MGK_OK;
+}
+
+mgk_status mgk_set_stop_prob(mgk_ctx* ctx, float q) {
+    if (!ctx) return MGK_EINVAL;
+    if (!(q > 0.f) || !std::isfinite(q)) return fail(ctx, MGK_EINVAL, "stopping probability must be > 0, got %g", q);
+    ctx->q = q;
+    return MGK_OK;
+}
+
+mgk_status mgk_set_solver(mgk_ctx* ctx, float rtol, int32_t max_iter) {
+    if (!ctx) return MGK_EINVAL;
+    if (!(rtol > 0.f) || !std::isfinite(rtol)) return fail(ctx, MGK_EINVAL, "rtol must be > 0, got %g", rtol);
+    ctx->rtol = rtol;
+    ctx->max_iter = max_iter;
+    return MGK_OK;
+}
+
+mgk_status mgk_set_tile_path(mgk_ctx* ctx, int32_t mode) {
+    if (!ctx) return MGK_EINVAL;
+    if (mode < MGK_TILE_AUTO || mode > MGK_TILE_DENSE) return fail(ctx, MGK_EINVAL, "unknown tile path %d", mode);
+    ctx->tile_path = mode;
+    return MGK_OK;
+}
+
+mgk_status mgk_set_launch(mgk_ctx* ctx, int32_t waves_per_pair) {
+    if (!ctx) return MGK_EINVAL;
+    const int w = waves_per_pair;
+    if (!(w == 0 || w == 1 || w == 2 || w == 4 || w == 8 || w == 16))
+        return fail(ctx, MGK_EINVAL, "waves_per_pair must be 0, 1, 2, 4, 8 or 16, got %d", w);
+    ctx->waves = w;
+    return MGK_OK;
+}
+
+// ----------------------------------------------------------------------------
+mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_off,
+                           const int32_t* vtx_label, const float* start_prob,
+                           const int64_t* edge_off, const int32_t* src, const int32_t* dst,
+                           const float* weight, const float* edge_label, int32_t reorder,
+                           mgk_batch** out) {
+    if (!ctx || !out) return MGK_EINVAL;
+    *out = nullptr;
+    if (n_graphs < 0 || !vtx_off || !edge_off) return fail(ctx, MGK_EINVAL, "null offsets or negative graph count");
+    if (reorder < MGK_REORDER_NONE || reorder > MGK_REORDER_RCM)
+        return fail(ctx, MGK_EINVAL, "unknown reorder mode %d", reorder);
+    if (vtx_off[0] != 0 || edge_off[0] != 0) return fail(ctx, MGK_EINVAL, "offset arrays must start at 0");
+    const int64_t tot_v = vtx_off[n_graphs], tot_e = edge_off[n_graphs];
+    if (tot_v > 0 && !vtx_label) return fail(ctx, MGK_EINVAL, "vtx_label is null");
+    if (tot_e > 0 && (!src || !dst)) return fail(ctx, MGK_EINVAL, "src/dst is null");
+    if (tot_v >= (int64_t)1 << 31 || 2 * tot_e >= (int64_t)1 << 31)
+        return fail(ctx, MGK_ELIMIT, "batch too large for 32-bit offsets");
+
+    mgk_batch* B = new (std::nothrow) mgk_batch();
+    if (!B) return fail(ctx, MGK_ENOMEM, "out of host memory");
+    struct Guard {
+        mgk_batch* b;
+        ~Guard() { if (b) { if (b->blob) (void)hipFree(b->blob); delete b; } }
+    } guard{B};
+
+    B->owner = ctx;
+    B->n_graphs = n_graphs;
+    B->graphs.resize(n_graphs);
+    B->vtx_off.assign(vtx_off, vtx_off + n_graphs + 1);
+    B->perm.resize((size_t)tot_v);
+    std::vector<int32_t> vlabel((size_t)tot_v), rowptr((size_t)tot_v), trow_ptr;
+    std::vector<float> rowsum((size_t)tot_v), start((size_t)tot_v);
+    B->w.reserve((size_t)(2 * tot_e));
+    B->e.reserve((size_t)(2 * tot_e));
+    double label_sum = 0.0;
+
+    struct Nz { uint64_t key; float w, e; };
+    std::vector<Nz> nz;
+    MgkAdj adj;
+    std::vector<int32_t> cursor;
+
+    for (int32_t g = 0; g < n_graphs; ++g) {
+        const int64_t v0 = vtx_off[g], v1 = vtx_off[g + 1], e0 = edge_off[g], e1 = edge_off[g + 1];
+        if (v1 <= v0) return fail(ctx, MGK_EINVAL, "graph %d has no vertices", g);
+        if (e1 < e0) return fail(ctx, MGK_EINVAL, "graph %d: edge offsets decrease", g);
+        const int64_t n64 = v1 - v0, m = e1 - e0;
+        if (n64 > 65535 * (int64_t)kTile) return fail(ctx, MGK_ELIMIT, "graph %d has too many vertices", g);
+        const int n = (int)n64;
+
+        // ---- validate edges, build adjacency (both directions)
+        adj.n = n;
+        adj.ptr.assign(n + 1, 0);
+        for (int64_t k = e0; k < e1; ++k) {
+            const int32_t s = src[k], d = dst[k];
+            if (s < 0 || s >= n || d < 0 || d >= n)
+                return fail(ctx, MGK_EINVAL, "graph %d edge %lld: endpoint out of range", g, (long long)(k - e0));
+            if (s == d) return fail(ctx, MGK_EINVAL, "graph %d edge %lld: self loop", g, (long long)(k - e0));
+            const float wv = weight ? weight[k] : 1.f;
+            if (!(wv > 0.f) || !std::isfinite(wv))
+                return fail(ctx, MGK_EINVAL, "graph %d edge %lld: weight must be finite and > 0", g, (long long)(k - e0));
+            if (edge_label && !std::isfinite(edge_label[k]))
+                return fail(ctx, MGK_EINVAL, "graph %d edge %lld: label is not finite", g, (long long)(k - e0));
+            adj.ptr[s + 1]++;
+            adj.ptr[d + 1]++;
+        }
+        for (int i = 0; i < n; ++i) adj.ptr[i + 1] += adj.ptr[i];
+        adj.idx.assign((size_t)(2 * m), 0);
+        cursor.assign(adj.ptr.begin(), adj.ptr.end() - 1);
+        for (int64_t k = e0; k < e1; ++k) {
+            adj.idx[cursor[src[k]]++] = dst[k];
+            adj.idx[cursor[dst[k]]++] = src[k];
+        }
+        for (int i = 0; i < n; ++i) {  // duplicate edges
+            std::sort(adj.idx.begin() + adj.ptr[i], adj.idx.begin() + adj.ptr[i + 1]);
+            if (std::adjacent_find(adj.idx.begin() + adj.ptr[i], adj.idx.begin() + adj.ptr[i + 1]) !=
+                adj.idx.begin() + adj.ptr[i + 1])
+                return fail(ctx, MGK_EINVAL, "graph %d: duplicate edge at vertex %d", g, i);
+        }
+        if (start_prob)
+            for (int i = 0; i < n; ++i)
+                if (!std::isfinite(start_prob[v0 + i]) || start_prob[v0 + i] < 0.f)
+                    return fail(ctx, MGK_EINVAL, "graph %d vertex %d: bad starting probability", g, i);
+
+        // ---- a2: vertex order
+        std::vector<int32_t> perm;
+        if (reorder == MGK_REORDER_PBR) perm = mgk_order_pbr(adj, kTile);
+        else if (reorder == MGK_REORDER_RCM) perm = mgk_order_rcm(adj);
+        else perm = mgk_order_identity(n);
+        std::copy(perm.begin(), perm.end(), B->perm.begin() + v0);
+
+        // ---- per-vertex data in stored order; a1: row sums for d_i = sum_j A_ij + q
+        std::vector<double> rs(n, 0.0);
+        for (int64_t k = e0; k < e1; ++k) {
+            const double wv = weight ? weight[k] : 1.0;
+            rs[perm[src[k]]] += wv;
+            rs[perm[dst[k]]] += wv;
+        }
+        for (int i = 0; i < n; ++i) {
+            const int ni = perm[i];
+            vlabel[v0 + ni] = vtx_label[v0 + i];
+            start[v0 + ni] = start_prob ? start_prob[v0 + i] : 1.0f / (float)n;
+            rowsum[v0 + ni] = (float)rs[ni];
+        }
+
+        // ---- a3: cut into octiles, drop empty ones, bitmap-pack
+        const int ntr = (n + kTile - 1) / kTile;
+        nz.clear();
+        nz.reserve((size_t)(2 * m));
+        for (int64_t k = e0; k < e1; ++k) {
+            const float wv = weight ? weight[k] : 1.f;
+            const float ev = edge_label ? edge_label[k] : 0.f;
+            if (wv != 1.f) B->weighted = true;
+            label_sum += 2.0 * ev;
+            const int a = perm[src[k]], b = perm[dst[k]];
+            for (int dir = 0; dir < 2; ++dir) {
+                const int i = dir ? b : a, j = dir ? a : b;
+                const uint64_t tile_id = (uint64_t)(i / kTile) * ntr + (uint64_t)(j / kTile);
+                nz.push_back({tile_id * 64 + (uint64_t)((i % kTile) * 8 + (j % kTile)), wv, ev});
+            }
+        }
+        std::sort(nz.begin(), nz.end(), [](const Nz& x, const Nz& y) { return x.key < y.key; });
+
+        MgkGraphDesc& gd = B->graphs[g];
+        gd.n = n;
+        gd.nnz = (int32_t)nz.size();
+        gd.n_tile_rows = ntr;
+        gd.voff = (int32_t)v0;
+        gd.zoff = (int32_t)B->w.size();
+        gd.toff = (int32_t)B->tiles.size();
+        gd.roff = (int32_t)trow_ptr.size();
+        std::vector<int32_t> deg(n, 0);
+        trow_ptr.resize(trow_ptr.size() + ntr + 1, 0);
+        int32_t* trp = trow_ptr.data() + gd.roff;
+        for (size_t k = 0; k < nz.size(); ++k) {
+            const uint64_t tile_id = nz[k].key >> 6;
+            const int bit = (int)(nz[k].key & 63);
+            const int tr = (int)(tile_id / ntr), tc = (int)(tile_id % ntr);
+            if (k == 0 || (nz[k - 1].key >> 6) != tile_id) {
+                MgkTile t;
+                t.tr = (uint16_t)tr;
+                t.tc = (uint16_t)tc;
+                t.nzoff = (uint32_t)k;
+                t.bitmap = 0;
+                B->tiles.push_back(t);
+                trp[tr + 1]++;
+                if (tr != tc) B->n_offdiag++;
+            }
+            B->tiles.back().bitmap |= 1ull << bit;
+            B->w.push_back(nz[k].w);
+            B->e.push_back(nz[k].e);
+            deg[tr * kTile + bit / 8]++;
+        }
+        for (int r = 0; r < ntr; ++r) trp[r + 1] += trp[r];
+        gd.n_tiles = (int32_t)B->tiles.size() - gd.toff;
+        int32_t run = 0;
+        for (int i = 0; i < n; ++i) { rowptr[v0 + i] = run; run += deg[i]; }
+    }
+    B->n_vertices = tot_v;
+    B->nnz = (int64_t)B->w.size();
+    B->n_tiles = (int64_t)B->tiles.size();
+    B->label_mean = B->nnz ? label_sum / (double)B->nnz : 0.0;
+
+    // ---- upload as one allocation
+    std::vector<char> blob;
+    const size_t o_g = append_bytes(blob, B->graphs);
+    const size_t o_t = append_bytes(blob, B->tiles);
+    const size_t o_w = append_bytes(blob, B->w);
+    const size_t o_e = append_bytes(blob, B->e);
+    const size_t o_vl = append_bytes(blob, vlabel);
+    const size_t o_rs = append_bytes(blob, rowsum);
+    const size_t o_st = append_bytes(blob, start);
+    const size_t o_rp = append_bytes(blob, rowptr);
+    const size_t o_tr = append_bytes(blob, trow_ptr);
+    if (ctx->device < 0) {  // host-only context: packed form is kept for inspection only
+        guard.b = nullptr;
+        *out = B;
+        return MGK_OK;
+    }
+    MGK_HIP(ctx, hipSetDevice(ctx->device));
+    MGK_HIP(ctx, hipMalloc(&B->blob, blob.size()));
+    MGK_HIP(ctx, hipMemcpy(B->blob, blob.data(), blob.size(), hipMemcpyHostToDevice));
+    char* base = static_cast<char*>(B->blob);
+    B->dev.graphs = reinterpret_cast<const MgkGraphDesc*>(base + o_g);
+    B->dev.tiles = reinterpret_cast<const MgkTile*>(base + o_t);
+    B->dev.w = reinterpret_cast<const float*>(base + o_w);
+    B->dev.e = reinterpret_cast<const float*>(base + o_e);
+    B->dev.vlabel = reinterpret_cast<const int32_t*>(base + o_vl);
+    B->dev.rowsum = reinterpret_cast<const float*>(base + o_rs);
+    B->dev.start = reinterpret_cast<const float*>(base + o_st);
+    B->dev.rowptr = reinterpret_cast<const int32_t*>(base + o_rp);
+    B->dev.trow_ptr = reinterpret_cast<const int32_t*>(base + o_tr);
+
+    guard.b = nullptr;
+    *out = B;
+    return MGK_OK;
+}
+
+void mgk_free_batch(mgk_ctx* ctx, mgk_batch* batch) {
+    if (!batch) return;
+    (void)ctx;
+    if (batch->blob || batch->gram_jobs.dev) (void)hipDeviceSynchronize();
+    if (batch->gram_jobs.dev) (void)hipFree(batch->gram_jobs.dev);
+    if (batch->blob) (void)hipFree(batch->blob);
+    delete batch;
+}
+
+mgk_status mgk_batch_stats(const mgk_batch* b, int64_t* n_graphs, int64_t* n_vertices, int64_t* nnz,
+                           int64_t* n_tiles, int64_t* n_offdiag_tiles) {
+    if (!b) return MGK_EINVAL;
+    if (n_graphs) *n_graphs = b->n_graphs;
+    if (n_vertices) *n_vertices = b->n_vertices;
+    if (nnz) *nnz = b->nnz;
+    if (n_tiles) *n_tiles = b->n_tiles;
+    if (n_offdiag_tiles) *n_offdiag_tiles = b->n_offdiag;
+    return MGK_OK;
+}
+
+mgk_status mgk_batch_permutation(const mgk_batch* b, int32_t* perm_host) {
+    if (!b || !perm_host) return MGK_EINVAL;
+    std::copy(b->perm.begin(), b->perm.end(), perm_host);
+    return MGK_OK;
+}
+
+mgk_status mgk_batch_get_tiles(const mgk_batch* b, int32_t g, int32_t* n_tiles, int32_t* nnz,
+                               int32_t* tile_row, int32_t* tile_col, uint64_t* bitmap, float* w,
+                               float* e) {
+    if (!b || g < 0 || g >= b->n_graphs) return MGK_EINVAL;
+    const MgkGraphDesc& gd = b->graphs[g];
+    if (n_tiles) *n_tiles = gd.n_tiles;
+    if (nnz) *nnz = gd.nnz;
+    for (int t = 0; t < gd.n_tiles; ++t) {
+        const MgkTile& tl = b->tiles[gd.toff + t];
+        if (tile_row) tile_row[t] = tl.tr;
+        if (tile_col) tile_col[t] = tl.tc;
+        if (bitmap) bitmap[t] = tl.bitmap;
+    }
+    if (w) std::copy(b->w.begin() + gd.zoff, b->w.begin() + gd.zoff + gd.nnz, w);
+    if (e) std::copy(b->e.begin() + gd.zoff, b->e.begin() + gd.zoff + gd.nnz, e);
+    return MGK_OK;
+}
+
+// ----------------------------------------------------------------------------
+mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters_dev,
+                    int32_t* flag_dev, void* stream_) {
+    if (!ctx || !batch || !K_dev) return fail(ctx, MGK_EINVAL, "null argument");
+    if (batch->owner != ctx) return fail(ctx, MGK_ESTATE, "batch belongs to another context");
+    if (ctx->device < 0) return fail(ctx, MGK_ESTATE, "host-only context cannot solve");
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    MGK_HIP(ctx, hipSetDevice(ctx->device));
+    const int64_t G = batch->n_graphs;
+    if (G * G >= (int64_t)1 << 31) return fail(ctx, MGK_ELIMIT, "Gram matrix too large for 32-bit output indices");
+    if (batch->gram_jobs.dev == nullptr && G > 0) {
+        // a4: job list, one job per unordered pair, kept with the batch
+        std::vector<HostJob> jobs;
+        jobs.reserve((size_t)(G * (G + 1) / 2));
+        for (int64_t i = 0; i < G; ++i)
+            for (int64_t j = i; j < G; ++j) {
+                const PairPlan pl = plan_pair(batch->graphs[i], batch->graphs[j], true);
+                HostJob hj;
+                hj.job.g1 = (int32_t)(pl.swap ? j : i);
+                hj.job.g2 = (int32_t)(pl.swap ? i : j);
+                hj.job.out0 = (int32_t)(i * G + j);
+                hj.job.out1 = i == j ? -1 : (int32_t)(j * G + i);
+                hj.cost = pl.cost;
+                hj.cls = lds_class(pl.lds_words);
+                if (hj.cls < 0)
+                    return fail(ctx, MGK_ELIMIT, "pair (%lld, %lld) needs %lld bytes of LDS; the on-chip solver holds %d",
+                                (long long)i, (long long)j, (long long)pl.lds_words * 4, MGK_LDS_LIMIT_BYTES);
+                jobs.push_back(hj);
+            }
+        mgk_status st = build_job_list(ctx, batch, batch, jobs, batch->gram_jobs, stream, nullptr);
+        if (st != MGK_OK) return st;
+    }
+    return launch_jobs(ctx, batch, batch, batch->gram_jobs, K_dev, iters_dev, flag_dev, stream);
+}
+
+mgk_status mgk_pairs(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
+                     const int32_t* i_host, const int32_t* j_host, float* K_dev, int32_t* iters_dev,
+                     int32_t* flag_dev, void* stream_) {
+    if (!ctx || !X || !Y) return fail(ctx, MGK_EINVAL, "null argument");
+    if (X->owner != ctx || Y->owner != ctx) return fail(ctx, MGK_ESTATE, "batch belongs to another context");
+    if (ctx->device < 0) return fail(ctx, MGK_ESTATE, "host-only context cannot solve");
+    if (n_pairs < 0 || n_pairs >= (int64_t)1 << 31) return fail(ctx, MGK_EINVAL, "bad pair count");
+    if (n_pairs == 0) return MGK_OK;
+    if (!i_host || !j_host || !K_dev) return fail(ctx, MGK_EINVAL, "null argument");
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    MGK_HIP(ctx, hipSetDevice(ctx->device));
+    // Batches of one orientation only: outer graph from X, inner from Y, unless
+    // X and Y are the same batch (then the cheaper orientation is chosen).
+    const bool may_swap = X == Y;
+    std::vector<HostJob> jobs((size_t)n_pairs);
+    for (int64_t k = 0; k < n_pairs; ++k) {
+        const int32_t i = i_host[k], j = j_host[k];
+        if (i < 0 || i >= X->n_graphs || j < 0 || j >= Y->n_graphs)
+            return fail(ctx, MGK_EINVAL, "pair %lld: graph index out of range", (long long)k);
+        const PairPlan pl = plan_pair(X->graphs[i], Y->graphs[j], may_swap);
+        HostJob& hj = jobs[(size_t)k];
+        hj.job.g1 = pl.swap ? j : i;
+        hj.job.g2 = pl.swap ? i : j;
+        hj.job.out0 = (int32_t)k;
+        hj.job.out1 = -1;
+        hj.cost = pl.cost;
+        hj.cls = lds_class(pl.lds_words);
+        if (hj.cls < 0)
+            return fail(ctx, MGK_ELIMIT, "pair %lld needs %lld bytes of LDS; the on-chip solver holds %d",
+                        (long long)k, (long long)pl.lds_words * 4, MGK_LDS_LIMIT_BYTES);
+    }
+    if (ctx->pair_jobs_busy) {  // the previous call's kernels may still read the job buffer
+        MGK_HIP(ctx, hipStreamSynchronize(ctx->pair_jobs_stream));
+        ctx->pair_jobs_busy = false;
+    }
+    mgk_status st = build_job_list(ctx, X, Y, jobs, ctx->pair_jobs, stream, &ctx->pair_jobs_cap);
+    if (st != MGK_OK) return st;
+    ctx->pair_jobs_stream = stream;
+    ctx->pair_jobs_busy = true;
+    return launch_jobs(ctx, X, Y, ctx->pair_jobs, K_dev, iters_dev, flag_dev, stream);
+}
+
+}  // extern "C"

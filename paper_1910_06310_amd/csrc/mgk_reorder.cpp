@@ -1,0 +1,359 @@
+// Vertex orderings for tile packing (Section IV-A).  Host only, no GPU code.
+//
+// The partition-based reordering follows the goal stated with Eq. 3: a
+// perfectly balanced K = ceil(n/t)-way partition with as few connected part
+// pairs as possible.  The paper obtains it from an external recursive
+// hypergraph bipartitioner; this is an independent heuristic with the same
+// objective: recursive bisection (greedy growing + exact-balance swap
+// refinement on the edge cut) followed by a K-way swap refinement that
+// evaluates Eq. 3 directly, with the edge cut as tie-break.  Any permutation
+// gives the same kernel values; only the tile count depends on it.
+#include "mgk_reorder.h"
+
+#include <algorithm>
+#include <numeric>
+#include <queue>
+#include <unordered_map>
+
+std::vector<int32_t> mgk_order_identity(int n) {
+    std::vector<int32_t> p(n);
+    std::iota(p.begin(), p.end(), 0);
+    return p;
+}
+
+// ---------------------------------------------------------------- RCM
+namespace {
+
+// BFS levels inside the vertex subset marked by in_set == tag; returns the
+// last vertex reached (an end of a long shortest path) and fills `order`.
+int bfs_far(const MgkAdj& g, int start, const std::vector<int>& in_set, int tag,
+            std::vector<int>& dist, std::vector<int32_t>& order) {
+    order.clear();
+    order.push_back(start);
+    dist[start] = 0;
+    for (size_t h = 0; h < order.size(); ++h) {
+        int v = order[h];
+        for (int k = g.ptr[v]; k < g.ptr[v + 1]; ++k) {
+            int w = g.idx[k];
+            if (in_set[w] == tag && dist[w] < 0) {
+                dist[w] = dist[v] + 1;
+                order.push_back(w);
+            }
+        }
+    }
+    int far = order.back();
+    for (int v : order) dist[v] = -1;
+    return far;
+}
+
+}  // namespace
+
+std::vector<int32_t> mgk_order_rcm(const MgkAdj& g) {
+    const int n = g.n;
+    std::vector<int32_t> seq;
+    seq.reserve(n);
+    std::vector<int> in_set(n, 0), dist(n, -1);
+    std::vector<char> done(n, 0);
+    std::vector<int32_t> tmp, nb;
+    auto deg = [&](int v) { return g.ptr[v + 1] - g.ptr[v]; };
+    for (int s0 = 0; s0 < n; ++s0) {
+        if (done[s0]) continue;
+        // pseudo-peripheral start: two sweeps
+        int s = bfs_far(g, s0, in_set, 0, dist, tmp);
+        s = bfs_far(g, s, in_set, 0, dist, tmp);
+        size_t head = seq.size();
+        seq.push_back(s);
+        done[s] = 1;
+        in_set[s] = 1;
+        for (; head < seq.size(); ++head) {
+            int v = seq[head];
+            nb.clear();
+            for (int k = g.ptr[v]; k < g.ptr[v + 1]; ++k)
+                if (!done[g.idx[k]]) { nb.push_back(g.idx[k]); done[g.idx[k]] = 1; in_set[g.idx[k]] = 1; }
+            std::sort(nb.begin(), nb.end(), [&](int a, int b) {
+                return deg(a) != deg(b) ? deg(a) < deg(b) : a < b;
+            });
+            for (int w : nb) seq.push_back(w);
+        }
+    }
+    std::vector<int32_t> perm(n);
+    for (int k = 0; k < n; ++k) perm[seq[k]] = n - 1 - k;
+    return perm;
+}
+
+// ---------------------------------------------------------------- PBR
+namespace {
+
+struct Bisector {
+    const MgkAdj& g;
+    int t;
+    std::vector<int32_t> part;   // result: part id per vertex
+    std::vector<int> mark;       // scratch: subset tag per vertex
+    std::vector<int> side;       // 0 / 1 inside the current subset
+    std::vector<int> gain;
+    std::vector<char> locked;
+    std::vector<int> dist;
+    std::vector<int32_t> tmp;
+    int tag_counter = 0;
+
+    Bisector(const MgkAdj& g_, int t_)
+        : g(g_), t(t_), part(g_.n, 0), mark(g_.n, 0), side(g_.n, 0), gain(g_.n, 0),
+          locked(g_.n, 0), dist(g_.n, -1) {}
+
+    void run() {
+        std::vector<int32_t> all(g.n);
+        std::iota(all.begin(), all.end(), 0);
+        split(all, 0, (g.n + t - 1) / t);
+    }
+
+    void split(std::vector<int32_t>& V, int first_part, int nparts) {
+        if (nparts <= 1) {
+            for (int v : V) part[v] = first_part;
+            return;
+        }
+        const int kl = (nparts + 1) / 2;
+        const int size_l = kl * t;
+        const int tag = ++tag_counter;
+        for (int v : V) { mark[v] = tag; side[v] = 1; }
+
+        // ---- greedy growing of side 0 from a far-apart vertex
+        int start = V[0];
+        for (int v : V)
+            if (g.ptr[v + 1] - g.ptr[v] < g.ptr[start + 1] - g.ptr[start]) start = v;
+        start = bfs_far(g, start, mark, tag, dist, tmp);
+        // conn[v] = edges from v into side 0 (only for side-1 vertices of the subset)
+        for (int v : V) gain[v] = 0;
+        int grown = 0;
+        auto add_to_left = [&](int v) {
+            side[v] = 0;
+            ++grown;
+            for (int k = g.ptr[v]; k < g.ptr[v + 1]; ++k) {
+                int w = g.idx[k];
+                if (mark[w] == tag) ++gain[w];
+            }
+        };
+        add_to_left(start);
+        while (grown < size_l) {
+            int best = -1, best_key = 0;
+            for (int v : V) {
+                if (side[v] == 0) continue;
+                // prefer vertices mostly attached to the grown side; among
+                // unattached ones (new component) prefer low degree
+                int in_sub = 0;
+                for (int k = g.ptr[v]; k < g.ptr[v + 1]; ++k) in_sub += mark[g.idx[k]] == tag;
+                int key = gain[v] > 0 ? 1000000 + 2 * gain[v] - in_sub : -in_sub;
+                if (best < 0 || key > best_key) { best = v; best_key = key; }
+            }
+            add_to_left(best);
+        }
+
+        refine_bisection(V, tag);
+
+        std::vector<int32_t> L, R;
+        L.reserve(size_l);
+        R.reserve(V.size() - size_l);
+        for (int v : V) (side[v] == 0 ? L : R).push_back(v);
+        V.clear();
+        V.shrink_to_fit();
+        split(L, first_part, kl);
+        split(R, first_part + kl, nparts - kl);
+    }
+
+    // Kernighan-Lin style passes of pairwise swaps (sizes stay exact),
+    // minimising the number of cut edges inside the subset.
+    void refine_bisection(const std::vector<int32_t>& V, int tag) {
+        const int max_pass = 6;
+        for (int pass = 0; pass < max_pass; ++pass) {
+            for (int v : V) {
+                int ext = 0, in = 0;
+                for (int k = g.ptr[v]; k < g.ptr[v + 1]; ++k) {
+                    int w = g.idx[k];
+                    if (mark[w] != tag) continue;
+                    (side[w] == side[v] ? in : ext)++;
+                }
+                gain[v] = ext - in;
+                locked[v] = 0;
+            }
+            std::vector<std::pair<int, int>> swaps;
+            int cum = 0, best_cum = 0;
+            size_t best_len = 0;
+            const size_t max_swaps = std::min<size_t>(V.size() / 2, 64 + V.size() / 8);
+            for (size_t s = 0; s < max_swaps; ++s) {
+                // best unlocked vertex on each side, then correct for a shared edge
+                int a = -1, b = -1;
+                for (int v : V) {
+                    if (locked[v]) continue;
+                    if (side[v] == 0) { if (a < 0 || gain[v] > gain[a]) a = v; }
+                    else { if (b < 0 || gain[v] > gain[b]) b = v; }
+                }
+                if (a < 0 || b < 0) break;
+                // look for a better partner among the top candidates of side 1
+                int best_b = b, best_g = -1000000;
+                for (int v : V) {
+                    if (locked[v] || side[v] != 1 || gain[v] < gain[b] - 2) continue;
+                    int adj = 0;
+                    for (int k = g.ptr[a]; k < g.ptr[a + 1]; ++k) adj += g.idx[k] == v;
+                    int gsum = gain[a] + gain[v] - 2 * adj;
+                    if (gsum > best_g) { best_g = gsum; best_b = v; }
+                }
+                b = best_b;
+                if (best_g < -4 && cum <= best_cum) break;  // hopeless tail
+                // apply swap
+                for (int pass_v = 0; pass_v < 2; ++pass_v) {
+                    int v = pass_v ? b : a;
+                    for (int k = g.ptr[v]; k < g.ptr[v + 1]; ++k) {
+                        int w = g.idx[k];
+                        if (mark[w] != tag || w == a || w == b) continue;
+                        gain[w] += (side[w] == side[v]) ? 2 : -2;
+                    }
+                }
+                side[a] = 1; side[b] = 0;
+                locked[a] = locked[b] = 1;
+                cum += best_g;
+                swaps.emplace_back(a, b);
+                if (cum > best_cum) { best_cum = cum; best_len = swaps.size(); }
+            }
+            for (size_t s = swaps.size(); s > best_len; --s) {
+                side[swaps[s - 1].first] = 0;
+                side[swaps[s - 1].second] = 1;
+            }
+            if (best_cum <= 0) break;
+        }
+    }
+};
+
+// Edge counts between parts: dense for moderate K, hashed otherwise.
+struct PairCounts {
+    int K;
+    bool dense;
+    std::vector<int32_t> d;
+    std::unordered_map<uint64_t, int32_t> h;
+    explicit PairCounts(int K_) : K(K_), dense(K_ <= 1024) {
+        if (dense) d.assign((size_t)K * K, 0);
+    }
+    static uint64_t key(int a, int b) {
+        if (a > b) std::swap(a, b);
+        return ((uint64_t)(uint32_t)a << 32) | (uint32_t)b;
+    }
+    int get(int a, int b) const {
+        if (dense) return d[(size_t)std::min(a, b) * K + std::max(a, b)];
+        auto it = h.find(key(a, b));
+        return it == h.end() ? 0 : it->second;
+    }
+    void add(int a, int b, int delta) {
+        if (dense) d[(size_t)std::min(a, b) * K + std::max(a, b)] += delta;
+        else h[key(a, b)] += delta;
+    }
+};
+
+// K-way refinement on the objective of Eq. 3: swap two vertices of different
+// parts when that lowers the number of connected part pairs (ties: fewer cut
+// edges).  Part sizes never change.
+void kway_refine(const MgkAdj& g, std::vector<int32_t>& part, int K, int max_pass) {
+    if (K < 2) return;
+    PairCounts C(K);
+    for (int v = 0; v < g.n; ++v)
+        for (int k = g.ptr[v]; k < g.ptr[v + 1]; ++k) {
+            int w = g.idx[k];
+            if (v < w) C.add(part[v], part[w], 1);
+        }
+    std::vector<std::vector<int32_t>> members(K);
+    for (int v = 0; v < g.n; ++v) members[part[v]].push_back(v);
+
+    struct Delta { int a, b, d; };
+    std::vector<Delta> touched;
+    auto bump = [&](int a, int b, int d) {
+        if (a > b) std::swap(a, b);
+        for (auto& t : touched)
+            if (t.a == a && t.b == b) { t.d += d; return; }
+        touched.push_back({a, b, d});
+    };
+    // change of (connected pairs, cut edges) if v (part A) and u (part B) trade places
+    auto eval_swap = [&](int v, int u, int& dpairs, int& dcut) {
+        const int A = part[v], B = part[u];
+        touched.clear();
+        for (int k = g.ptr[v]; k < g.ptr[v + 1]; ++k) {
+            int w = g.idx[k];
+            if (w == u) continue;
+            bump(A, part[w], -1);
+            bump(B, part[w], +1);
+        }
+        for (int k = g.ptr[u]; k < g.ptr[u + 1]; ++k) {
+            int w = g.idx[k];
+            if (w == v) continue;
+            bump(B, part[w], -1);
+            bump(A, part[w], +1);
+        }
+        dpairs = 0; dcut = 0;
+        for (auto& t : touched) {
+            if (t.a == t.b || t.d == 0) continue;
+            int c = C.get(t.a, t.b);
+            dpairs += ((c + t.d) > 0) - (c > 0);
+            dcut += t.d;
+        }
+    };
+    auto apply_swap = [&](int v, int u) {
+        const int A = part[v], B = part[u];
+        int dp, dc;
+        eval_swap(v, u, dp, dc);
+        for (auto& t : touched) if (t.d) C.add(t.a, t.b, t.d);
+        part[v] = B; part[u] = A;
+        std::replace(members[A].begin(), members[A].end(), v, u);
+        std::replace(members[B].begin(), members[B].end(), u, v);
+    };
+
+    std::vector<int> cand_parts;
+    for (int pass = 0; pass < max_pass; ++pass) {
+        bool improved = false;
+        for (int v = 0; v < g.n; ++v) {
+            const int A = part[v];
+            cand_parts.clear();
+            for (int k = g.ptr[v]; k < g.ptr[v + 1]; ++k) {
+                int P = part[g.idx[k]];
+                if (P != A && std::find(cand_parts.begin(), cand_parts.end(), P) == cand_parts.end())
+                    cand_parts.push_back(P);
+            }
+            if (cand_parts.empty()) continue;
+            int best_u = -1, best_dp = 0, best_dc = 0;
+            for (int B : cand_parts)
+                for (int u : members[B]) {
+                    int dp, dc;
+                    eval_swap(v, u, dp, dc);
+                    if (dp < best_dp || (dp == best_dp && dc < best_dc)) {
+                        best_dp = dp; best_dc = dc; best_u = u;
+                    }
+                }
+            if (best_u >= 0) {
+                apply_swap(v, best_u);
+                improved = true;
+            }
+        }
+        if (!improved) break;
+    }
+}
+
+}  // namespace
+
+std::vector<int32_t> mgk_order_pbr(const MgkAdj& g, int t) {
+    const int n = g.n;
+    const int K = (n + t - 1) / t;
+    if (K <= 1) return mgk_order_identity(n);
+    Bisector bis(g, t);
+    bis.run();
+    kway_refine(g, bis.part, K, 8);
+    // new id = part * t + rank inside the part (by original id)
+    std::vector<int32_t> perm(n), fill(K, 0);
+    for (int v = 0; v < n; ++v) perm[v] = bis.part[v] * t + fill[bis.part[v]]++;
+    return perm;
+}
+
+int64_t mgk_count_offdiag_tiles(const MgkAdj& g, const std::vector<int32_t>& perm, int t) {
+    std::vector<uint64_t> keys;
+    for (int v = 0; v < g.n; ++v)
+        for (int k = g.ptr[v]; k < g.ptr[v + 1]; ++k) {
+            int a = perm[v] / t, b = perm[g.idx[k]] / t;
+            if (a != b) keys.push_back(((uint64_t)(uint32_t)a << 32) | (uint32_t)b);
+        }
+    std::sort(keys.begin(), keys.end());
+    return (int64_t)(std::unique(keys.begin(), keys.end()) - keys.begin());
+}

@@ -1,0 +1,206 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle.
+
+Tolerance: |K_gpu - K_oracle| <= 1e-4 |K_oracle| per pair (fp32 arithmetic on
+the device, PCG stopped at a relative residual of 1e-6)."""
+import numpy as np
+import pytest
+
+import mgk_workloads as W
+import paper_1910_06310_amd as M
+from oracle import c_oracle as C
+from oracle import mgk_oracle as O
+
+pytestmark = pytest.mark.gpu
+RTOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    return torch
+
+
+@pytest.fixture(scope="module")
+def solver(torch):
+    return M.Solver(0)
+
+
+def run_gram(torch, solver, wb, reorder=M.REORDER_PBR):
+    solver.configure(wb.params)
+    B = solver.load_batch(wb, reorder=reorder)
+    G = wb.n_graphs
+    K = torch.full((G, G), float("nan"), dtype=torch.float32, device="cuda")
+    it = torch.zeros((G, G), dtype=torch.int32, device="cuda")
+    fl = torch.full((G, G), -1, dtype=torch.int32, device="cuda")
+    solver.gram(B, K, it, fl)
+    torch.cuda.synchronize()
+    return K.cpu().numpy().astype(np.float64), it.cpu().numpy(), fl.cpu().numpy()
+
+
+def run_pairs(torch, solver, BX, BY, pi, pj):
+    n = len(pi)
+    K = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+    it = torch.zeros((n,), dtype=torch.int32, device="cuda")
+    fl = torch.full((n,), -1, dtype=torch.int32, device="cuda")
+    solver.pairs(BX, BY, pi, pj, K, it, fl)
+    torch.cuda.synchronize()
+    return K.cpu().numpy().astype(np.float64), it.cpu().numpy(), fl.cpu().numpy()
+
+
+def test_config0_full_gram(torch, solver):
+    wb = W.config0()
+    solver.set_solver(1e-6, 0)
+    solver.set_launch(0)
+    K, it, fl = run_gram(torch, solver, wb)
+    pi, pj = W.gram_pairs(4)
+    ref = np.zeros((4, 4))
+    ref[pi, pj] = ref[pj, pi] = O.gram_values(wb, pi, pj)
+    np.testing.assert_allclose(K, ref, rtol=RTOL)
+    assert (K == K.T).all()
+    assert (fl == 0).all() and (it > 0).all()
+
+
+@pytest.mark.parametrize("waves", [1, 2, 4, 8, 16])
+def test_config1_full_gram_all_workgroup_sizes(torch, solver, waves):
+    wb = W.config1()
+    solver.set_solver(1e-6, 0)
+    solver.set_launch(waves)
+    K, it, fl = run_gram(torch, solver, wb)
+    solver.set_launch(0)
+    pi, pj = W.gram_pairs(100)
+    ref = C.pairs(wb, pi, pj, tier=1)
+    err = np.abs(K[pi, pj] - ref) / ref
+    assert err.max() <= RTOL, (err.max(), int(err.argmax()))
+    assert (K == K.T).all() and (fl == 0).all()
+    ev = np.linalg.eigvalsh(K)
+    assert ev.min() >= -1e-5 * ev.max()
+    if waves == 4:  # dense tier on a sample as well
+        sel = np.random.default_rng(0).choice(len(pi), 300, replace=False)
+        ref0 = C.pairs(wb, pi[sel], pj[sel], tier=0)
+        np.testing.assert_allclose(K[pi[sel], pj[sel]], ref0, rtol=RTOL)
+
+
+@pytest.mark.parametrize("reorder", [M.REORDER_NONE, M.REORDER_RCM, M.REORDER_PBR])
+def test_reordering_does_not_change_values(torch, solver, reorder):
+    wb = W.permute_vertices(W.config1(24), np.random.default_rng(3))
+    solver.set_solver(1e-6, 0)
+    K, _, fl = run_gram(torch, solver, wb, reorder=reorder)
+    pi, pj = W.gram_pairs(24)
+    ref = C.pairs(wb, pi, pj, tier=0)
+    np.testing.assert_allclose(K[pi, pj], ref, rtol=RTOL)
+    assert (fl == 0).all()
+
+
+def _graph_batch(graphs, params):
+    from mgk_workloads.generators import _assemble
+    return _assemble(graphs, params, "adhoc")
+
+
+def test_closed_forms_on_device(torch, solver):
+    prm = W.KernelParams(q=0.05, h=0.5, length_scale=1.0)
+    e = np.zeros(0)
+    tri = (3, [0, 0, 0], [0, 0, 1], [1, 2, 2], np.ones(3), np.ones(3))
+    single_a = (1, [0], [], [], e, e)
+    single_b = (1, [1], [], [], e, e)
+    edgeless3 = (3, [0, 1, 1], [], [], e, e)
+    edgeless2 = (2, [0, 1], [], [], e, e)
+    wb = _graph_batch([tri, single_a, single_b, edgeless3, edgeless2], prm)
+    solver.set_solver(1e-6, 0)
+    K, it, fl = run_gram(torch, solver, wb)
+    assert K[0, 0] == pytest.approx(1681.0 / 32400.0, rel=RTOL)     # two triangles, all kappa = 1
+    assert K[1, 1] == pytest.approx(0.0025, rel=1e-6)
+    assert K[1, 2] == pytest.approx(0.00125, rel=1e-6)
+    assert K[3, 4] == pytest.approx(0.001875, rel=1e-6)
+    assert (fl == 0).all()
+
+
+def test_weighted_graphs_and_separate_batches(torch, solver):
+    rng = np.random.default_rng(5)
+    prm = W.KernelParams(q=0.05, h=0.4, length_scale=0.7)
+    X = W.erdos_renyi_batch(rng, 6, 5, 30, 0.3, (0.2, 2.0), (0.0, 2.0), 3, prm)
+    Y = W.erdos_renyi_batch(rng, 5, 9, 70, 0.1, (0.2, 2.0), (0.0, 2.0), 3, prm)
+    both = W.concat_batches([X, Y], prm)
+    solver.configure(prm)
+    solver.set_solver(1e-6, 0)
+    BX = solver.load_batch(X)
+    BY = solver.load_batch(Y, reorder=M.REORDER_RCM)
+    pi = np.repeat(np.arange(6), 5).astype(np.int32)
+    pj = np.tile(np.arange(5), 6).astype(np.int32)
+    K, it, fl = run_pairs(torch, solver, BX, BY, pi, pj)
+    ref = C.pairs(both, pi, pj + 6, tier=0)
+    np.testing.assert_allclose(K, ref, rtol=RTOL)
+    assert (fl == 0).all()
+    # same batch on both sides, arbitrary (ordered) pair list incl. repeats
+    pi2 = np.array([0, 3, 3, 5, 2], np.int32); pj2 = np.array([5, 3, 1, 0, 2], np.int32)
+    K2, _, _ = run_pairs(torch, solver, BX, BX, pi2, pj2)
+    np.testing.assert_allclose(K2, C.pairs(X, pi2, pj2, tier=0), rtol=RTOL)
+    assert K2[0] == K2[3]
+
+
+def test_unlabeled_random_walk_kernel(torch, solver):
+    # h = 1 and a constant edge kernel of 1 give Eq. 2
+    wb = W.config1(12)
+    solver.set_stop_prob(0.05)
+    solver.set_vertex_kernel_delta(1.0)
+    solver.set_edge_kernel_const(1.0)
+    solver.set_solver(1e-6, 0)
+    B = solver.load_batch(wb)
+    pi, pj = W.gram_pairs(12)
+    K, it, fl = run_pairs(torch, solver, B, B, pi, pj)
+    wb.params = W.KernelParams(q=0.05, h=1.0, length_scale=1e9)
+    np.testing.assert_allclose(K, C.pairs(wb, pi, pj, tier=0), rtol=RTOL)
+    # constant kernel 0.5 on weighted graphs: same as labels e, e' at a fixed distance
+    rng = np.random.default_rng(8)
+    prm = W.KernelParams(q=0.1, h=0.6, length_scale=1.0)
+    wb2 = W.erdos_renyi_batch(rng, 4, 6, 20, 0.4, (0.3, 1.5), (0.0, 0.0), 2, prm)
+    solver.set_stop_prob(0.1); solver.set_vertex_kernel_delta(0.6); solver.set_edge_kernel_const(1.0)
+    B2 = solver.load_batch(wb2)
+    pi, pj = W.gram_pairs(4)
+    K2, _, _ = run_pairs(torch, solver, B2, B2, pi, pj)
+    np.testing.assert_allclose(K2, C.pairs(wb2, pi, pj, tier=0), rtol=RTOL)  # all labels 0 -> kappa_e = 1
+
+
+def test_iteration_cap_sets_flag(torch, solver):
+    wb = W.config1(8)
+    solver.configure(wb.params)
+    solver.set_solver(1e-6, 1)
+    B = solver.load_batch(wb)
+    pi, pj = W.gram_pairs(8)
+    K, it, fl = run_pairs(torch, solver, B, B, pi, pj)
+    assert (it == 1).all() and (fl == 1).all() and np.isfinite(K).all()
+    solver.set_solver(1e-6, 0)
+
+
+def test_start_probabilities(torch, solver):
+    wb = W.config1(6)
+    rng = np.random.default_rng(2)
+    sp = rng.random(int(wb.vtx_off[-1])).astype(np.float32)
+    for g in range(6):
+        sl = slice(int(wb.vtx_off[g]), int(wb.vtx_off[g + 1]))
+        sp[sl] /= sp[sl].sum()
+    solver.configure(wb.params)
+    solver.set_solver(1e-6, 0)
+    B = solver.load_batch(wb, start_prob=sp)
+    pi, pj = W.gram_pairs(6)
+    K, _, _ = run_pairs(torch, solver, B, B, pi, pj)
+    ref = C.pairs(wb, pi, pj, tier=0, start_prob=sp.astype(np.float64))
+    np.testing.assert_allclose(K, ref, rtol=RTOL)
+
+
+def test_config4_full_size_sampled(torch, solver):
+    """The 2000-graph Gram in the launch configuration the benchmark times:
+    sampled pairs against the oracle, plus properties of the whole matrix."""
+    wb = W.config4()
+    solver.set_solver(1e-6, 0)
+    solver.set_launch(0)
+    K, it, fl = run_gram(torch, solver, wb)
+    assert np.isfinite(K).all() and (fl == 0).all() and (it > 0).all()
+    assert (K == K.T).all()
+    pi, pj = W.gram_pairs(2000)
+    sel = np.random.default_rng(4).choice(len(pi), 400, replace=False)
+    ref = C.pairs(wb, pi[sel], pj[sel], tier=1)
+    np.testing.assert_allclose(K[pi[sel], pj[sel]], ref, rtol=RTOL)
+    ev = np.linalg.eigvalsh(K)
+    assert ev.min() >= -1e-5 * ev.max()
+    dg = np.diag(K)
+    assert (K * K <= np.outer(dg, dg) * (1 + 1e-4)).all()
