@@ -80,7 +80,9 @@ mgk_status mgk_set_solver(mgk_ctx* ctx, float rtol, int32_t max_iter);
 /* Force the sparse or the dense tile-pair primitive, or choose per tile pair. */
 mgk_status mgk_set_tile_path(mgk_ctx* ctx, int32_t mode);
 /* Tuning knobs, safe to leave alone.  waves_per_pair: wavefronts of the
- * workgroup that solves one on-chip pair (1, 2, 4, 8 or 16; 0 = automatic). */
+ * workgroup that solves one on-chip pair (1, 2, 4, 8 or 16; 0 = automatic by
+ * product size).  A pair too large for the requested size gets the next
+ * larger one that fits. */
 mgk_status mgk_set_launch(mgk_ctx* ctx, int32_t waves_per_pair);
 
 /* ---- graphs -----------------------------------------------------------------

@@ -8,13 +8,16 @@ from __future__ import annotations
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmgk.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-DEVICE_SOURCES = ["mgk_small.hip"]
+# (source, output tag, extra flags); the on-chip solver is compiled once per
+# workgroup size so the translation units build in parallel
+DEVICE_SOURCES = [("mgk_small.hip", "w%d" % w, ["-DMGK_SMALL_WAVES=%d" % w]) for w in (1, 2, 4, 8, 16)]
 HOST_SOURCES = ["mgk_host.cpp", "mgk_reorder.cpp"]
 
 # packed fp32 instructions are switched off on purpose for the test machines
@@ -47,15 +50,17 @@ def build(verbose: bool = False) -> str:
     hipcc = _hipcc()
     inc = ["-I" + os.path.join(os.path.dirname(HERE), "include"), "-I" + CSRC,
            "-I/opt/rocm/include"]
-    objs = []
-    for src in DEVICE_SOURCES:
-        obj = os.path.join(OBJ_DIR, src + ".o")
-        _run([hipcc] + HIP_FLAGS + inc + ["-c", os.path.join(CSRC, src), "-o", obj])
+    objs, cmds = [], []
+    for src, tag, extra in DEVICE_SOURCES:
+        obj = os.path.join(OBJ_DIR, "%s.%s.o" % (src, tag))
+        cmds.append([hipcc] + HIP_FLAGS + extra + inc + ["-c", os.path.join(CSRC, src), "-o", obj])
         objs.append(obj)
     for src in HOST_SOURCES:
         obj = os.path.join(OBJ_DIR, src + ".o")
-        _run(["g++"] + HOST_FLAGS + inc + ["-c", os.path.join(CSRC, src), "-o", obj])
+        cmds.append(["g++"] + HOST_FLAGS + inc + ["-c", os.path.join(CSRC, src), "-o", obj])
         objs.append(obj)
+    with ThreadPoolExecutor(max_workers=min(8, len(cmds))) as pool:
+        list(pool.map(_run, cmds))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
     if verbose:
         print("built", LIB)

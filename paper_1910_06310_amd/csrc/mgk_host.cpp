@@ -25,6 +25,9 @@ struct JobBin {
     int64_t first = 0;   // index of the bin's first job in the job array
     int64_t count = 0;
     size_t lds_bytes = 0;
+    int waves = 0, ept = 0;
+    bool atomic_rows = false;  // an inner graph has a row longer than one lane group
+    bool swapped = false;      // outer graphs come from batch Y, inner from X
 };
 
 struct JobList {
@@ -51,6 +54,7 @@ struct mgk_batch {
     void* blob = nullptr;
     MgkBatchDev dev{};
     JobList gram_jobs;
+    int gram_jobs_waves = 0;       // waves_per_pair setting the list was built for
 };
 
 struct mgk_ctx {
@@ -110,60 +114,92 @@ MgkParams make_params(const mgk_ctx* ctx, const mgk_batch* X) {
     return p;
 }
 
-// Orientation and cost of one pair for the on-chip solver.  The inner graph's
-// nonzeros are spread over lanes in chunks of 64, the outer graph's are
-// streamed, so the work is z_outer * ceil(z_inner / 64) wave iterations.
+// Launch shapes of the on-chip solver: `waves` wavefronts per pair, `ept`
+// vector elements per thread; a pair fits when n n' <= waves * 64 * ept.
+struct SmallConfig { int waves, ept; };
+const SmallConfig kAutoConfigs[] = {{1, 4}, {2, 4}, {4, 4}, {4, 8}, {4, 16}, {8, 16}, {16, 16}};
+const int kEpts[] = {4, 8, 16};
+
+// Orientation, launch shape and cost of one pair for the on-chip solver.  The
+// inner graph's nonzeros are spread over lanes in chunks of 64, the outer
+// graph's are streamed, so the work is z_outer * ceil(z_inner / 64) wave
+// iterations.
 struct PairPlan {
-    bool swap;       // true: Y's graph is the outer one
-    int64_t cost;
-    int64_t lds_words;
+    bool swap = false;   // true: Y's graph is the outer one
+    bool atomic_rows = false;
+    int64_t cost = 0;
+    int64_t lds_words = 0;
+    int waves = 0, ept = 0;  // 0: does not fit
 };
 
-PairPlan plan_pair(const MgkGraphDesc& a, const MgkGraphDesc& b, bool may_swap) {
-    auto passes = [](int64_t zo, int64_t zi) { return zo * ((zi + 63) / 64); };
+PairPlan plan_pair(const MgkGraphDesc& a, const MgkGraphDesc& b, bool may_swap, int forced_waves) {
+    // wave iterations of one XMV: outer nonzeros x 64-lane chunks of the inner layout
+    auto passes = [](const MgkGraphDesc& o, const MgkGraphDesc& i) {
+        return (int64_t)o.nnz * (i.lane_len / 64) + 2 * (int64_t)o.n * (i.lane_len / 64);
+    };
     PairPlan pl;
-    const int64_t keep = passes(a.nnz, b.nnz), swp = passes(b.nnz, a.nnz);
-    pl.swap = may_swap && swp < keep;
+    const int64_t keep = passes(a, b), swp = passes(b, a);
+    const bool keep_atomic = b.max_deg > MGK_LANE_GROUP, swp_atomic = a.max_deg > MGK_LANE_GROUP;
+    pl.swap = may_swap && (keep_atomic != swp_atomic ? keep_atomic : swp < keep);
+    pl.atomic_rows = pl.swap ? swp_atomic : keep_atomic;
     const int64_t N = (int64_t)a.n * b.n;
-    pl.cost = std::min(keep, pl.swap ? swp : keep) * 64 + 16 * N;
-    pl.lds_words = pl.swap ? mgk_small_lds_words(b.n, a.n, b.nnz, a.nnz)
-                           : mgk_small_lds_words(a.n, b.n, a.nnz, b.nnz);
+    pl.cost = (pl.swap ? swp : keep) * 64 + 16 * N;
+    if (N > MGK_SMALL_MAX_N) return pl;
+    if (forced_waves > 0) {  // requested workgroup size, doubled until the pair fits
+        for (int w = forced_waves; w <= 16 && pl.waves == 0; w *= 2)
+            for (int e : kEpts)
+                if ((int64_t)w * 64 * e >= N) { pl.waves = w; pl.ept = e; break; }
+    } else {
+        for (const SmallConfig& c : kAutoConfigs)
+            if ((int64_t)c.waves * 64 * c.ept >= N) { pl.waves = c.waves; pl.ept = c.ept; break; }
+    }
+    if (pl.waves == 0) return pl;
+    const MgkGraphDesc& o = pl.swap ? b : a;
+    const MgkGraphDesc& i = pl.swap ? a : b;
+    pl.lds_words = mgk_small_plan(o.n, i.n, o.nnz, i.lane_len, o.n_tiles, i.n_tiles, pl.waves).total;
+    if (pl.lds_words * 4 > MGK_LDS_LIMIT_BYTES) pl.waves = pl.ept = 0;
     return pl;
 }
-
-// LDS size classes: k pairs resident per compute unit.
-const int kResident[] = {16, 12, 10, 8, 6, 5, 4, 3, 2, 1};
 
 struct HostJob {
     MgkJob job;
     int64_t cost;
-    int32_t cls;
+    int32_t lds_words;
+    int16_t waves, ept;
+    bool atomic_rows, swapped;
 };
 
-mgk_status build_job_list(mgk_ctx* ctx, const mgk_batch* X, const mgk_batch* Y,
-                          std::vector<HostJob>& jobs, JobList& out, hipStream_t stream,
-                          int64_t* capacity) {
-    // class of each job, then order by (class, cost descending): big pairs start first
+mgk_status build_job_list(mgk_ctx* ctx, std::vector<HostJob>& jobs, JobList& out,
+                          hipStream_t stream, int64_t* capacity) {
+    // group by launch shape (largest first), inside a group big pairs start first
     std::stable_sort(jobs.begin(), jobs.end(), [](const HostJob& a, const HostJob& b) {
-        return a.cls != b.cls ? a.cls > b.cls : a.cost > b.cost;
+        const int ka = a.waves * 64 * a.ept, kb = b.waves * 64 * b.ept;
+        if (ka != kb) return ka > kb;
+        if (a.waves != b.waves) return a.waves > b.waves;
+        if (a.atomic_rows != b.atomic_rows) return a.atomic_rows;
+        if (a.swapped != b.swapped) return b.swapped;
+        return a.cost > b.cost;
     });
     out.bins.clear();
     out.n = (int64_t)jobs.size();
     std::vector<MgkJob> flat(jobs.size());
-    const int n_cls = (int)(sizeof kResident / sizeof kResident[0]);
     for (size_t k = 0; k < jobs.size(); ++k) {
         flat[k] = jobs[k].job;
-        if (out.bins.empty() || jobs[k].cls != jobs[k - 1].cls) {
+        if (out.bins.empty() || jobs[k].waves != out.bins.back().waves ||
+            jobs[k].ept != out.bins.back().ept || jobs[k].atomic_rows != out.bins.back().atomic_rows ||
+            jobs[k].swapped != out.bins.back().swapped) {
             JobBin b;
             b.first = (int64_t)k;
-            b.count = 0;
-            const int res = kResident[std::min(jobs[k].cls, n_cls - 1)];
-            b.lds_bytes = (size_t)(MGK_LDS_LIMIT_BYTES / res) & ~(size_t)255;
+            b.waves = jobs[k].waves;
+            b.ept = jobs[k].ept;
+            b.atomic_rows = jobs[k].atomic_rows;
+            b.swapped = jobs[k].swapped;
             out.bins.push_back(b);
         }
-        out.bins.back().count++;
+        JobBin& b = out.bins.back();
+        b.count++;
+        b.lds_bytes = std::max(b.lds_bytes, (size_t)jobs[k].lds_words * 4);
     }
-    (void)X; (void)Y;
     if (capacity == nullptr || *capacity < out.n) {
         if (out.dev) MGK_HIP(ctx, hipFree(out.dev));
         out.dev = nullptr;
@@ -179,25 +215,18 @@ mgk_status build_job_list(mgk_ctx* ctx, const mgk_batch* X, const mgk_batch* Y,
     return MGK_OK;
 }
 
-int lds_class(int64_t lds_words) {
-    const int64_t bytes = lds_words * 4;
-    const int n_cls = (int)(sizeof kResident / sizeof kResident[0]);
-    for (int c = 0; c < n_cls; ++c)
-        if (bytes <= (int64_t)((MGK_LDS_LIMIT_BYTES / kResident[c]) & ~255)) return c;
-    return -1;
-}
-
 mgk_status launch_jobs(mgk_ctx* ctx, const mgk_batch* X, const mgk_batch* Y, const JobList& jl,
                        float* K, int32_t* iters, int32_t* flags, hipStream_t stream) {
     const MgkParams prm = make_params(ctx, X);
     const bool weighted = X->weighted || Y->weighted;
-    const int waves = ctx->waves > 0 ? ctx->waves : 4;
     for (const JobBin& b : jl.bins) {
         int64_t done = 0;
         while (done < b.count) {  // grid dimension limit
             const int64_t chunk = std::min<int64_t>(b.count - done, (int64_t)1 << 30);
-            hipError_t e = mgk_launch_small(waves, weighted, X->dev, Y->dev, jl.dev + b.first + done,
-                                            (int)chunk, prm, b.lds_bytes, K, iters, flags, stream);
+            hipError_t e = mgk_launch_small(b.waves, b.ept, weighted, b.atomic_rows,
+                                            b.swapped ? Y->dev : X->dev, b.swapped ? X->dev : Y->dev,
+                                            jl.dev + b.first + done, (int)chunk, prm, b.lds_bytes,
+                                            K, iters, flags, stream);
             if (e != hipSuccess)
                 return fail(ctx, MGK_EDEVICE, "kernel launch failed: %s", hipGetErrorString(e));
             done += chunk;
@@ -320,7 +349,7 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
     B->graphs.resize(n_graphs);
     B->vtx_off.assign(vtx_off, vtx_off + n_graphs + 1);
     B->perm.resize((size_t)tot_v);
-    std::vector<int32_t> vlabel((size_t)tot_v), rowptr((size_t)tot_v), trow_ptr;
+    std::vector<int32_t> vlabel((size_t)tot_v), rowptr((size_t)tot_v), lanepos((size_t)tot_v), trow_ptr;
     std::vector<float> rowsum((size_t)tot_v), start((size_t)tot_v);
     B->w.reserve((size_t)(2 * tot_e));
     B->e.reserve((size_t)(2 * tot_e));
@@ -446,6 +475,18 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
         gd.n_tiles = (int32_t)B->tiles.size() - gd.toff;
         int32_t run = 0;
         for (int i = 0; i < n; ++i) { rowptr[v0 + i] = run; run += deg[i]; }
+        // lane layout as inner operand: rows packed into groups of 16 lanes
+        int32_t slot = 0, max_deg = 0;
+        for (int i = 0; i < n; ++i) {
+            const int dg = deg[i];
+            max_deg = std::max(max_deg, dg);
+            const int room = MGK_LANE_GROUP - slot % MGK_LANE_GROUP;
+            if (dg > room && room != MGK_LANE_GROUP) slot += room;  // start a new group
+            lanepos[v0 + i] = slot;
+            slot += dg;
+        }
+        gd.max_deg = max_deg;
+        gd.lane_len = (slot + 63) & ~63;
     }
     B->n_vertices = tot_v;
     B->nnz = (int64_t)B->w.size();
@@ -462,6 +503,7 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
     const size_t o_rs = append_bytes(blob, rowsum);
     const size_t o_st = append_bytes(blob, start);
     const size_t o_rp = append_bytes(blob, rowptr);
+    const size_t o_lp = append_bytes(blob, lanepos);
     const size_t o_tr = append_bytes(blob, trow_ptr);
     if (ctx->device < 0) {  // host-only context: packed form is kept for inspection only
         guard.b = nullptr;
@@ -480,6 +522,7 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
     B->dev.rowsum = reinterpret_cast<const float*>(base + o_rs);
     B->dev.start = reinterpret_cast<const float*>(base + o_st);
     B->dev.rowptr = reinterpret_cast<const int32_t*>(base + o_rp);
+    B->dev.lanepos = reinterpret_cast<const int32_t*>(base + o_lp);
     B->dev.trow_ptr = reinterpret_cast<const int32_t*>(base + o_tr);
 
     guard.b = nullptr;
@@ -541,26 +584,36 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
     MGK_HIP(ctx, hipSetDevice(ctx->device));
     const int64_t G = batch->n_graphs;
     if (G * G >= (int64_t)1 << 31) return fail(ctx, MGK_ELIMIT, "Gram matrix too large for 32-bit output indices");
+    if (batch->gram_jobs.dev != nullptr && batch->gram_jobs_waves != ctx->waves) {
+        MGK_HIP(ctx, hipStreamSynchronize(stream));  // launch shape changed: rebuild the job list
+        MGK_HIP(ctx, hipFree(batch->gram_jobs.dev));
+        batch->gram_jobs.dev = nullptr;
+    }
     if (batch->gram_jobs.dev == nullptr && G > 0) {
         // a4: job list, one job per unordered pair, kept with the batch
         std::vector<HostJob> jobs;
         jobs.reserve((size_t)(G * (G + 1) / 2));
         for (int64_t i = 0; i < G; ++i)
             for (int64_t j = i; j < G; ++j) {
-                const PairPlan pl = plan_pair(batch->graphs[i], batch->graphs[j], true);
+                const PairPlan pl = plan_pair(batch->graphs[i], batch->graphs[j], true, ctx->waves);
                 HostJob hj;
                 hj.job.g1 = (int32_t)(pl.swap ? j : i);
                 hj.job.g2 = (int32_t)(pl.swap ? i : j);
                 hj.job.out0 = (int32_t)(i * G + j);
                 hj.job.out1 = i == j ? -1 : (int32_t)(j * G + i);
                 hj.cost = pl.cost;
-                hj.cls = lds_class(pl.lds_words);
-                if (hj.cls < 0)
-                    return fail(ctx, MGK_ELIMIT, "pair (%lld, %lld) needs %lld bytes of LDS; the on-chip solver holds %d",
-                                (long long)i, (long long)j, (long long)pl.lds_words * 4, MGK_LDS_LIMIT_BYTES);
+                hj.lds_words = (int32_t)pl.lds_words;
+                hj.waves = (int16_t)pl.waves;
+                hj.ept = (int16_t)pl.ept;
+                hj.atomic_rows = pl.atomic_rows;
+                hj.swapped = false;  // one batch: swapping is done through the indices
+                if (pl.waves == 0)
+                    return fail(ctx, MGK_ELIMIT, "pair (%lld, %lld) with %lld product vertices does not fit the on-chip solver",
+                                (long long)i, (long long)j, (long long)batch->graphs[i].n * batch->graphs[j].n);
                 jobs.push_back(hj);
             }
-        mgk_status st = build_job_list(ctx, batch, batch, jobs, batch->gram_jobs, stream, nullptr);
+        mgk_status st = build_job_list(ctx, jobs, batch->gram_jobs, stream, nullptr);
+        batch->gram_jobs_waves = ctx->waves;
         if (st != MGK_OK) return st;
     }
     return launch_jobs(ctx, batch, batch, batch->gram_jobs, K_dev, iters_dev, flag_dev, stream);
@@ -577,31 +630,34 @@ mgk_status mgk_pairs(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
     if (!i_host || !j_host || !K_dev) return fail(ctx, MGK_EINVAL, "null argument");
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     MGK_HIP(ctx, hipSetDevice(ctx->device));
-    // Batches of one orientation only: outer graph from X, inner from Y, unless
-    // X and Y are the same batch (then the cheaper orientation is chosen).
-    const bool may_swap = X == Y;
+    // Either graph of a pair may be the outer operand; jobs whose outer graph
+    // comes from Y are launched with the batch arguments exchanged.
     std::vector<HostJob> jobs((size_t)n_pairs);
     for (int64_t k = 0; k < n_pairs; ++k) {
         const int32_t i = i_host[k], j = j_host[k];
         if (i < 0 || i >= X->n_graphs || j < 0 || j >= Y->n_graphs)
             return fail(ctx, MGK_EINVAL, "pair %lld: graph index out of range", (long long)k);
-        const PairPlan pl = plan_pair(X->graphs[i], Y->graphs[j], may_swap);
+        const PairPlan pl = plan_pair(X->graphs[i], Y->graphs[j], true, ctx->waves);
         HostJob& hj = jobs[(size_t)k];
         hj.job.g1 = pl.swap ? j : i;
         hj.job.g2 = pl.swap ? i : j;
         hj.job.out0 = (int32_t)k;
         hj.job.out1 = -1;
         hj.cost = pl.cost;
-        hj.cls = lds_class(pl.lds_words);
-        if (hj.cls < 0)
-            return fail(ctx, MGK_ELIMIT, "pair %lld needs %lld bytes of LDS; the on-chip solver holds %d",
-                        (long long)k, (long long)pl.lds_words * 4, MGK_LDS_LIMIT_BYTES);
+        hj.lds_words = (int32_t)pl.lds_words;
+        hj.waves = (int16_t)pl.waves;
+        hj.ept = (int16_t)pl.ept;
+        hj.atomic_rows = pl.atomic_rows;
+        hj.swapped = pl.swap && X != Y;
+        if (pl.waves == 0)
+            return fail(ctx, MGK_ELIMIT, "pair %lld with %lld product vertices does not fit the on-chip solver",
+                        (long long)k, (long long)X->graphs[i].n * Y->graphs[j].n);
     }
     if (ctx->pair_jobs_busy) {  // the previous call's kernels may still read the job buffer
         MGK_HIP(ctx, hipStreamSynchronize(ctx->pair_jobs_stream));
         ctx->pair_jobs_busy = false;
     }
-    mgk_status st = build_job_list(ctx, X, Y, jobs, ctx->pair_jobs, stream, &ctx->pair_jobs_cap);
+    mgk_status st = build_job_list(ctx, jobs, ctx->pair_jobs, stream, &ctx->pair_jobs_cap);
     if (st != MGK_OK) return st;
     ctx->pair_jobs_stream = stream;
     ctx->pair_jobs_busy = true;

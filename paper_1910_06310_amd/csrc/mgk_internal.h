@@ -11,7 +11,7 @@
 #define MGK_HD
 #endif
 
-// One graph of a batch, as the device sees it (32 bytes).  All offsets index
+// One graph of a batch, as the device sees it (40 bytes).  All offsets index
 // the batch-wide arrays of MgkBatchDev.
 struct MgkGraphDesc {
     int32_t n;            // vertices
@@ -22,7 +22,15 @@ struct MgkGraphDesc {
     int32_t zoff;         // first packed nonzero in w[] / e[]
     int32_t toff;         // first tile in tiles[]
     int32_t roff;         // first entry in trow_ptr[] (n_tile_rows + 1 entries)
+    int32_t max_deg;      // largest number of nonzeros in a row
+    int32_t lane_len;     // lane slots of the graph as inner operand (multiple of 64)
 };
+
+// Lane layout of a graph used as the inner operand of the on-chip XMV: the
+// nonzeros of a row occupy adjacent lanes that never cross a group of 16
+// lanes (rows longer than 16 are cut into runs of 16), so that the sum over a
+// row is a DPP shift-and-add inside one 16-lane row of a wavefront.
+#define MGK_LANE_GROUP 16
 
 // One non-empty octile (Section IV-A/B): tile coordinates, occupancy bitmap
 // (bit 8*r + c <-> element (r, c) of the tile) and where its packed nonzeros
@@ -43,6 +51,7 @@ struct MgkBatchDev {
     const float* rowsum;     // sum_j A_ij per vertex; d_i = rowsum + q (Eq. 1)
     const float* start;      // starting probability p_i
     const int32_t* rowptr;   // per vertex: nonzeros of the graph in rows before it
+    const int32_t* lanepos;  // per vertex: first lane slot of its row (inner operand layout)
     const int32_t* trow_ptr; // per graph: tile-row pointers into its tile list
 };
 
@@ -67,18 +76,47 @@ struct MgkParams {
 };
 
 // ---- LDS plan of the on-chip solver (one workgroup per pair) ---------------
-// words (4 bytes each):
-//   x, r, p, a, M            5 * N            N = n1 * n2
-//   rowptr1                  n1 + 1
-//   ent1 (outer graph)       4 * z1           {p-row byte offset, label, weight, -}
-//   ent2 (inner graph)       4 * z2           {i'*4, j'*4, label, log2 weight}
-//   reduction scratch        64
-static inline MGK_HD int64_t mgk_small_lds_words(int64_t n1, int64_t n2, int64_t z1, int64_t z2) {
-    int64_t words = 5 * n1 * n2 + (n1 + 1);
-    words = (words + 3) & ~(int64_t)3;  // ent arrays are 16-byte aligned
-    words += 4 * z1 + 4 * z2 + 64;
-    return words;
+// All offsets in 4-byte words from the start of dynamic LDS.  Computed the same
+// way on the host (to size the launch) and in the kernel.
+struct MgkSmallPlan {
+    int32_t p, y;            // vectors, N words each (padded to 4)
+    int32_t ent1, ent2;      // expanded nonzeros, 4 words each
+    int32_t rowend;          // bit k set: outer entry k is the last of its row
+    int32_t tiles1, tiles2;  // staged octile headers, 4 words each
+    int32_t vtx1, vtx2;      // per vertex: d_i, start probability, label
+    int32_t red;             // reduction scratch, 64 words
+    int32_t total;           // words
+    int32_t z1pad;           // outer entries padded (multiple of 4, + 4 spare)
+    int32_t share;           // nominal outer entries per wave
+    int32_t rowend_words;
+};
+
+static inline MGK_HD MgkSmallPlan mgk_small_plan(int32_t n1, int32_t n2, int32_t z1,
+                                                 int32_t lane_len2, int32_t t1, int32_t t2,
+                                                 int32_t waves) {
+    MgkSmallPlan L;
+    const int32_t np = (n1 * n2 + 3) & ~3;
+    L.z1pad = ((z1 + 3) & ~3) + 4;
+    L.share = (z1 + waves - 1) / waves;
+    if (L.share < 1) L.share = 1;
+    L.rowend_words = L.z1pad / 32 + 2;
+    L.p = 0;
+    L.y = np;
+    L.ent1 = 2 * np;
+    L.ent2 = L.ent1 + 4 * L.z1pad;
+    L.rowend = L.ent2 + 4 * lane_len2;
+    L.tiles1 = L.rowend + ((L.rowend_words + 3) & ~3);
+    L.tiles2 = L.tiles1 + 4 * t1;
+    L.vtx1 = L.tiles2 + 4 * t2;
+    L.vtx2 = L.vtx1 + 3 * n1;
+    L.red = L.vtx2 + 3 * n2;
+    L.total = L.red + 64;
+    return L;
 }
+
+// Largest product size N = n n' the on-chip solver takes: 16 waves x 16
+// elements per thread.
+#define MGK_SMALL_MAX_N (16 * 64 * 16)
 
 #define MGK_LDS_LIMIT_BYTES (160 * 1024)
 

@@ -1,12 +1,20 @@
 // On-chip solver: one workgroup runs the whole preconditioned CG iteration
-// (Alg. 1) for one graph pair with every vector resident in LDS.
+// (Alg. 1) for one graph pair.  The search direction p and the off-diagonal
+// product y live in LDS; x, r, M and the owner's copies of p and z live in
+// registers, EPT elements per thread.
 //
-// The off-diagonal product of Alg. 1 (the XMV of Alg. 2) is formed on the fly:
-// the inner graph's nonzeros live one per lane, the outer graph's nonzeros are
-// streamed from LDS as wave-uniform operands, and each (outer nonzero, inner
-// nonzero) pair costs one kappa_e evaluation, one gathered read of p_jj' and
-// one fused multiply-add.  Contributions to a_ii' are kept in a register while
-// the outer row i lasts and then added to LDS with one float atomic.
+// The off-diagonal product of Alg. 1 (the XMV of Alg. 2) is formed on the fly.
+// The octiles of both graphs are expanded once per pair into LDS entry lists
+// (Section IV-B: stored compact, expanded on chip).  The inner graph's
+// nonzeros then sit one per lane in registers, rows in adjacent lanes; the
+// outer graph's nonzeros are streamed from LDS as wave-uniform operands in row
+// order, four at a time so that their LDS reads overlap.  Each (outer, inner)
+// nonzero pair costs one kappa_e evaluation, one gathered read of p_jj' and
+// one fused multiply-add into a register that lasts for the outer row i.  At
+// the end of the row the lanes of each inner row i' are summed with DPP
+// shifts and one lane stores y_ii'.  Every y_ii' has exactly one writer, so no
+// atomics are needed (LDS float atomics cost ~200 clocks per wavefront
+// instruction on this chip, against 2 for a store).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -15,10 +23,23 @@
 
 namespace {
 
+// ---- wavefront reductions with DPP (no LDS traffic) --------------------------
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v) {
+    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true);
+    return v + __int_as_float(moved);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
+    v = dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);  // row_half_mirror
+    v = dpp_add<0x140>(v);  // row_mirror: every lane holds the sum of its row of 16
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return (r0 + r1) + (r2 + r3);
 }
 
 template <int WAVES>
@@ -33,46 +54,95 @@ __device__ __forceinline__ float block_sum(float v, float* red, int wave, int la
     return s;
 }
 
-// Expand the octiles of one graph row into LDS entries (Section IV-B: tiles
-// are stored compact and expanded on chip).  `row` is a vertex of graph g.
+template <int WAVES>
+__device__ __forceinline__ void block_sum2(float& u, float& v, float* red, int wave, int lane) {
+    u = wave_sum(u);
+    v = wave_sum(v);
+    if (WAVES == 1) return;
+    if (lane == 0) { red[wave] = u; red[16 + wave] = v; }
+    __syncthreads();
+    float su = 0.f, sv = 0.f;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) { su += red[w]; sv += red[16 + w]; }
+    u = su;
+    v = sv;
+}
+
+// Expand one octile (one wave, lane <-> bit of the bitmap) into the entry list
+// of its graph.
+// Outer graph: CSR order, entry = {byte offset of p row j, scaled label (or
+// weight for the constant kernel), log2 weight, byte offset of y row i};
+// `rowend` gets bit k set when entry k is the last of its row.
+// Inner graph: lane layout (rows in adjacent lanes inside groups of 16), entry
+// = {i'*4 | rank in run << 20 | last-of-run << 31, j'*4, scaled label or
+// weight, log2 weight}.
 template <bool OUTER, bool WEIGHTED, int EK>
-__device__ __forceinline__ void expand_row(const MgkBatchDev& B, const MgkGraphDesc& g, int row,
-                                           uint4* ent, int n_inner, const MgkParams& prm) {
-    const int tr = row >> 3, r = row & 7;
-    const int32_t* trp = B.trow_ptr + g.roff;
-    const int t0 = trp[tr], t1 = trp[tr + 1];
-    int pos = B.rowptr[g.voff + row];
-    for (int t = t0; t < t1; ++t) {
-        const MgkTile tile = B.tiles[g.toff + t];
-        uint32_t byte = (uint32_t)(tile.bitmap >> (8 * r)) & 0xffu;
-        if (!byte) continue;
-        const uint64_t below = tile.bitmap & ((1ull << (8 * r)) - 1ull);
-        int k = g.zoff + (int)tile.nzoff + __popcll(below);
-        while (byte) {
-            const int c = __ffs(byte) - 1;
-            byte &= byte - 1;
-            const int col = (int)tile.tc * 8 + c;
-            const float w = B.w[k];
-            const float el = (B.e[k] - prm.e_shift) * prm.e_scale;
-            ++k;
-            uint4 v;
-            if (OUTER) {
-                v.x = (uint32_t)(col * n_inner * 4);  // byte offset of p row `col`
-                v.y = __float_as_uint(el);
-                v.z = __float_as_uint(WEIGHTED ? __log2f(w) : 0.f);
-                v.w = __float_as_uint(w);
-            } else {
-                v.x = (uint32_t)(row * 4);
-                v.y = (uint32_t)(col * 4);
-                v.z = __float_as_uint(EK == MGK_EK_SE ? el : w);
-                v.w = __float_as_uint(WEIGHTED ? __log2f(w) : 0.f);
-            }
-            ent[pos++] = v;
-        }
+__device__ __forceinline__ void expand_tile(const MgkBatchDev& B, const MgkGraphDesc& g,
+                                            const MgkTile* tiles_lds, int t, int lane, uint4* ent,
+                                            uint32_t* rowend, int n_inner, const MgkParams& prm) {
+    const MgkTile tile = tiles_lds[t];
+    const int r = lane >> 3, c = lane & 7;
+    const bool set = (tile.bitmap >> lane) & 1ull;
+    const int row = (int)tile.tr * 8 + r, col = (int)tile.tc * 8 + c;
+    const uint64_t below = tile.bitmap & ((1ull << lane) - 1ull);
+    const int k = (int)tile.nzoff + __popcll(below);
+    float w = 1.f, el = 0.f;
+    int rp0 = 0, rp1 = 0, lp = 0;
+    if (set) {
+        w = B.w[g.zoff + k];
+        el = (B.e[g.zoff + k] - prm.e_shift) * prm.e_scale;
+        rp0 = B.rowptr[g.voff + row];
+        rp1 = (row + 1 < g.n) ? B.rowptr[g.voff + row + 1] : g.nnz;
+        if (!OUTER) lp = B.lanepos[g.voff + row];
+    }
+    // nonzeros of this row in earlier tiles of the same tile row
+    int prior = 0;
+    for (int tp = t - 1; tp >= 0 && tiles_lds[tp].tr == tile.tr; --tp)
+        prior += __popc((uint32_t)(tiles_lds[tp].bitmap >> (8 * r)) & 0xffu);
+    if (!set) return;
+    const uint32_t rowbyte = (uint32_t)(tile.bitmap >> (8 * r)) & 0xffu;
+    const int rank = prior + __popc(rowbyte & ((1u << c) - 1u));  // position inside the row
+    uint4 v;
+    if (OUTER) {
+        const int pos = rp0 + rank;
+        v.x = (uint32_t)(col * n_inner * 4);
+        v.y = __float_as_uint(EK == MGK_EK_SE ? el : w);
+        v.z = __float_as_uint(WEIGHTED ? __log2f(w) : 0.f);
+        v.w = (uint32_t)(row * n_inner * 4);
+        ent[pos] = v;
+        if (pos + 1 == rp1) atomicOr(&rowend[pos >> 5], 1u << (pos & 31));
+    } else {
+        const int deg = rp1 - rp0;
+        const uint32_t run_rank = (uint32_t)rank % MGK_LANE_GROUP;
+        const uint32_t last = (rank + 1 == deg || run_rank == MGK_LANE_GROUP - 1) ? 1u : 0u;
+        v.x = (uint32_t)(row * 4) | (run_rank << 20) | (last << 31);
+        v.y = (uint32_t)(col * 4);
+        v.z = __float_as_uint(EK == MGK_EK_SE ? el : w);
+        v.w = __float_as_uint(WEIGHTED ? __log2f(w) : 0.f);
+        ent[lp + rank] = v;
     }
 }
 
-template <int WAVES, bool WEIGHTED, int EK>
+template <int DIST>
+__device__ __forceinline__ float row_shr(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x110 + DIST, 0xf, 0xf, true));
+}
+
+// position of the first set bit at or after `from` in a bit array of `words` words; `none` if absent
+__device__ __forceinline__ int next_set_bit(const uint32_t* bits, int words, int from, int none) {
+    int wi = from >> 5;
+    if (wi >= words) return none;
+    uint32_t cur = bits[wi] & (0xffffffffu << (from & 31));
+    while (true) {
+        if (cur) return wi * 32 + __ffs(cur) - 1;
+        if (++wi >= words) return none;
+        cur = bits[wi];
+    }
+}
+
+// ATOMIC: the inner graph has rows longer than 16 nonzeros; their runs are
+// combined with float atomics and y is cleared by its reader every iteration.
+template <int WAVES, int EPT, bool WEIGHTED, int EK, bool ATOMIC>
 __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
     MgkBatchDev X, MgkBatchDev Y, const MgkJob* __restrict__ jobs, MgkParams prm,
     float* __restrict__ K_out, int32_t* __restrict__ iters_out, int32_t* __restrict__ flag_out) {
@@ -83,140 +153,220 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
     const MgkJob job = jobs[blockIdx.x];
     const MgkGraphDesc g1 = X.graphs[job.g1];
     const MgkGraphDesc g2 = Y.graphs[job.g2];
-    const int n1 = g1.n, n2 = g2.n, N = n1 * n2, z1 = g1.nnz, z2 = g2.nnz;
+    const int n1 = g1.n, n2 = g2.n, N = n1 * n2, z1 = g1.nnz, len2 = g2.lane_len;
+    const MgkSmallPlan L = mgk_small_plan(n1, n2, z1, len2, g1.n_tiles, g2.n_tiles, WAVES);
 
-    float* x = reinterpret_cast<float*>(lds);
-    float* r = x + N;
-    float* p = r + N;
-    float* a = p + N;
-    float* M = a + N;
-    int* rowptr1 = reinterpret_cast<int*>(M + N);
-    uint4* ent1 = reinterpret_cast<uint4*>(lds + ((5 * N + n1 + 1 + 3) & ~3));
-    uint4* ent2 = ent1 + z1;
-    float* red = reinterpret_cast<float*>(ent2 + z2);
+    float* p = reinterpret_cast<float*>(lds + L.p);
+    float* y = reinterpret_cast<float*>(lds + L.y);
+    uint4* ent1 = reinterpret_cast<uint4*>(lds + L.ent1);
+    uint4* ent2 = reinterpret_cast<uint4*>(lds + L.ent2);
+    uint32_t* rowend = lds + L.rowend;
+    MgkTile* tl1 = reinterpret_cast<MgkTile*>(lds + L.tiles1);
+    MgkTile* tl2 = reinterpret_cast<MgkTile*>(lds + L.tiles2);
+    float* dq1 = reinterpret_cast<float*>(lds + L.vtx1);           // d_i = rowsum + q
+    float* st1 = dq1 + n1;                                         // start probability
+    int* lb1 = reinterpret_cast<int*>(st1 + n1);                   // vertex label
+    float* dq2 = reinterpret_cast<float*>(lds + L.vtx2);
+    float* st2 = dq2 + n2;
+    int* lb2 = reinterpret_cast<int*>(st2 + n2);
+    float* red = reinterpret_cast<float*>(lds + L.red);
 
-    // ---- expand both graphs into LDS --------------------------------------
-    for (int row = tid; row < n1 + n2; row += NT) {
-        if (row < n1) {
-            rowptr1[row] = X.rowptr[g1.voff + row];
-            expand_row<true, WEIGHTED, EK>(X, g1, row, ent1, n2, prm);
-        } else {
-            expand_row<false, WEIGHTED, EK>(Y, g2, row - n1, ent2, n2, prm);
-        }
+    // ---- stage tiles and per-vertex data; clear row-end bits, entries and y ----
+    for (int t = tid; t < g1.n_tiles; t += NT) tl1[t] = X.tiles[g1.toff + t];
+    for (int t = tid; t < g2.n_tiles; t += NT) tl2[t] = Y.tiles[g2.toff + t];
+    for (int v = tid; v < n1; v += NT) {
+        dq1[v] = X.rowsum[g1.voff + v] + prm.q;
+        st1[v] = X.start[g1.voff + v];
+        lb1[v] = X.vlabel[g1.voff + v];
     }
-    if (tid == 0) rowptr1[n1] = z1;
-
-    // ---- Alg. 1 set-up: M = D_x V_x^{-1}, x = 0, r = b = D_x q_x, z = M^{-1} r,
-    //      p = z, rho = r^T z.  a is preset to M p so that the XMV only has to
-    //      subtract the off-diagonal product (a = M p - L p). -----------------
-    const float qq = prm.q * prm.q;
-    float s_rz = 0.f, s_bb = 0.f;
-    for (int idx = tid; idx < N; idx += NT) {
-        const int i = idx / n2, ip = idx - i * n2;
-        const float d1 = X.rowsum[g1.voff + i] + prm.q;
-        const float d2 = Y.rowsum[g2.voff + ip] + prm.q;
-        const float kv = (X.vlabel[g1.voff + i] == Y.vlabel[g2.voff + ip]) ? 1.f : prm.h;
-        const float dd = d1 * d2;
-        const float b = dd * qq;
-        const float z0 = kv * qq;          // M^{-1} b
-        M[idx] = dd / kv;
-        x[idx] = 0.f;
-        r[idx] = b;
-        p[idx] = z0;
-        a[idx] = b;                        // M p
-        s_rz += b * z0;
-        s_bb += b * b;
+    for (int v = tid; v < n2; v += NT) {
+        dq2[v] = Y.rowsum[g2.voff + v] + prm.q;
+        st2[v] = Y.start[g2.voff + v];
+        lb2[v] = Y.vlabel[g2.voff + v];
     }
-    float rho = block_sum<WAVES>(s_rz, red, wave, lane);
-    const float bb = block_sum<WAVES>(s_bb, red + 16, wave, lane);
-    const float thresh = prm.rtol2 * bb;
-    int max_iter = prm.max_iter;
-    if (max_iter <= 0) max_iter = min(2 * N, 1000);
+    for (int k = tid; k < L.rowend_words; k += NT) rowend[k] = 0u;
+    // spare outer entries past z1 (read by the 4-wide loop, never used) and idle
+    // lane slots of the inner layout: weight 0, address 0, never the end of a run
+    for (int k = z1 + tid; k < L.z1pad; k += NT) ent1[k] = make_uint4(0u, 0u, 0u, 0u);
+    for (int k = tid; k < len2; k += NT) ent2[k] = make_uint4(0u, 0u, 0u, 0xff800000u);  // log2 w = -inf
+    for (int k = tid; k < L.y; k += NT) y[k] = 0.f;  // entries no row pair reaches stay 0
     __syncthreads();
 
+    // ---- expand the octiles ---------------------------------------------------
+    for (int t = wave; t < g1.n_tiles + g2.n_tiles; t += WAVES) {
+        if (t < g1.n_tiles)
+            expand_tile<true, WEIGHTED, EK>(X, g1, tl1, t, lane, ent1, rowend, n2, prm);
+        else
+            expand_tile<false, WEIGHTED, EK>(Y, g2, tl2, t - g1.n_tiles, lane, ent2, nullptr, n2, prm);
+    }
+
+    // ---- Alg. 1 set-up: M = D_x V_x^{-1}, x = 0, r = b = D_x q_x, z = M^{-1} r,
+    //      p = z, rho = r^T z ----------------------------------------------------
+    float xr[EPT], rr_[EPT], Mr[EPT], pr[EPT], zr[EPT];
+    const float qq = prm.q * prm.q;
+    const float inv_n2 = 1.0f / (float)n2;
+    float s_rz = 0.f, s_bb = 0.f;
+#pragma unroll
+    for (int m = 0; m < EPT; ++m) {
+        const int idx = tid + m * NT;
+        const bool ok = idx < N;
+        const int ic = ok ? idx : 0;
+        const int i = (int)(((float)ic + 0.5f) * inv_n2);
+        const int ip = ic - i * n2;
+        const float kv = (lb1[i] == lb2[ip]) ? 1.f : prm.h;
+        const float dd = dq1[i] * dq2[ip];
+        const float b = ok ? dd * qq : 0.f;
+        const float z0 = ok ? kv * qq : 0.f;  // M^{-1} b
+        Mr[m] = ok ? dd / kv : 1.f;
+        xr[m] = 0.f;
+        rr_[m] = b;
+        pr[m] = z0;
+        if (ok) p[idx] = z0;
+        s_rz = __builtin_fmaf(b, z0, s_rz);
+        s_bb = __builtin_fmaf(b, b, s_bb);
+    }
+    block_sum2<WAVES>(s_rz, s_bb, red, wave, lane);
+    float rho = s_rz;
+    const float thresh = prm.rtol2 * s_bb;
+    int max_iter = prm.max_iter;
+    if (max_iter <= 0) max_iter = min(2 * N, 1000);
+    __syncthreads();  // entries, row-end bits and p are complete
+
+    // ---- this wave's share of the outer nonzeros: whole rows, about z1 / WAVES
+    int kbeg = 0, kend = z1;
+    if (WAVES > 1) {
+        if (wave > 0) kbeg = next_set_bit(rowend, L.rowend_words, wave * L.share - 1, z1 - 1) + 1;
+        if (wave < WAVES - 1) kend = next_set_bit(rowend, L.rowend_words, (wave + 1) * L.share - 1, z1 - 1) + 1;
+        kbeg = __builtin_amdgcn_readfirstlane(min(kbeg, z1));
+        kend = __builtin_amdgcn_readfirstlane(min(kend, z1));
+    }
+    const int nsteps = g2.max_deg <= 1 ? 0 : g2.max_deg <= 2 ? 1 : g2.max_deg <= 4 ? 2
+                     : g2.max_deg <= 8 ? 3 : 4;
+
     const char* pbytes = reinterpret_cast<const char*>(p);
-    char* abytes = reinterpret_cast<char*>(a);
+    char* ybytes = reinterpret_cast<char*>(y);
     const float ke_c = prm.ke_const;
 
     int it = 0;
     int flag = 1;
     while (it < max_iter) {
-        // ---- XMV (Alg. 2): a_ii' -= sum_{j,j'} A_ij A'_i'j' kappa_e(E_ij,E'_i'j') p_jj'
-        for (int c = 0; c < z2; c += 64) {
-            const int k2 = c + lane;
-            const bool act = k2 < z2;
-            const uint4 e2 = ent2[act ? k2 : 0];
-            const uint32_t ip4 = e2.x, jp4 = e2.y;
+        // ---- XMV (Alg. 2): y_ii' = sum_{j,j'} A_ij A'_i'j' kappa_e(E_ij,E'_i'j') p_jj'
+        for (int c = 0; c < len2; c += 64) {
+            const uint4 e2 = ent2[c + lane];
+            const uint32_t ip4 = e2.x & 0xfffffu, jp4 = e2.y;
+            const uint32_t rank = (e2.x >> 20) & 0xffu;
+            const bool last = (e2.x >> 31) != 0u;
             const float el2 = __uint_as_float(e2.z);
             const float lw2 = __uint_as_float(e2.w);
-            for (int i = wave; i < n1; i += WAVES) {
-                const int kb = __builtin_amdgcn_readfirstlane(rowptr1[i]);
-                const int ke = __builtin_amdgcn_readfirstlane(rowptr1[i + 1]);
-                if (kb == ke) continue;
-                float acc = 0.f;
-                for (int k = kb; k < ke; ++k) {
-                    const uint4 e1 = ent1[k];
-                    const float pv = *reinterpret_cast<const float*>(pbytes + (e1.x + jp4));
-                    if (EK == MGK_EK_SE) {
-                        const float d = el2 - __uint_as_float(e1.y);
-                        float t;
-                        if (WEIGHTED) t = __builtin_fmaf(-d, d, lw2 + __uint_as_float(e1.z));
-                        else t = -d * d;
-                        acc = __builtin_fmaf(__builtin_amdgcn_exp2f(t), pv, acc);
-                    } else {
-                        if (WEIGHTED) acc = __builtin_fmaf(__uint_as_float(e1.w), pv, acc);
-                        else acc += pv;
+            const float m1 = rank >= 1 ? 1.f : 0.f, m2 = rank >= 2 ? 1.f : 0.f;
+            const float m4 = rank >= 4 ? 1.f : 0.f, m8 = rank >= 8 ? 1.f : 0.f;
+            float acc = 0.f;
+            for (int k0 = kbeg; k0 < kend; k0 += 32) {
+                // row-end bits of entries k0 .. k0+31
+                const uint32_t lo = __builtin_amdgcn_readfirstlane(rowend[k0 >> 5]);
+                const uint32_t hi = __builtin_amdgcn_readfirstlane(rowend[(k0 >> 5) + 1]);
+                uint32_t window = (uint32_t)((((uint64_t)hi << 32) | lo) >> (k0 & 31));
+                const int kstop = min(k0 + 32, kend);
+                if (kstop - k0 < 32) window &= (1u << (kstop - k0)) - 1u;
+                for (int k = k0; k < kstop; k += 4, window >>= 4) {
+                    uint4 e1[4];
+                    float pv[4], cu[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) e1[u] = ent1[k + u];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        pv[u] = *reinterpret_cast<const float*>(pbytes + (e1[u].x + jp4));
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        if (EK == MGK_EK_SE) {
+                            const float d = el2 - __uint_as_float(e1[u].y);
+                            float t;
+                            if (WEIGHTED) t = __builtin_fmaf(-d, d, lw2 + __uint_as_float(e1[u].z));
+                            else t = __builtin_fmaf(-d, d, lw2);  // lw2: 0, or -inf on idle lanes
+                            cu[u] = __builtin_amdgcn_exp2f(t);
+                        } else {
+                            cu[u] = WEIGHTED ? __uint_as_float(e1[u].y) : 1.f;  // A_ij
+                        }
                     }
-                }
-                if (EK == MGK_EK_CONST) {
-                    acc *= WEIGHTED ? ke_c * el2 : ke_c;  // el2 holds A'_i'j' for the constant kernel
-                }
-                if (act) {
-                    float* dst = reinterpret_cast<float*>(abytes + (i * n2 * 4 + ip4));
-                    __hip_atomic_fetch_add(dst, -acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        acc = __builtin_fmaf(cu[u], pv[u], acc);
+                        if ((window >> u) & 1u) {   // end of outer row i: sum over each inner row
+                            if (EK == MGK_EK_CONST) acc *= ke_c * el2;  // el2 = A'_i'j' (0 on idle lanes)
+                            if (nsteps > 0) acc = __builtin_fmaf(m1, row_shr<1>(acc), acc);
+                            if (nsteps > 1) acc = __builtin_fmaf(m2, row_shr<2>(acc), acc);
+                            if (nsteps > 2) acc = __builtin_fmaf(m4, row_shr<4>(acc), acc);
+                            if (nsteps > 3) acc = __builtin_fmaf(m8, row_shr<8>(acc), acc);
+                            if (last) {
+                                float* dst = reinterpret_cast<float*>(ybytes + (e1[u].w + ip4));
+                                if (ATOMIC)
+                                    __hip_atomic_fetch_add(dst, acc, __ATOMIC_RELAXED,
+                                                           __HIP_MEMORY_SCOPE_WORKGROUP);
+                                else
+                                    *dst = acc;
+                            }
+                            acc = 0.f;
+                        }
+                    }
                 }
             }
         }
         __syncthreads();
 
-        // ---- alpha = rho / p^T a
+        // ---- a = M p - y ; alpha = rho / p^T a
         float s_pa = 0.f;
-        for (int idx = tid; idx < N; idx += NT) s_pa += p[idx] * a[idx];
+#pragma unroll
+        for (int m = 0; m < EPT; ++m) {
+            const int idx = tid + m * NT;
+            float yv = 0.f;
+            if (idx < N) {
+                yv = y[idx];
+                if (ATOMIC) y[idx] = 0.f;
+            }
+            zr[m] = __builtin_fmaf(Mr[m], pr[m], -yv);
+            s_pa = __builtin_fmaf(pr[m], zr[m], s_pa);
+        }
         const float pa = block_sum<WAVES>(s_pa, red + 32, wave, lane);
         const float alpha = rho / pa;
 
-        // ---- x += alpha p; r -= alpha a; z = M^{-1} r (kept in a); rho' = r^T z
+        // ---- x += alpha p; r -= alpha a; z = M^{-1} r; rho' = r^T z
         float s_rz2 = 0.f, s_rr = 0.f;
-        for (int idx = tid; idx < N; idx += NT) {
-            x[idx] = __builtin_fmaf(alpha, p[idx], x[idx]);
-            const float rv = __builtin_fmaf(-alpha, a[idx], r[idx]);
-            r[idx] = rv;
-            const float zv = rv * __builtin_amdgcn_rcpf(M[idx]);
-            a[idx] = zv;
+#pragma unroll
+        for (int m = 0; m < EPT; ++m) {
+            xr[m] = __builtin_fmaf(alpha, pr[m], xr[m]);
+            const float rv = __builtin_fmaf(-alpha, zr[m], rr_[m]);
+            rr_[m] = rv;
+            const float zv = rv * __builtin_amdgcn_rcpf(Mr[m]);
+            zr[m] = zv;
             s_rz2 = __builtin_fmaf(rv, zv, s_rz2);
             s_rr = __builtin_fmaf(rv, rv, s_rr);
         }
-        const float rho2 = block_sum<WAVES>(s_rz2, red, wave, lane);
-        const float rr = block_sum<WAVES>(s_rr, red + 16, wave, lane);
+        block_sum2<WAVES>(s_rz2, s_rr, red, wave, lane);
         ++it;
-        if (rr <= thresh) { flag = 0; break; }
+        if (s_rr <= thresh) { flag = 0; break; }
 
-        // ---- p = z + beta p ; a = M p
-        const float beta = rho2 / rho;
-        rho = rho2;
-        for (int idx = tid; idx < N; idx += NT) {
-            const float pn = __builtin_fmaf(beta, p[idx], a[idx]);
-            p[idx] = pn;
-            a[idx] = M[idx] * pn;
+        // ---- p = z + beta p
+        const float beta = s_rz2 / rho;
+        rho = s_rz2;
+#pragma unroll
+        for (int m = 0; m < EPT; ++m) {
+            const int idx = tid + m * NT;
+            const float pn = __builtin_fmaf(beta, pr[m], zr[m]);
+            pr[m] = pn;
+            if (idx < N) p[idx] = pn;
         }
         __syncthreads();
     }
 
     // ---- K = p_x^T x (Eq. 1)
     float s_k = 0.f;
-    for (int idx = tid; idx < N; idx += NT) {
-        const int i = idx / n2, ip = idx - i * n2;
-        s_k += X.start[g1.voff + i] * Y.start[g2.voff + ip] * x[idx];
+#pragma unroll
+    for (int m = 0; m < EPT; ++m) {
+        const int idx = tid + m * NT;
+        const int ic = idx < N ? idx : 0;
+        const int i = (int)(((float)ic + 0.5f) * inv_n2);
+        const int ip = ic - i * n2;
+        s_k = __builtin_fmaf(st1[i] * st2[ip], xr[m], s_k);  // x is 0 beyond N
     }
     const float Kval = block_sum<WAVES>(s_k, red + 48, wave, lane);
     if (tid == 0) {
@@ -233,49 +383,61 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
     }
 }
 
-template <int WAVES, bool WEIGHTED, int EK>
+template <int WAVES, int EPT, bool WEIGHTED, int EK, bool ATOMIC>
 hipError_t launch_one(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkJob* jobs, int n_jobs,
                       const MgkParams& prm, size_t lds_bytes, float* K, int32_t* iters,
                       int32_t* flags, hipStream_t stream) {
-    auto kern = mgk_pcg_small<WAVES, WEIGHTED, EK>;
-    static size_t configured = 0;  // per instantiation
-    if (lds_bytes > configured) {
+    auto kern = mgk_pcg_small<WAVES, EPT, WEIGHTED, EK, ATOMIC>;
+    static bool configured = false;  // per instantiation
+    if (!configured) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize,
                                            MGK_LDS_LIMIT_BYTES);
         if (e != hipSuccess) return e;
-        configured = MGK_LDS_LIMIT_BYTES;
+        configured = true;
     }
     hipLaunchKernelGGL(kern, dim3(n_jobs), dim3(WAVES * 64), lds_bytes, stream, X, Y, jobs, prm, K,
                        iters, flags);
     return hipGetLastError();
 }
 
-template <int WAVES>
-hipError_t launch_w(bool weighted, int ek, const MgkBatchDev& X, const MgkBatchDev& Y,
-                    const MgkJob* jobs, int n_jobs, const MgkParams& prm, size_t lds_bytes, float* K,
-                    int32_t* iters, int32_t* flags, hipStream_t stream) {
+template <int WAVES, int EPT>
+hipError_t launch_we(bool weighted, bool atomic_rows, int ek, const MgkBatchDev& X,
+                     const MgkBatchDev& Y, const MgkJob* jobs, int n_jobs, const MgkParams& prm,
+                     size_t lds_bytes, float* K, int32_t* iters, int32_t* flags, hipStream_t stream) {
+#define MGK_GO(WT, EKV, AT) \
+    return launch_one<WAVES, EPT, WT, EKV, AT>(X, Y, jobs, n_jobs, prm, lds_bytes, K, iters, flags, stream)
     if (ek == MGK_EK_SE) {
-        if (weighted) return launch_one<WAVES, true, MGK_EK_SE>(X, Y, jobs, n_jobs, prm, lds_bytes, K, iters, flags, stream);
-        return launch_one<WAVES, false, MGK_EK_SE>(X, Y, jobs, n_jobs, prm, lds_bytes, K, iters, flags, stream);
+        if (weighted) { if (atomic_rows) MGK_GO(true, MGK_EK_SE, true); MGK_GO(true, MGK_EK_SE, false); }
+        if (atomic_rows) MGK_GO(false, MGK_EK_SE, true);
+        MGK_GO(false, MGK_EK_SE, false);
     }
-    if (weighted) return launch_one<WAVES, true, MGK_EK_CONST>(X, Y, jobs, n_jobs, prm, lds_bytes, K, iters, flags, stream);
-    return launch_one<WAVES, false, MGK_EK_CONST>(X, Y, jobs, n_jobs, prm, lds_bytes, K, iters, flags, stream);
+    if (weighted) { if (atomic_rows) MGK_GO(true, MGK_EK_CONST, true); MGK_GO(true, MGK_EK_CONST, false); }
+    if (atomic_rows) MGK_GO(false, MGK_EK_CONST, true);
+    MGK_GO(false, MGK_EK_CONST, false);
+#undef MGK_GO
 }
 
 }  // namespace
 
-hipError_t mgk_launch_small(int waves, bool weighted, const MgkBatchDev& X, const MgkBatchDev& Y,
-                            const MgkJob* jobs_dev, int n_jobs, const MgkParams& prm,
-                            size_t lds_bytes, float* K, int32_t* iters, int32_t* flags,
-                            hipStream_t stream) {
+#ifndef MGK_SMALL_WAVES
+#error "compile with -DMGK_SMALL_WAVES=<1|2|4|8|16>"
+#endif
+
+#define MGK_CAT2(a, b) a##b
+#define MGK_CAT(a, b) MGK_CAT2(a, b)
+
+// One translation unit per workgroup size keeps the build parallel.
+hipError_t MGK_CAT(mgk_launch_small_w, MGK_SMALL_WAVES)(
+    int ept, bool weighted, bool atomic_rows, const MgkBatchDev& X, const MgkBatchDev& Y,
+    const MgkJob* jobs_dev, int n_jobs, const MgkParams& prm, size_t lds_bytes, float* K,
+    int32_t* iters, int32_t* flags, hipStream_t stream) {
     if (n_jobs <= 0) return hipSuccess;
-    switch (waves) {
-        case 1: return launch_w<1>(weighted, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
-        case 2: return launch_w<2>(weighted, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
-        case 4: return launch_w<4>(weighted, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
-        case 8: return launch_w<8>(weighted, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
-        case 16: return launch_w<16>(weighted, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
+    constexpr int W = MGK_SMALL_WAVES;
+    switch (ept) {
+        case 4: return launch_we<W, 4>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
+        case 8: return launch_we<W, 8>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
+        case 16: return launch_we<W, 16>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
         default: return hipErrorInvalidValue;
     }
 }

@@ -137,6 +137,28 @@ def test_weighted_graphs_and_separate_batches(torch, solver):
     assert K2[0] == K2[3]
 
 
+def test_rows_longer_than_a_lane_group(torch, solver):
+    # dense small graphs: rows of more than 16 nonzeros take the atomic row-combine path,
+    # pairs of a dense and a sparse graph put the sparse one on the lanes
+    rng = np.random.default_rng(12)
+    prm = W.KernelParams(q=0.05, h=0.5, length_scale=0.8)
+    dense = W.erdos_renyi_batch(rng, 4, 20, 40, 0.8, (0.2, 1.0), (0.0, 2.0), 3, prm)
+    sparse = W.erdos_renyi_batch(rng, 3, 20, 40, 0.1, (0.2, 1.0), (0.0, 2.0), 3, prm)
+    wb = W.concat_batches([dense, sparse], prm)
+    solver.configure(prm)
+    solver.set_solver(1e-6, 0)
+    K, it, fl = run_gram(torch, solver, wb)
+    pi, pj = W.gram_pairs(7)
+    np.testing.assert_allclose(K[pi, pj], C.pairs(wb, pi, pj, tier=0), rtol=RTOL)
+    assert (fl == 0).all()
+    BX = solver.load_batch(dense); BY = solver.load_batch(sparse)
+    qi = np.repeat(np.arange(4), 3).astype(np.int32); qj = np.tile(np.arange(3), 4).astype(np.int32)
+    K2, _, _ = run_pairs(torch, solver, BX, BY, qi, qj)
+    np.testing.assert_allclose(K2, C.pairs(wb, qi, qj + 4, tier=0), rtol=RTOL)
+    K3, _, _ = run_pairs(torch, solver, BY, BX, qj, qi)
+    np.testing.assert_allclose(K3, K2, rtol=1e-5)
+
+
 def test_unlabeled_random_walk_kernel(torch, solver):
     # h = 1 and a constant edge kernel of 1 give Eq. 2
     wb = W.config1(12)
