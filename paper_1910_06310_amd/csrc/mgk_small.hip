@@ -140,6 +140,76 @@ __device__ __forceinline__ int next_set_bit(const uint32_t* bits, int words, int
     }
 }
 
+// One XMV (Alg. 2) over this wave's share [kbeg, kend) of the outer nonzeros:
+// y_ii' = sum_{j,j'} A_ij A'_i'j' kappa_e(E_ij, E'_i'j') p_jj'.  NSTEPS DPP
+// shift-and-add steps sum the lanes of each inner row (rows of up to 2^NSTEPS
+// nonzeros).
+template <int NSTEPS, bool WEIGHTED, int EK, bool ATOMIC>
+__device__ __forceinline__ void xmv_pass(const uint4* ent1, const uint4* ent2, const uint32_t* rowend,
+                                         const char* pbytes, char* ybytes, int len2, int kbeg,
+                                         int kend, float ke_c, int lane) {
+    for (int c = 0; c < len2; c += 64) {
+        const uint4 e2 = ent2[c + lane];
+        const uint32_t ip4 = e2.x & 0xfffffu, jp4 = e2.y;
+        const uint32_t rank = (e2.x >> 20) & 0xffu;
+        const bool last = (e2.x >> 31) != 0u;
+        const float el2 = __uint_as_float(e2.z);
+        const float lw2 = __uint_as_float(e2.w);
+        const float m1 = rank >= 1 ? 1.f : 0.f, m2 = rank >= 2 ? 1.f : 0.f;
+        const float m4 = rank >= 4 ? 1.f : 0.f, m8 = rank >= 8 ? 1.f : 0.f;
+        float acc = 0.f;
+        for (int k0 = kbeg; k0 < kend; k0 += 32) {
+            // row-end bits of entries k0 .. k0+31
+            const uint32_t lo = __builtin_amdgcn_readfirstlane(rowend[k0 >> 5]);
+            const uint32_t hi = __builtin_amdgcn_readfirstlane(rowend[(k0 >> 5) + 1]);
+            uint32_t window = (uint32_t)((((uint64_t)hi << 32) | lo) >> (k0 & 31));
+            const int kstop = min(k0 + 32, kend);
+            if (kstop - k0 < 32) window &= (1u << (kstop - k0)) - 1u;
+            for (int k = k0; k < kstop; k += 4, window >>= 4) {
+                uint4 e1[4];
+                float pv[4], cu[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) e1[u] = ent1[k + u];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    pv[u] = *reinterpret_cast<const float*>(pbytes + (e1[u].x + jp4));
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (EK == MGK_EK_SE) {
+                        const float d = el2 - __uint_as_float(e1[u].y);
+                        float t;
+                        if (WEIGHTED) t = __builtin_fmaf(-d, d, lw2 + __uint_as_float(e1[u].z));
+                        else t = __builtin_fmaf(-d, d, lw2);  // lw2: 0, or -inf on idle lanes
+                        cu[u] = __builtin_amdgcn_exp2f(t);
+                    } else {
+                        cu[u] = WEIGHTED ? __uint_as_float(e1[u].y) : 1.f;  // A_ij
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    acc = __builtin_fmaf(cu[u], pv[u], acc);
+                    if ((window >> u) & 1u) {   // end of outer row i: sum over each inner row
+                        if (EK == MGK_EK_CONST) acc *= ke_c * el2;  // el2 = A'_i'j' (0 on idle lanes)
+                        if (NSTEPS > 0) acc = __builtin_fmaf(m1, row_shr<1>(acc), acc);
+                        if (NSTEPS > 1) acc = __builtin_fmaf(m2, row_shr<2>(acc), acc);
+                        if (NSTEPS > 2) acc = __builtin_fmaf(m4, row_shr<4>(acc), acc);
+                        if (NSTEPS > 3) acc = __builtin_fmaf(m8, row_shr<8>(acc), acc);
+                        if (last) {
+                            float* dst = reinterpret_cast<float*>(ybytes + (e1[u].w + ip4));
+                            if (ATOMIC)
+                                __hip_atomic_fetch_add(dst, acc, __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_WORKGROUP);
+                            else
+                                *dst = acc;
+                        }
+                        acc = 0.f;
+                    }
+                }
+            }
+        }
+    }
+}
+
 // ATOMIC: the inner graph has rows longer than 16 nonzeros; their runs are
 // combined with float atomics and y is cleared by its reader every iteration.
 template <int WAVES, int EPT, bool WEIGHTED, int EK, bool ATOMIC>
@@ -251,65 +321,12 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
     int flag = 1;
     while (it < max_iter) {
         // ---- XMV (Alg. 2): y_ii' = sum_{j,j'} A_ij A'_i'j' kappa_e(E_ij,E'_i'j') p_jj'
-        for (int c = 0; c < len2; c += 64) {
-            const uint4 e2 = ent2[c + lane];
-            const uint32_t ip4 = e2.x & 0xfffffu, jp4 = e2.y;
-            const uint32_t rank = (e2.x >> 20) & 0xffu;
-            const bool last = (e2.x >> 31) != 0u;
-            const float el2 = __uint_as_float(e2.z);
-            const float lw2 = __uint_as_float(e2.w);
-            const float m1 = rank >= 1 ? 1.f : 0.f, m2 = rank >= 2 ? 1.f : 0.f;
-            const float m4 = rank >= 4 ? 1.f : 0.f, m8 = rank >= 8 ? 1.f : 0.f;
-            float acc = 0.f;
-            for (int k0 = kbeg; k0 < kend; k0 += 32) {
-                // row-end bits of entries k0 .. k0+31
-                const uint32_t lo = __builtin_amdgcn_readfirstlane(rowend[k0 >> 5]);
-                const uint32_t hi = __builtin_amdgcn_readfirstlane(rowend[(k0 >> 5) + 1]);
-                uint32_t window = (uint32_t)((((uint64_t)hi << 32) | lo) >> (k0 & 31));
-                const int kstop = min(k0 + 32, kend);
-                if (kstop - k0 < 32) window &= (1u << (kstop - k0)) - 1u;
-                for (int k = k0; k < kstop; k += 4, window >>= 4) {
-                    uint4 e1[4];
-                    float pv[4], cu[4];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) e1[u] = ent1[k + u];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u)
-                        pv[u] = *reinterpret_cast<const float*>(pbytes + (e1[u].x + jp4));
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        if (EK == MGK_EK_SE) {
-                            const float d = el2 - __uint_as_float(e1[u].y);
-                            float t;
-                            if (WEIGHTED) t = __builtin_fmaf(-d, d, lw2 + __uint_as_float(e1[u].z));
-                            else t = __builtin_fmaf(-d, d, lw2);  // lw2: 0, or -inf on idle lanes
-                            cu[u] = __builtin_amdgcn_exp2f(t);
-                        } else {
-                            cu[u] = WEIGHTED ? __uint_as_float(e1[u].y) : 1.f;  // A_ij
-                        }
-                    }
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        acc = __builtin_fmaf(cu[u], pv[u], acc);
-                        if ((window >> u) & 1u) {   // end of outer row i: sum over each inner row
-                            if (EK == MGK_EK_CONST) acc *= ke_c * el2;  // el2 = A'_i'j' (0 on idle lanes)
-                            if (nsteps > 0) acc = __builtin_fmaf(m1, row_shr<1>(acc), acc);
-                            if (nsteps > 1) acc = __builtin_fmaf(m2, row_shr<2>(acc), acc);
-                            if (nsteps > 2) acc = __builtin_fmaf(m4, row_shr<4>(acc), acc);
-                            if (nsteps > 3) acc = __builtin_fmaf(m8, row_shr<8>(acc), acc);
-                            if (last) {
-                                float* dst = reinterpret_cast<float*>(ybytes + (e1[u].w + ip4));
-                                if (ATOMIC)
-                                    __hip_atomic_fetch_add(dst, acc, __ATOMIC_RELAXED,
-                                                           __HIP_MEMORY_SCOPE_WORKGROUP);
-                                else
-                                    *dst = acc;
-                            }
-                            acc = 0.f;
-                        }
-                    }
-                }
-            }
+        switch (nsteps) {
+            case 0: xmv_pass<0, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, ke_c, lane); break;
+            case 1: xmv_pass<1, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, ke_c, lane); break;
+            case 2: xmv_pass<2, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, ke_c, lane); break;
+            case 3: xmv_pass<3, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, ke_c, lane); break;
+            default: xmv_pass<4, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, ke_c, lane); break;
         }
         __syncthreads();
 
