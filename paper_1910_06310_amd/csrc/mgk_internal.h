@@ -24,6 +24,8 @@ struct MgkGraphDesc {
     int32_t roff;         // first entry in trow_ptr[] (n_tile_rows + 1 entries)
     int32_t max_deg;      // largest number of nonzeros in a row
     int32_t lane_len;     // lane slots of the graph as inner operand (multiple of 64)
+    int32_t loff;         // first lane slot of the graph in batch-wide expanded inner lists
+    int32_t reserved;
 };
 
 // Lane layout of a graph used as the inner operand of the on-chip XMV: the
@@ -53,6 +55,8 @@ struct MgkBatchDev {
     const int32_t* rowptr;   // per vertex: nonzeros of the graph in rows before it
     const int32_t* lanepos;  // per vertex: first lane slot of its row (inner operand layout)
     const int32_t* trow_ptr; // per graph: tile-row pointers into its tile list
+    const int32_t* tile_graph; // per tile: the graph it belongs to
+    int32_t n_graphs, n_tiles_total, nnz_total, lanes_total;
 };
 
 // One unit of work: solve the pair (outer graph g1 of batch X, inner graph g2
@@ -119,5 +123,43 @@ static inline MGK_HD MgkSmallPlan mgk_small_plan(int32_t n1, int32_t n2, int32_t
 #define MGK_SMALL_MAX_N (16 * 64 * 16)
 
 #define MGK_LDS_LIMIT_BYTES (160 * 1024)
+
+// ---- solver with vectors in global memory (pairs too large for LDS) ---------
+// Expanded nonzero lists of a whole batch, rebuilt per call because the label
+// scaling depends on the edge-kernel parameters:
+//   outer list (CSR order, index zoff + position): {col, scaled label or
+//     weight, log2 weight, row}
+//   inner list (lane layout, index loff + slot): {row, col | rank in run << 24
+//     | last of run << 31, scaled label or weight, log2 weight}
+struct alignas(16) MgkEntry {
+    uint32_t x, y, z, w;
+};
+
+struct MgkExpanded {
+    const MgkEntry* outer;
+    const MgkEntry* inner;
+};
+
+// One pair solved with global-memory vectors.  Vector v of the pair starts at
+// vec + v * npad floats: 0 x, 1 r, 2 p, 3 M, 4 y (also holds z).
+struct MgkLargePair {
+    int32_t g1, g2;        // outer graph (batch X), inner graph (batch Y)
+    int32_t n1, n2;
+    int64_t vec;           // offset of the pair's vectors in the scratch array (floats)
+    int32_t npad;          // n1 * n2 rounded up to 64
+    int32_t out0, out1;
+    int32_t max_iter;
+    int32_t nsteps;        // DPP steps for the inner row sums
+    int32_t atomic_rows;   // inner graph has rows longer than a lane group
+};
+
+struct MgkPairState {
+    float rho, pa, rz, rr, thresh, alpha, beta, kval;
+    int32_t iters, done, flag, pad;
+};
+
+#define MGK_LARGE_ROWS_PER_BLOCK 16   // outer rows per workgroup of the large XMV
+#define MGK_LARGE_CHUNKS_PER_WAVE 2   // 64-lane chunks of the inner layout per wave
+#define MGK_LARGE_WAVES 4
 
 #endif

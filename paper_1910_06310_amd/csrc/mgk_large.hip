@@ -1,0 +1,370 @@
+// Solver for pairs whose vectors do not fit on chip: x, r, p, M, y live in
+// global memory and each step of Alg. 1 is a kernel over all such pairs of a
+// call.  The XMV (Alg. 2) uses the same lane scheme as the on-chip solver:
+// inner nonzeros one per lane with rows in adjacent lanes, outer nonzeros
+// streamed as wave-uniform operands, one kappa_e evaluation and one gathered
+// p_jj' per nonzero pair, DPP row sums at the end of every outer row, a single
+// writer per y_ii'.  Here the entry lists come from global memory (expanded
+// once per call by mgk_expand_kernel) and p is gathered from global memory.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mgk_internal.h"
+#include "mgk_launch.h"
+
+namespace {
+
+constexpr int kWaves = MGK_LARGE_WAVES;
+constexpr int kThreads = kWaves * 64;
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v) {
+    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true);
+    return v + __int_as_float(moved);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+    v = dpp_add<0xB1>(v);
+    v = dpp_add<0x4E>(v);
+    v = dpp_add<0x141>(v);
+    v = dpp_add<0x140>(v);
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return (r0 + r1) + (r2 + r3);
+}
+
+// sum over the workgroup, then one atomic per workgroup into *dst
+__device__ __forceinline__ void block_accumulate(float v, float* dst, float* red) {
+    v = wave_sum(v);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) red[wave] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float s = 0.f;
+        for (int w = 0; w < (int)(blockDim.x >> 6); ++w) s += red[w];
+        atomicAdd(dst, s);
+    }
+    __syncthreads();
+}
+
+template <int DIST>
+__device__ __forceinline__ float row_shr(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x110 + DIST, 0xf, 0xf, true));
+}
+
+// ---- expansion of the octiles of a whole batch --------------------------------
+// idle lane slots of the inner lists: weight 0 (log2 = -inf), never the end of a run
+__global__ void mgk_fill_idle_kernel(uint4* inner, int n) {
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < n) inner[k] = make_uint4(0u, 0u, 0u, 0xff800000u);
+}
+
+// one wave per octile, lane <-> bit of the bitmap
+template <int EK>
+__global__ __launch_bounds__(256) void mgk_expand_kernel(MgkBatchDev B, MgkParams prm, uint4* outer,
+                                                         uint4* inner) {
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= B.n_tiles_total) return;
+    const MgkGraphDesc g = B.graphs[B.tile_graph[t]];
+    const MgkTile tile = B.tiles[t];
+    const int r = lane >> 3, c = lane & 7;
+    int prior = 0;  // nonzeros of this row in earlier tiles of the same tile row
+    for (int tp = t - 1; tp >= g.toff && B.tiles[tp].tr == tile.tr; --tp)
+        prior += __popc((uint32_t)(B.tiles[tp].bitmap >> (8 * r)) & 0xffu);
+    if (!((tile.bitmap >> lane) & 1ull)) return;
+    const int row = (int)tile.tr * 8 + r, col = (int)tile.tc * 8 + c;
+    const int k = g.zoff + (int)tile.nzoff + __popcll(tile.bitmap & ((1ull << lane) - 1ull));
+    const float w = B.w[k];
+    const float el = (B.e[k] - prm.e_shift) * prm.e_scale;
+    const int rp0 = B.rowptr[g.voff + row];
+    const int rp1 = (row + 1 < g.n) ? B.rowptr[g.voff + row + 1] : g.nnz;
+    const uint32_t rowbyte = (uint32_t)(tile.bitmap >> (8 * r)) & 0xffu;
+    const int rank = prior + __popc(rowbyte & ((1u << c) - 1u));
+    const float lw = __log2f(w);
+    const float lab = EK == MGK_EK_SE ? el : w;
+    outer[g.zoff + rp0 + rank] = make_uint4((uint32_t)col, __float_as_uint(lab), __float_as_uint(lw), (uint32_t)row);
+    const uint32_t run_rank = (uint32_t)rank % MGK_LANE_GROUP;
+    const uint32_t last = (rank + 1 == rp1 - rp0 || run_rank == MGK_LANE_GROUP - 1) ? 1u : 0u;
+    inner[g.loff + B.lanepos[g.voff + row] + rank] =
+        make_uint4((uint32_t)row, (uint32_t)col | (run_rank << 24) | (last << 31), __float_as_uint(lab),
+                   __float_as_uint(lw));
+}
+
+// ---- Alg. 1 set-up -------------------------------------------------------------
+__global__ __launch_bounds__(256) void mgk_large_init_kernel(MgkBatchDev X, MgkBatchDev Y,
+                                                             const MgkLargePair* pairs,
+                                                             MgkPairState* state, float* vec,
+                                                             MgkParams prm) {
+    __shared__ float red[8];
+    const MgkLargePair P = pairs[blockIdx.y];
+    const int N = P.n1 * P.n2;
+    const MgkGraphDesc g1 = X.graphs[P.g1], g2 = Y.graphs[P.g2];
+    float* x = vec + P.vec;
+    float* r = x + P.npad;
+    float* p = r + P.npad;
+    float* M = p + P.npad;
+    float* y = M + P.npad;
+    const float qq = prm.q * prm.q;
+    float s_rz = 0.f, s_bb = 0.f;
+    for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < P.npad; idx += gridDim.x * blockDim.x) {
+        float b = 0.f, z0 = 0.f, m = 1.f;
+        if (idx < N) {
+            const int i = idx / P.n2, ip = idx - i * P.n2;
+            const float d1 = X.rowsum[g1.voff + i] + prm.q, d2 = Y.rowsum[g2.voff + ip] + prm.q;
+            const float kv = (X.vlabel[g1.voff + i] == Y.vlabel[g2.voff + ip]) ? 1.f : prm.h;
+            const float dd = d1 * d2;
+            m = dd / kv;
+            b = dd * qq;
+            z0 = kv * qq;
+        }
+        x[idx] = 0.f; r[idx] = b; p[idx] = z0; M[idx] = m; y[idx] = 0.f;
+        s_rz = __builtin_fmaf(b, z0, s_rz);
+        s_bb = __builtin_fmaf(b, b, s_bb);
+    }
+    block_accumulate(s_rz, &state[blockIdx.y].rho, red);
+    block_accumulate(s_bb, &state[blockIdx.y].thresh, red);  // scaled by rtol^2 in the first scalar step
+}
+
+// ---- XMV ---------------------------------------------------------------------------
+// grid.y = pair; grid.x enumerates (outer row block, group of inner chunks).
+template <bool WEIGHTED, int EK>
+__global__ __launch_bounds__(kThreads) void mgk_large_xmv_kernel(
+    MgkBatchDev X, MgkBatchDev Y, MgkExpanded EX, MgkExpanded EY, const MgkLargePair* pairs,
+    const MgkPairState* state, float* vec, float ke_c) {
+    if (state[blockIdx.y].done) return;
+    const MgkLargePair P = pairs[blockIdx.y];
+    const MgkGraphDesc g1 = X.graphs[P.g1], g2 = Y.graphs[P.g2];
+    const int chunks = g2.lane_len / 64;
+    constexpr int CPB = kWaves * MGK_LARGE_CHUNKS_PER_WAVE;   // chunks per workgroup
+    const int chunk_groups = (chunks + CPB - 1) / CPB;
+    const int row_blocks = (P.n1 + MGK_LARGE_ROWS_PER_BLOCK - 1) / MGK_LARGE_ROWS_PER_BLOCK;
+    if ((int)blockIdx.x >= row_blocks * chunk_groups) return;
+    const int rb = blockIdx.x / chunk_groups, cg = blockIdx.x - rb * chunk_groups;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int row0 = rb * MGK_LARGE_ROWS_PER_BLOCK;
+    const int row1 = min(row0 + MGK_LARGE_ROWS_PER_BLOCK, P.n1);
+    const float* p = vec + P.vec + 2 * (int64_t)P.npad;
+    float* y = vec + P.vec + 4 * (int64_t)P.npad;
+    const uint4* outer = reinterpret_cast<const uint4*>(EX.outer) + g1.zoff;
+    const uint4* inner = reinterpret_cast<const uint4*>(EY.inner) + g2.loff;
+    const int32_t* rowptr1 = X.rowptr + g1.voff;
+    const int n2 = P.n2;
+
+    for (int cc = 0; cc < MGK_LARGE_CHUNKS_PER_WAVE; ++cc) {
+        const int c = (cg * kWaves + wave) * MGK_LARGE_CHUNKS_PER_WAVE + cc;
+        if (c >= chunks) break;
+        const uint4 e2 = inner[c * 64 + lane];
+        const int ip = (int)e2.x, jp = (int)(e2.y & 0xffffffu);
+        const uint32_t rank = (e2.y >> 24) & 0xfu;
+        const bool last = (e2.y >> 31) != 0u;
+        const float el2 = __uint_as_float(e2.z);
+        const float lw2 = __uint_as_float(e2.w);
+        const float m1 = rank >= 1 ? 1.f : 0.f, m2 = rank >= 2 ? 1.f : 0.f;
+        const float m4 = rank >= 4 ? 1.f : 0.f, m8 = rank >= 8 ? 1.f : 0.f;
+        for (int i = row0; i < row1; ++i) {
+            const int kb = rowptr1[i];
+            const int ke = (i + 1 < P.n1) ? rowptr1[i + 1] : g1.nnz;
+            if (kb == ke) continue;
+            float acc = 0.f;
+            for (int k = kb; k < ke; ++k) {
+                const uint4 e1 = outer[k];   // wave-uniform
+                const float pv = p[(int64_t)e1.x * n2 + jp];
+                if (EK == MGK_EK_SE) {
+                    const float d = el2 - __uint_as_float(e1.y);
+                    float t;
+                    if (WEIGHTED) t = __builtin_fmaf(-d, d, lw2 + __uint_as_float(e1.z));
+                    else t = __builtin_fmaf(-d, d, lw2);
+                    acc = __builtin_fmaf(__builtin_amdgcn_exp2f(t), pv, acc);
+                } else {
+                    acc = __builtin_fmaf(WEIGHTED ? __uint_as_float(e1.y) : 1.f, pv, acc);
+                }
+            }
+            if (EK == MGK_EK_CONST) acc *= ke_c * el2;
+            if (P.nsteps > 0) acc = __builtin_fmaf(m1, row_shr<1>(acc), acc);
+            if (P.nsteps > 1) acc = __builtin_fmaf(m2, row_shr<2>(acc), acc);
+            if (P.nsteps > 2) acc = __builtin_fmaf(m4, row_shr<4>(acc), acc);
+            if (P.nsteps > 3) acc = __builtin_fmaf(m8, row_shr<8>(acc), acc);
+            if (last) {
+                float* dst = y + ((int64_t)i * n2 + ip);
+                if (P.atomic_rows) atomicAdd(dst, acc);
+                else *dst = acc;
+            }
+        }
+    }
+}
+
+// ---- p^T a with a = M p - y ---------------------------------------------------------
+__global__ __launch_bounds__(256) void mgk_large_dot_kernel(const MgkLargePair* pairs,
+                                                            MgkPairState* state, const float* vec) {
+    __shared__ float red[8];
+    if (state[blockIdx.y].done) return;
+    const MgkLargePair P = pairs[blockIdx.y];
+    const float* p = vec + P.vec + 2 * (int64_t)P.npad;
+    const float* M = p + P.npad;
+    const float* y = M + P.npad;
+    float s = 0.f;
+    for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < P.npad; idx += gridDim.x * blockDim.x) {
+        const float pv = p[idx];
+        s = __builtin_fmaf(pv, __builtin_fmaf(M[idx], pv, -y[idx]), s);
+    }
+    block_accumulate(s, &state[blockIdx.y].pa, red);
+}
+
+// scalar step 1: alpha = rho / p^T a
+__global__ void mgk_large_scalar1_kernel(MgkPairState* state, int n_pairs, float rtol2, int first) {
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= n_pairs) return;
+    MgkPairState& s = state[k];
+    if (first) s.thresh *= rtol2;   // holds b^T b after the set-up kernel
+    if (s.done) return;
+    s.alpha = s.rho / s.pa;
+    s.rz = 0.f;
+    s.rr = 0.f;
+}
+
+// ---- x += alpha p; r -= alpha a; z = M^{-1} r (stored over y); rho' = r^T z; r^T r ----
+__global__ __launch_bounds__(256) void mgk_large_update_kernel(const MgkLargePair* pairs,
+                                                               MgkPairState* state, float* vec) {
+    __shared__ float red[8];
+    if (state[blockIdx.y].done) return;
+    const MgkLargePair P = pairs[blockIdx.y];
+    const float alpha = state[blockIdx.y].alpha;
+    float* x = vec + P.vec;
+    float* r = x + P.npad;
+    const float* p = r + P.npad;
+    const float* M = p + P.npad;
+    float* y = const_cast<float*>(M) + P.npad;
+    float s_rz = 0.f, s_rr = 0.f;
+    for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < P.npad; idx += gridDim.x * blockDim.x) {
+        const float pv = p[idx], m = M[idx];
+        const float av = __builtin_fmaf(m, pv, -y[idx]);
+        x[idx] = __builtin_fmaf(alpha, pv, x[idx]);
+        const float rv = __builtin_fmaf(-alpha, av, r[idx]);
+        r[idx] = rv;
+        const float zv = rv / m;
+        y[idx] = zv;
+        s_rz = __builtin_fmaf(rv, zv, s_rz);
+        s_rr = __builtin_fmaf(rv, rv, s_rr);
+    }
+    block_accumulate(s_rz, &state[blockIdx.y].rz, red);
+    block_accumulate(s_rr, &state[blockIdx.y].rr, red);
+}
+
+// scalar step 2: convergence test, beta = rho' / rho
+__global__ void mgk_large_scalar2_kernel(const MgkLargePair* pairs, MgkPairState* state, int n_pairs,
+                                         int* n_active) {
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= n_pairs) return;
+    MgkPairState& s = state[k];
+    if (s.done) return;
+    s.iters += 1;
+    s.pa = 0.f;
+    if (s.rr <= s.thresh) { s.done = 1; s.flag = 0; atomicSub(n_active, 1); return; }
+    if (s.iters >= pairs[k].max_iter) { s.done = 1; s.flag = 1; atomicSub(n_active, 1); return; }
+    s.beta = s.rz / s.rho;
+    s.rho = s.rz;
+}
+
+// ---- p = z + beta p; y cleared for the next product ------------------------------------
+__global__ __launch_bounds__(256) void mgk_large_pupdate_kernel(const MgkLargePair* pairs,
+                                                                const MgkPairState* state, float* vec) {
+    if (state[blockIdx.y].done) return;
+    const MgkLargePair P = pairs[blockIdx.y];
+    const float beta = state[blockIdx.y].beta;
+    float* p = vec + P.vec + 2 * (int64_t)P.npad;
+    float* y = p + 2 * (int64_t)P.npad;
+    for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < P.npad; idx += gridDim.x * blockDim.x) {
+        p[idx] = __builtin_fmaf(beta, p[idx], y[idx]);
+        y[idx] = 0.f;
+    }
+}
+
+// ---- K = p_x^T x ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void mgk_large_final_kernel(MgkBatchDev X, MgkBatchDev Y,
+                                                              const MgkLargePair* pairs,
+                                                              MgkPairState* state, const float* vec) {
+    __shared__ float red[8];
+    const MgkLargePair P = pairs[blockIdx.y];
+    const int N = P.n1 * P.n2;
+    const MgkGraphDesc g1 = X.graphs[P.g1], g2 = Y.graphs[P.g2];
+    const float* x = vec + P.vec;
+    float s = 0.f;
+    for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < N; idx += gridDim.x * blockDim.x) {
+        const int i = idx / P.n2, ip = idx - i * P.n2;
+        s = __builtin_fmaf(X.start[g1.voff + i] * Y.start[g2.voff + ip], x[idx], s);
+    }
+    block_accumulate(s, &state[blockIdx.y].kval, red);
+}
+
+__global__ void mgk_large_store_kernel(const MgkLargePair* pairs, const MgkPairState* state,
+                                       int n_pairs, float* K, int32_t* iters, int32_t* flags) {
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= n_pairs) return;
+    const MgkLargePair P = pairs[k];
+    const MgkPairState s = state[k];
+    K[P.out0] = s.kval;
+    if (P.out1 >= 0) K[P.out1] = s.kval;
+    if (iters) { iters[P.out0] = s.iters; if (P.out1 >= 0) iters[P.out1] = s.iters; }
+    if (flags) { flags[P.out0] = s.flag; if (P.out1 >= 0) flags[P.out1] = s.flag; }
+}
+
+}  // namespace
+
+// ---- launchers -----------------------------------------------------------------------------
+hipError_t mgk_launch_expand(const MgkBatchDev& B, const MgkParams& prm, MgkEntry* outer_, MgkEntry* inner_,
+                             hipStream_t stream) {
+    uint4* outer = reinterpret_cast<uint4*>(outer_);
+    uint4* inner = reinterpret_cast<uint4*>(inner_);
+    if (B.lanes_total > 0)
+        hipLaunchKernelGGL(mgk_fill_idle_kernel, dim3((B.lanes_total + 255) / 256), dim3(256), 0, stream,
+                           inner, B.lanes_total);
+    if (B.n_tiles_total > 0) {
+        const dim3 grid((B.n_tiles_total + 3) / 4);
+        if (prm.edge_kernel == MGK_EK_SE)
+            hipLaunchKernelGGL(mgk_expand_kernel<MGK_EK_SE>, grid, dim3(256), 0, stream, B, prm, outer, inner);
+        else
+            hipLaunchKernelGGL(mgk_expand_kernel<MGK_EK_CONST>, grid, dim3(256), 0, stream, B, prm, outer, inner);
+    }
+    return hipGetLastError();
+}
+
+hipError_t mgk_launch_large_init(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkLargePair* pairs,
+                                 MgkPairState* state, float* vec, const MgkParams& prm, int n_pairs,
+                                 int vec_blocks, hipStream_t stream) {
+    hipLaunchKernelGGL(mgk_large_init_kernel, dim3(vec_blocks, n_pairs), dim3(256), 0, stream, X, Y, pairs,
+                       state, vec, prm);
+    return hipGetLastError();
+}
+
+hipError_t mgk_launch_large_iteration(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkExpanded& EX,
+                                      const MgkExpanded& EY, const MgkLargePair* pairs,
+                                      MgkPairState* state, float* vec, const MgkParams& prm,
+                                      bool weighted, int n_pairs, int xmv_blocks, int vec_blocks,
+                                      int* n_active, bool first, hipStream_t stream) {
+    const dim3 gx(xmv_blocks, n_pairs), gv(vec_blocks, n_pairs), gs((n_pairs + 63) / 64);
+#define MGK_XMV(WT, EKV) \
+    hipLaunchKernelGGL((mgk_large_xmv_kernel<WT, EKV>), gx, dim3(kThreads), 0, stream, X, Y, EX, EY, pairs, state, vec, prm.ke_const)
+    if (prm.edge_kernel == MGK_EK_SE) { if (weighted) MGK_XMV(true, MGK_EK_SE); else MGK_XMV(false, MGK_EK_SE); }
+    else { if (weighted) MGK_XMV(true, MGK_EK_CONST); else MGK_XMV(false, MGK_EK_CONST); }
+#undef MGK_XMV
+    hipLaunchKernelGGL(mgk_large_dot_kernel, gv, dim3(256), 0, stream, pairs, state, vec);
+    hipLaunchKernelGGL(mgk_large_scalar1_kernel, gs, dim3(64), 0, stream, state, n_pairs, prm.rtol2, first ? 1 : 0);
+    hipLaunchKernelGGL(mgk_large_update_kernel, gv, dim3(256), 0, stream, pairs, state, vec);
+    hipLaunchKernelGGL(mgk_large_scalar2_kernel, gs, dim3(64), 0, stream, pairs, state, n_pairs, n_active);
+    hipLaunchKernelGGL(mgk_large_pupdate_kernel, gv, dim3(256), 0, stream, pairs, state, vec);
+    return hipGetLastError();
+}
+
+hipError_t mgk_launch_large_final(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkLargePair* pairs,
+                                  MgkPairState* state, const float* vec, int n_pairs, int vec_blocks,
+                                  float* K, int32_t* iters, int32_t* flags, hipStream_t stream) {
+    hipLaunchKernelGGL(mgk_large_final_kernel, dim3(vec_blocks, n_pairs), dim3(256), 0, stream, X, Y, pairs,
+                       state, vec);
+    hipLaunchKernelGGL(mgk_large_store_kernel, dim3((n_pairs + 63) / 64), dim3(64), 0, stream, pairs, state,
+                       n_pairs, K, iters, flags);
+    return hipGetLastError();
+}

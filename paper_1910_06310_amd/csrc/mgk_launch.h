@@ -39,4 +39,25 @@ static inline hipError_t mgk_launch_small(int waves, int ept, bool weighted, boo
     }
 }
 
+// ---- solver with vectors in global memory (mgk_large.hip) --------------------
+// Expand every octile of batch B into the outer (CSR order) and inner (lane
+// layout) entry lists; `outer` holds B.nnz_total entries, `inner` B.lanes_total.
+hipError_t mgk_launch_expand(const MgkBatchDev& B, const MgkParams& prm, MgkEntry* outer, MgkEntry* inner,
+                             hipStream_t stream);
+// Set-up of Alg. 1 for n_pairs pairs (state must be zero-filled before).
+hipError_t mgk_launch_large_init(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkLargePair* pairs,
+                                 MgkPairState* state, float* vec, const MgkParams& prm, int n_pairs,
+                                 int vec_blocks, hipStream_t stream);
+// One iteration of Alg. 1 for all pairs that have not stopped; *n_active is
+// decremented for every pair that stops.
+hipError_t mgk_launch_large_iteration(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkExpanded& EX,
+                                      const MgkExpanded& EY, const MgkLargePair* pairs,
+                                      MgkPairState* state, float* vec, const MgkParams& prm,
+                                      bool weighted, int n_pairs, int xmv_blocks, int vec_blocks,
+                                      int* n_active, bool first, hipStream_t stream);
+// K = p_x^T x and the per-pair outputs.
+hipError_t mgk_launch_large_final(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkLargePair* pairs,
+                                  MgkPairState* state, const float* vec, int n_pairs, int vec_blocks,
+                                  float* K, int32_t* iters, int32_t* flags, hipStream_t stream);
+
 #endif
