@@ -25,6 +25,10 @@
  *    has synchronised that stream.
  *  - A ctx is bound to one device and is not thread-safe.  Batches belong to
  *    the ctx that loaded them.
+ *  - Calls that include pairs too large for the on-chip solver synchronise the
+ *    stream before returning (the host watches how many of them still iterate)
+ *    and allocate device scratch owned by the ctx (5 vectors of n n' floats per
+ *    such pair, plus expanded nonzero lists of the batches).
  *  - Non-convergence is data, not an error: the pair's flag is set to 1 and the
  *    value of the last iterate is still written.
  *  - Precision: fp32 on the device.  Product index of (i,i') is i*n'+i'.
@@ -84,6 +88,11 @@ mgk_status mgk_set_tile_path(mgk_ctx* ctx, int32_t mode);
  * product size).  A pair too large for the requested size gets the next
  * larger one that fits. */
 mgk_status mgk_set_launch(mgk_ctx* ctx, int32_t waves_per_pair);
+/* Pairs with n n' <= max_product are solved on chip (one workgroup per pair,
+ * vectors in LDS and registers); larger pairs keep their vectors in global
+ * memory and run one kernel per step of Alg. 1.  Default and upper bound:
+ * 16384.  0 sends every pair to the global-memory solver. */
+mgk_status mgk_set_onchip_limit(mgk_ctx* ctx, int32_t max_product);
 
 /* ---- graphs -----------------------------------------------------------------
  * Load n_graphs graphs given in flat host arrays (all caller-owned, copied):

@@ -18,6 +18,7 @@ OBJ_DIR = os.path.join(HERE, "_build")
 # (source, output tag, extra flags); the on-chip solver is compiled once per
 # workgroup size so the translation units build in parallel
 DEVICE_SOURCES = [("mgk_small.hip", "w%d" % w, ["-DMGK_SMALL_WAVES=%d" % w]) for w in (1, 2, 4, 8, 16)]
+DEVICE_SOURCES.append(("mgk_large.hip", "all", []))
 HOST_SOURCES = ["mgk_host.cpp", "mgk_reorder.cpp"]
 
 # packed fp32 instructions are switched off on purpose for the test machines

@@ -34,6 +34,14 @@ struct JobList {
     MgkJob* dev = nullptr;
     int64_t n = 0;
     std::vector<JobBin> bins;
+    // pairs whose vectors do not fit on chip: [0] outer graph from X, [1] from Y
+    std::vector<MgkLargePair> large[2];
+};
+
+// growable device allocation owned by a context
+struct DevBuf {
+    void* p = nullptr;
+    size_t cap = 0;
 };
 
 }  // namespace
@@ -55,6 +63,8 @@ struct mgk_batch {
     MgkBatchDev dev{};
     JobList gram_jobs;
     int gram_jobs_waves = 0;       // waves_per_pair setting the list was built for
+    int gram_jobs_max_iter = 0;    // max_iter setting the list was built for
+    int gram_jobs_limit = 0;       // on-chip limit the list was built for
 };
 
 struct mgk_ctx {
@@ -65,10 +75,15 @@ struct mgk_ctx {
     int max_iter = 0;
     int tile_path = MGK_TILE_AUTO;
     int waves = 0;
+    int onchip_limit = MGK_SMALL_MAX_N;  // largest n n' given to the on-chip solver
     JobList pair_jobs;          // reused by mgk_pairs
     int64_t pair_jobs_cap = 0;
     hipStream_t pair_jobs_stream = nullptr;
     bool pair_jobs_busy = false;
+    // scratch of the global-memory solver
+    DevBuf exp_outer[2], exp_inner[2];  // expanded entry lists of batch X / batch Y
+    DevBuf vec, lpairs, lstate, lactive;
+    int* active_host = nullptr;         // pinned
 };
 
 namespace {
@@ -132,7 +147,8 @@ struct PairPlan {
     int waves = 0, ept = 0;  // 0: does not fit
 };
 
-PairPlan plan_pair(const MgkGraphDesc& a, const MgkGraphDesc& b, bool may_swap, int forced_waves) {
+PairPlan plan_pair(const MgkGraphDesc& a, const MgkGraphDesc& b, bool may_swap, int forced_waves,
+                   int onchip_limit) {
     // wave iterations of one XMV: outer nonzeros x 64-lane chunks of the inner layout
     auto passes = [](const MgkGraphDesc& o, const MgkGraphDesc& i) {
         return (int64_t)o.nnz * (i.lane_len / 64) + 2 * (int64_t)o.n * (i.lane_len / 64);
@@ -144,7 +160,7 @@ PairPlan plan_pair(const MgkGraphDesc& a, const MgkGraphDesc& b, bool may_swap, 
     pl.atomic_rows = pl.swap ? swp_atomic : keep_atomic;
     const int64_t N = (int64_t)a.n * b.n;
     pl.cost = (pl.swap ? swp : keep) * 64 + 16 * N;
-    if (N > MGK_SMALL_MAX_N) return pl;
+    if (N > MGK_SMALL_MAX_N || N > onchip_limit) return pl;
     if (forced_waves > 0) {  // requested workgroup size, doubled until the pair fits
         for (int w = forced_waves; w <= 16 && pl.waves == 0; w *= 2)
             for (int e : kEpts)
@@ -215,6 +231,113 @@ mgk_status build_job_list(mgk_ctx* ctx, std::vector<HostJob>& jobs, JobList& out
     return MGK_OK;
 }
 
+mgk_status ensure(mgk_ctx* ctx, DevBuf& b, size_t bytes) {
+    if (bytes <= b.cap) return MGK_OK;
+    if (b.p) MGK_HIP(ctx, hipFree(b.p));
+    b.p = nullptr;
+    b.cap = 0;
+    hipError_t e = hipMalloc(&b.p, bytes);
+    if (e != hipSuccess)
+        return fail(ctx, MGK_ENOMEM, "device allocation of %zu bytes failed: %s", bytes, hipGetErrorString(e));
+    b.cap = bytes;
+    return MGK_OK;
+}
+
+// Plan of one pair for the global-memory solver (any size).
+MgkLargePair plan_large(const MgkGraphDesc& a, const MgkGraphDesc& b, int32_t ia, int32_t ib, bool* swap,
+                        int max_iter_param) {
+    auto passes = [](const MgkGraphDesc& o, const MgkGraphDesc& i) {
+        return (int64_t)o.nnz * (i.lane_len / 64) + 2 * (int64_t)o.n * (i.lane_len / 64);
+    };
+    const bool keep_atomic = b.max_deg > MGK_LANE_GROUP, swp_atomic = a.max_deg > MGK_LANE_GROUP;
+    *swap = keep_atomic != swp_atomic ? keep_atomic : passes(b, a) < passes(a, b);
+    const MgkGraphDesc& o = *swap ? b : a;
+    const MgkGraphDesc& i = *swap ? a : b;
+    MgkLargePair P{};
+    P.g1 = *swap ? ib : ia;
+    P.g2 = *swap ? ia : ib;
+    P.n1 = o.n;
+    P.n2 = i.n;
+    const int64_t N = (int64_t)o.n * i.n;
+    P.npad = (int32_t)((N + 63) & ~(int64_t)63);
+    P.max_iter = max_iter_param > 0 ? max_iter_param : (int32_t)std::min<int64_t>(2 * N, 1000);
+    P.nsteps = i.max_deg <= 1 ? 0 : i.max_deg <= 2 ? 1 : i.max_deg <= 4 ? 2 : i.max_deg <= 8 ? 3 : 4;
+    P.atomic_rows = i.max_deg > MGK_LANE_GROUP ? 1 : 0;
+    return P;
+}
+
+// Run Alg. 1 with global-memory vectors for a list of pairs (outer graphs from
+// A, inner from B).  Synchronises the stream: the host watches the number of
+// pairs still iterating.
+mgk_status solve_large(mgk_ctx* ctx, const mgk_batch* A, const mgk_batch* Bb, int ia, int ib,
+                       std::vector<MgkLargePair> pairs, float* K, int32_t* iters, int32_t* flags,
+                       hipStream_t stream, const MgkParams& prm, bool weighted) {
+    const int n_pairs = (int)pairs.size();
+    if (n_pairs == 0) return MGK_OK;
+    int64_t total = 0;
+    int max_npad = 0, max_iter = 0, xmv_blocks = 1;
+    constexpr int CPB = MGK_LARGE_WAVES * MGK_LARGE_CHUNKS_PER_WAVE;
+    for (MgkLargePair& P : pairs) {
+        P.vec = total;
+        total += 5 * (int64_t)P.npad;
+        max_npad = std::max(max_npad, P.npad);
+        max_iter = std::max(max_iter, P.max_iter);
+        const int chunks = Bb->graphs[P.g2].lane_len / 64;
+        const int rb = (P.n1 + MGK_LARGE_ROWS_PER_BLOCK - 1) / MGK_LARGE_ROWS_PER_BLOCK;
+        xmv_blocks = std::max(xmv_blocks, rb * ((chunks + CPB - 1) / CPB));
+    }
+    const int vec_blocks = std::max(1, std::min(2048, (max_npad + 1023) / 1024));
+    mgk_status st;
+    if ((st = ensure(ctx, ctx->vec, (size_t)total * sizeof(float))) != MGK_OK) return st;
+    if ((st = ensure(ctx, ctx->lpairs, (size_t)n_pairs * sizeof(MgkLargePair))) != MGK_OK) return st;
+    if ((st = ensure(ctx, ctx->lstate, (size_t)n_pairs * sizeof(MgkPairState))) != MGK_OK) return st;
+    if ((st = ensure(ctx, ctx->lactive, 64)) != MGK_OK) return st;
+    if (!ctx->active_host) MGK_HIP(ctx, hipHostMalloc((void**)&ctx->active_host, 64, hipHostMallocDefault));
+
+    // expanded entry lists of the batches involved (label scaling depends on the parameters)
+    const mgk_batch* bt[2] = {A, Bb};
+    const int slot[2] = {ia, ib};
+    MgkExpanded ex[2];
+    for (int k = 0; k < 2; ++k) {
+        if (k == 1 && Bb == A) { ex[1] = ex[0]; break; }
+        DevBuf& bo = ctx->exp_outer[slot[k]];
+        DevBuf& bi = ctx->exp_inner[slot[k]];
+        if ((st = ensure(ctx, bo, std::max<size_t>(16, (size_t)bt[k]->dev.nnz_total * sizeof(MgkEntry)))) != MGK_OK) return st;
+        if ((st = ensure(ctx, bi, std::max<size_t>(16, (size_t)bt[k]->dev.lanes_total * sizeof(MgkEntry)))) != MGK_OK) return st;
+        hipError_t e = mgk_launch_expand(bt[k]->dev, prm, (MgkEntry*)bo.p, (MgkEntry*)bi.p, stream);
+        if (e != hipSuccess) return fail(ctx, MGK_EDEVICE, "expand launch failed: %s", hipGetErrorString(e));
+        ex[k].outer = (const MgkEntry*)bo.p;
+        ex[k].inner = (const MgkEntry*)bi.p;
+    }
+
+    MgkLargePair* dpairs = (MgkLargePair*)ctx->lpairs.p;
+    MgkPairState* dstate = (MgkPairState*)ctx->lstate.p;
+    int* dactive = (int*)ctx->lactive.p;
+    float* vec = (float*)ctx->vec.p;
+    MGK_HIP(ctx, hipMemcpyAsync(dpairs, pairs.data(), (size_t)n_pairs * sizeof(MgkLargePair),
+                                hipMemcpyHostToDevice, stream));
+    MGK_HIP(ctx, hipMemsetAsync(dstate, 0, (size_t)n_pairs * sizeof(MgkPairState), stream));
+    *ctx->active_host = n_pairs;
+    MGK_HIP(ctx, hipMemcpyAsync(dactive, ctx->active_host, sizeof(int), hipMemcpyHostToDevice, stream));
+    MGK_HIP(ctx, hipStreamSynchronize(stream));  // `pairs` and active_host are reused below
+    hipError_t e = mgk_launch_large_init(A->dev, Bb->dev, dpairs, dstate, vec, prm, n_pairs, vec_blocks, stream);
+    if (e != hipSuccess) return fail(ctx, MGK_EDEVICE, "init launch failed: %s", hipGetErrorString(e));
+    const int check_every = 4;
+    for (int it = 0; it < max_iter; ++it) {
+        e = mgk_launch_large_iteration(A->dev, Bb->dev, ex[0], ex[1], dpairs, dstate, vec, prm, weighted,
+                                       n_pairs, xmv_blocks, vec_blocks, dactive, it == 0, stream);
+        if (e != hipSuccess) return fail(ctx, MGK_EDEVICE, "iteration launch failed: %s", hipGetErrorString(e));
+        if ((it + 1) % check_every == 0 || it + 1 == max_iter) {
+            MGK_HIP(ctx, hipMemcpyAsync(ctx->active_host, dactive, sizeof(int), hipMemcpyDeviceToHost, stream));
+            MGK_HIP(ctx, hipStreamSynchronize(stream));
+            if (*ctx->active_host <= 0) break;
+        }
+    }
+    e = mgk_launch_large_final(A->dev, Bb->dev, dpairs, dstate, vec, n_pairs, vec_blocks, K, iters, flags, stream);
+    if (e != hipSuccess) return fail(ctx, MGK_EDEVICE, "final launch failed: %s", hipGetErrorString(e));
+    return MGK_OK;
+}
+
 mgk_status launch_jobs(mgk_ctx* ctx, const mgk_batch* X, const mgk_batch* Y, const JobList& jl,
                        float* K, int32_t* iters, int32_t* flags, hipStream_t stream) {
     const MgkParams prm = make_params(ctx, X);
@@ -232,7 +355,9 @@ mgk_status launch_jobs(mgk_ctx* ctx, const mgk_batch* X, const mgk_batch* Y, con
             done += chunk;
         }
     }
-    return MGK_OK;
+    mgk_status st = solve_large(ctx, X, Y, 0, 1, jl.large[0], K, iters, flags, stream, prm, weighted);
+    if (st != MGK_OK) return st;
+    return solve_large(ctx, Y, X, 1, 0, jl.large[1], K, iters, flags, stream, prm, weighted);
 }
 
 }  // namespace
@@ -259,6 +384,10 @@ mgk_status mgk_create(mgk_ctx** out, int device) {
 void mgk_destroy(mgk_ctx* ctx) {
     if (!ctx) return;
     if (ctx->pair_jobs.dev) (void)hipFree(ctx->pair_jobs.dev);
+    for (DevBuf* b : {&ctx->exp_outer[0], &ctx->exp_outer[1], &ctx->exp_inner[0], &ctx->exp_inner[1],
+                      &ctx->vec, &ctx->lpairs, &ctx->lstate, &ctx->lactive})
+        if (b->p) (void)hipFree(b->p);
+    if (ctx->active_host) (void)hipHostFree(ctx->active_host);
     delete ctx;
 }
 
@@ -310,6 +439,13 @@ mgk_status mgk_set_tile_path(mgk_ctx* ctx, int32_t mode) {
     return MGK_OK;
 }
 
+mgk_status mgk_set_onchip_limit(mgk_ctx* ctx, int32_t max_product) {
+    if (!ctx) return MGK_EINVAL;
+    if (max_product < 0) return fail(ctx, MGK_EINVAL, "on-chip limit must be >= 0, got %d", max_product);
+    ctx->onchip_limit = std::min<int32_t>(max_product, MGK_SMALL_MAX_N);
+    return MGK_OK;
+}
+
 mgk_status mgk_set_launch(mgk_ctx* ctx, int32_t waves_per_pair) {
     if (!ctx) return MGK_EINVAL;
     const int w = waves_per_pair;
@@ -349,7 +485,8 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
     B->graphs.resize(n_graphs);
     B->vtx_off.assign(vtx_off, vtx_off + n_graphs + 1);
     B->perm.resize((size_t)tot_v);
-    std::vector<int32_t> vlabel((size_t)tot_v), rowptr((size_t)tot_v), lanepos((size_t)tot_v), trow_ptr;
+    std::vector<int32_t> vlabel((size_t)tot_v), rowptr((size_t)tot_v), lanepos((size_t)tot_v), trow_ptr, tile_graph;
+    int64_t lanes_total = 0;
     std::vector<float> rowsum((size_t)tot_v), start((size_t)tot_v);
     B->w.reserve((size_t)(2 * tot_e));
     B->e.reserve((size_t)(2 * tot_e));
@@ -487,6 +624,11 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
         }
         gd.max_deg = max_deg;
         gd.lane_len = (slot + 63) & ~63;
+        gd.loff = (int32_t)lanes_total;
+        gd.reserved = 0;
+        lanes_total += gd.lane_len;
+        if (lanes_total >= (int64_t)1 << 31) return fail(ctx, MGK_ELIMIT, "batch too large for 32-bit offsets");
+        tile_graph.resize(B->tiles.size(), g);
     }
     B->n_vertices = tot_v;
     B->nnz = (int64_t)B->w.size();
@@ -505,6 +647,11 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
     const size_t o_rp = append_bytes(blob, rowptr);
     const size_t o_lp = append_bytes(blob, lanepos);
     const size_t o_tr = append_bytes(blob, trow_ptr);
+    const size_t o_tg = append_bytes(blob, tile_graph);
+    B->dev.n_graphs = n_graphs;
+    B->dev.n_tiles_total = (int32_t)B->tiles.size();
+    B->dev.nnz_total = (int32_t)B->w.size();
+    B->dev.lanes_total = (int32_t)lanes_total;
     if (ctx->device < 0) {  // host-only context: packed form is kept for inspection only
         guard.b = nullptr;
         *out = B;
@@ -524,6 +671,7 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
     B->dev.rowptr = reinterpret_cast<const int32_t*>(base + o_rp);
     B->dev.lanepos = reinterpret_cast<const int32_t*>(base + o_lp);
     B->dev.trow_ptr = reinterpret_cast<const int32_t*>(base + o_tr);
+    B->dev.tile_graph = reinterpret_cast<const int32_t*>(base + o_tg);
 
     guard.b = nullptr;
     *out = B;
@@ -584,7 +732,9 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
     MGK_HIP(ctx, hipSetDevice(ctx->device));
     const int64_t G = batch->n_graphs;
     if (G * G >= (int64_t)1 << 31) return fail(ctx, MGK_ELIMIT, "Gram matrix too large for 32-bit output indices");
-    if (batch->gram_jobs.dev != nullptr && batch->gram_jobs_waves != ctx->waves) {
+    if (batch->gram_jobs.dev != nullptr &&
+        (batch->gram_jobs_waves != ctx->waves || batch->gram_jobs_max_iter != ctx->max_iter ||
+         batch->gram_jobs_limit != ctx->onchip_limit)) {
         MGK_HIP(ctx, hipStreamSynchronize(stream));  // launch shape changed: rebuild the job list
         MGK_HIP(ctx, hipFree(batch->gram_jobs.dev));
         batch->gram_jobs.dev = nullptr;
@@ -593,9 +743,11 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
         // a4: job list, one job per unordered pair, kept with the batch
         std::vector<HostJob> jobs;
         jobs.reserve((size_t)(G * (G + 1) / 2));
+        batch->gram_jobs.large[0].clear();
+        batch->gram_jobs.large[1].clear();
         for (int64_t i = 0; i < G; ++i)
             for (int64_t j = i; j < G; ++j) {
-                const PairPlan pl = plan_pair(batch->graphs[i], batch->graphs[j], true, ctx->waves);
+                const PairPlan pl = plan_pair(batch->graphs[i], batch->graphs[j], true, ctx->waves, ctx->onchip_limit);
                 HostJob hj;
                 hj.job.g1 = (int32_t)(pl.swap ? j : i);
                 hj.job.g2 = (int32_t)(pl.swap ? i : j);
@@ -607,13 +759,22 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
                 hj.ept = (int16_t)pl.ept;
                 hj.atomic_rows = pl.atomic_rows;
                 hj.swapped = false;  // one batch: swapping is done through the indices
-                if (pl.waves == 0)
-                    return fail(ctx, MGK_ELIMIT, "pair (%lld, %lld) with %lld product vertices does not fit the on-chip solver",
-                                (long long)i, (long long)j, (long long)batch->graphs[i].n * batch->graphs[j].n);
+                if (pl.waves == 0) {  // vectors do not fit on chip
+                    if ((int64_t)batch->graphs[i].n * batch->graphs[j].n >= ((int64_t)1 << 31) - 64)
+                        return fail(ctx, MGK_ELIMIT, "pair (%lld, %lld) is too large", (long long)i, (long long)j);
+                    bool sw;
+                    MgkLargePair P = plan_large(batch->graphs[i], batch->graphs[j], (int32_t)i, (int32_t)j, &sw, ctx->max_iter);
+                    P.out0 = hj.job.out0;
+                    P.out1 = hj.job.out1;
+                    batch->gram_jobs.large[0].push_back(P);
+                    continue;
+                }
                 jobs.push_back(hj);
             }
         mgk_status st = build_job_list(ctx, jobs, batch->gram_jobs, stream, nullptr);
         batch->gram_jobs_waves = ctx->waves;
+        batch->gram_jobs_max_iter = ctx->max_iter;
+        batch->gram_jobs_limit = ctx->onchip_limit;
         if (st != MGK_OK) return st;
     }
     return launch_jobs(ctx, batch, batch, batch->gram_jobs, K_dev, iters_dev, flag_dev, stream);
@@ -633,11 +794,12 @@ mgk_status mgk_pairs(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
     // Either graph of a pair may be the outer operand; jobs whose outer graph
     // comes from Y are launched with the batch arguments exchanged.
     std::vector<HostJob> jobs((size_t)n_pairs);
+    std::vector<MgkLargePair> large[2];
     for (int64_t k = 0; k < n_pairs; ++k) {
         const int32_t i = i_host[k], j = j_host[k];
         if (i < 0 || i >= X->n_graphs || j < 0 || j >= Y->n_graphs)
             return fail(ctx, MGK_EINVAL, "pair %lld: graph index out of range", (long long)k);
-        const PairPlan pl = plan_pair(X->graphs[i], Y->graphs[j], true, ctx->waves);
+        const PairPlan pl = plan_pair(X->graphs[i], Y->graphs[j], true, ctx->waves, ctx->onchip_limit);
         HostJob& hj = jobs[(size_t)k];
         hj.job.g1 = pl.swap ? j : i;
         hj.job.g2 = pl.swap ? i : j;
@@ -649,16 +811,27 @@ mgk_status mgk_pairs(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
         hj.ept = (int16_t)pl.ept;
         hj.atomic_rows = pl.atomic_rows;
         hj.swapped = pl.swap && X != Y;
-        if (pl.waves == 0)
-            return fail(ctx, MGK_ELIMIT, "pair %lld with %lld product vertices does not fit the on-chip solver",
-                        (long long)k, (long long)X->graphs[i].n * Y->graphs[j].n);
+        if (pl.waves == 0) {
+            if ((int64_t)X->graphs[i].n * Y->graphs[j].n >= ((int64_t)1 << 31) - 64)
+                return fail(ctx, MGK_ELIMIT, "pair %lld is too large", (long long)k);
+            bool sw;
+            MgkLargePair P = plan_large(X->graphs[i], Y->graphs[j], i, j, &sw, ctx->max_iter);
+            P.out0 = (int32_t)k;
+            P.out1 = -1;
+            large[(sw && X != Y) ? 1 : 0].push_back(P);
+            hj.waves = 0;
+        }
     }
     if (ctx->pair_jobs_busy) {  // the previous call's kernels may still read the job buffer
         MGK_HIP(ctx, hipStreamSynchronize(ctx->pair_jobs_stream));
         ctx->pair_jobs_busy = false;
     }
+    jobs.erase(std::remove_if(jobs.begin(), jobs.end(), [](const HostJob& h) { return h.waves == 0; }),
+               jobs.end());
     mgk_status st = build_job_list(ctx, jobs, ctx->pair_jobs, stream, &ctx->pair_jobs_cap);
     if (st != MGK_OK) return st;
+    ctx->pair_jobs.large[0] = std::move(large[0]);
+    ctx->pair_jobs.large[1] = std::move(large[1]);
     ctx->pair_jobs_stream = stream;
     ctx->pair_jobs_busy = true;
     return launch_jobs(ctx, X, Y, ctx->pair_jobs, K_dev, iters_dev, flag_dev, stream);

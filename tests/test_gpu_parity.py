@@ -226,3 +226,64 @@ def test_config4_full_size_sampled(torch, solver):
     assert ev.min() >= -1e-5 * ev.max()
     dg = np.diag(K)
     assert (K * K <= np.outer(dg, dg) * (1 + 1e-4)).all()
+
+
+# ---- global-memory solver (pairs too large for the on-chip one) ----------------
+def test_global_memory_solver_agrees_with_oracle_and_onchip(torch, solver):
+    wb = W.config1(20)
+    solver.set_solver(1e-6, 0)
+    K_chip, it_chip, _ = run_gram(torch, solver, wb)
+    solver.set_onchip_limit(0)
+    try:
+        K_glob, it_glob, fl = run_gram(torch, solver, wb)
+    finally:
+        solver.set_onchip_limit(16384)
+    pi, pj = W.gram_pairs(20)
+    ref = C.pairs(wb, pi, pj, tier=0)
+    np.testing.assert_allclose(K_glob[pi, pj], ref, rtol=RTOL)
+    np.testing.assert_allclose(K_glob, K_chip, rtol=2e-5)
+    assert (fl == 0).all() and (K_glob == K_glob.T).all()
+    assert np.abs(it_glob - it_chip).max() <= 1
+
+
+def test_global_memory_solver_weighted_long_rows_two_batches(torch, solver):
+    rng = np.random.default_rng(21)
+    prm = W.KernelParams(q=0.05, h=0.5, length_scale=0.8)
+    X = W.erdos_renyi_batch(rng, 3, 30, 60, 0.6, (0.2, 1.0), (0.0, 2.0), 3, prm)   # rows > 16
+    Y = W.erdos_renyi_batch(rng, 4, 40, 90, 0.05, (0.2, 1.0), (0.0, 2.0), 3, prm)  # sparse
+    both = W.concat_batches([X, Y], prm)
+    solver.configure(prm)
+    solver.set_solver(1e-6, 0)
+    solver.set_onchip_limit(0)
+    try:
+        BX = solver.load_batch(X); BY = solver.load_batch(Y)
+        pi = np.repeat(np.arange(3), 4).astype(np.int32); pj = np.tile(np.arange(4), 3).astype(np.int32)
+        K, it, fl = run_pairs(torch, solver, BX, BY, pi, pj)
+        np.testing.assert_allclose(K, C.pairs(both, pi, pj + 3, tier=0), rtol=RTOL)
+        K2, _, _ = run_pairs(torch, solver, BY, BX, pj, pi)
+        np.testing.assert_allclose(K2, K, rtol=1e-5)
+        qi, qj = W.gram_pairs(3)
+        K3, _, fl3 = run_pairs(torch, solver, BX, BX, qi, qj)       # dense x dense: atomic row sums
+        np.testing.assert_allclose(K3, C.pairs(X, qi, qj, tier=0), rtol=RTOL)
+        assert (fl == 0).all() and (fl3 == 0).all()
+        solver.set_solver(1e-6, 2)                                   # iteration cap
+        K4, it4, fl4 = run_pairs(torch, solver, BX, BY, pi, pj)
+        assert (it4 == 2).all() and (fl4 == 1).all()
+    finally:
+        solver.set_onchip_limit(16384)
+        solver.set_solver(1e-6, 0)
+
+
+def test_mixed_sizes_in_one_call(torch, solver):
+    # one Gram whose pairs are split between the on-chip and the global-memory solver
+    rng = np.random.default_rng(33)
+    prm = W.KernelParams(q=0.05, h=0.5, length_scale=1.0)
+    small = W.erdos_renyi_batch(rng, 3, 10, 30, 0.2, (0.5, 1.0), (0.0, 1.0), 4, prm)
+    big = W.erdos_renyi_batch(rng, 2, 150, 200, 0.03, (0.5, 1.0), (0.0, 1.0), 4, prm)
+    wb = W.concat_batches([small, big], prm)
+    solver.set_solver(1e-6, 0)
+    K, it, fl = run_gram(torch, solver, wb)
+    pi, pj = W.gram_pairs(5)
+    ref = C.pairs(wb, pi, pj, tier=1)
+    np.testing.assert_allclose(K[pi, pj], ref, rtol=RTOL)
+    assert (fl == 0).all() and (K == K.T).all()
