@@ -36,6 +36,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--graphs", type=int, default=2000, help="graphs in the batch (2000 = the named workload)")
+    ap.add_argument("--workload", default="config4",
+                    help="config4 (default, the benchmark line), config1, config2:<density>, config3")
     ap.add_argument("--waves", type=int, default=0, help="wavefronts per pair (0 = library default)")
     ap.add_argument("--reorder", type=int, default=1, help="0 none, 1 PBR, 2 RCM")
     ap.add_argument("--cpu-sample", type=int, default=64, help="pairs timed on the CPU oracle (0 = skip)")
@@ -53,7 +55,26 @@ def main() -> int:
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
 
-    wb = W.config4(args.graphs)
+    wl = args.workload
+    pair_list = None
+    if wl == "config4":
+        wb = W.config4(args.graphs)
+        wl_name = "config4: Gram of %d molecule-like graphs (20-60 vertices)" % wb.n_graphs
+    elif wl == "config1":
+        wb = W.config1()
+        wl_name = "config1: Gram of 100 molecule-like graphs (10-40 vertices)"
+    elif wl.startswith("config2"):
+        rho = float(wl.split(":")[1]) if ":" in wl else 0.05
+        wb = W.config2(rho)
+        pair_list = (np.arange(0, 128, 2, dtype=np.int32), np.arange(1, 128, 2, dtype=np.int32))
+        wl_name = "config2: 64 pairs of ER graphs, n=256, edge density %g" % rho
+    elif wl == "config3":
+        wb = W.config3()
+        pair_list = (np.arange(0, 32, 2, dtype=np.int32), np.arange(1, 32, 2, dtype=np.int32))
+        wl_name = "config3: 16 pairs of 3-D geometric graphs, n=2048, mean degree 12"
+    else:
+        print("unknown workload " + wl, file=sys.stderr)
+        return 2
     G = wb.n_graphs
     solver = M.Solver(0)
     solver.configure(wb.params)
@@ -64,16 +85,27 @@ def main() -> int:
     load_s = time.perf_counter() - t0
     stats = B.stats()
 
-    K = torch.zeros((G, G), dtype=torch.float32, device="cuda")
-    iters = torch.zeros((G, G), dtype=torch.int32, device="cuda")
-    flags = torch.zeros((G, G), dtype=torch.int32, device="cuda")
+    if pair_list is None:
+        K = torch.zeros((G, G), dtype=torch.float32, device="cuda")
+        iters = torch.zeros((G, G), dtype=torch.int32, device="cuda")
+        flags = torch.zeros((G, G), dtype=torch.int32, device="cuda")
+
+        def step():
+            solver.gram(B, K, iters, flags)
+    else:
+        K = torch.zeros(len(pair_list[0]), dtype=torch.float32, device="cuda")
+        iters = torch.zeros(len(pair_list[0]), dtype=torch.int32, device="cuda")
+        flags = torch.zeros(len(pair_list[0]), dtype=torch.int32, device="cuda")
+
+        def step():
+            solver.pairs(B, B, pair_list[0], pair_list[1], K, iters, flags)
 
     t0 = time.perf_counter()
-    solver.gram(B, K, iters, flags)          # first call also builds the job list
+    step()                                   # first call also builds the job list
     torch.cuda.synchronize()
     first_s = time.perf_counter() - t0
     for _ in range(max(args.warmup - 1, 0)):
-        solver.gram(B, K, iters, flags)
+        step()
     torch.cuda.synchronize()
 
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
@@ -82,25 +114,29 @@ def main() -> int:
     t0 = time.perf_counter()
     for a, b in ev:
         a.record()
-        solver.gram(B, K, iters, flags)
+        step()
         b.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     kernel_ms = [a.elapsed_time(b) for a, b in ev]
 
-    n_pairs = G * (G + 1) // 2
+    if pair_list is None:
+        pi, pj = W.gram_pairs(G)
+    else:
+        pi, pj = pair_list
+    n_pairs = len(pi)
     ms_per_step = wall * 1e3 / args.steps
     pairs_per_s = n_pairs / (wall / args.steps)
 
-    # exact work from the returned iteration counts: sum over unordered pairs of
+    # exact work from the returned iteration counts: sum over pairs of
     # iterations * nnz(A) * nnz(A')
-    it = iters.cpu().numpy().astype(np.float64)
+    it_all = iters.cpu().numpy().astype(np.float64)
+    fl_all = flags.cpu().numpy()
+    it = it_all[pi, pj] if pair_list is None else it_all
     z = wb.nnz().astype(np.float64)
-    zz = np.outer(z, z)
-    iu = np.triu_indices(G)
-    element_pairs = float((it[iu] * zz[iu]).sum())
-    pair_iterations = float(it[iu].sum())
-    not_converged = int(flags.cpu().numpy()[iu].sum())
+    element_pairs = float((it * z[pi] * z[pj]).sum())
+    pair_iterations = float(it.sum())
+    not_converged = int((fl_all[pi, pj] if pair_list is None else fl_all).sum())
     kernel_s = float(np.mean(kernel_ms)) * 1e-3
     alg_flops = FLOPS_PER_ELEMENT_PAIR * element_pairs
     achieved_tflops = alg_flops / kernel_s / 1e12
@@ -119,8 +155,7 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {
-            "workload": "config4: Gram of %d molecule-like graphs (20-60 vertices), %d unordered pairs"
-                        % (G, n_pairs),
+            "workload": "%s, %d pairs" % (wl_name, n_pairs),
             "q": wb.params.q, "h": wb.params.h, "length_scale": wb.params.length_scale,
             "rtol": 1e-6, "reorder": {0: "none", 1: "pbr", 2: "rcm"}[args.reorder],
             "waves_per_pair": args.waves or "auto",
@@ -132,7 +167,7 @@ def main() -> int:
         "load_and_pack_s": load_s, "first_call_s": first_s,
         "roofline": {
             "bound": "alu",
-            "kernel": "mgk_pcg_small",
+            "kernel": "mgk_pcg_small" if wl in ("config4", "config1") else "mgk_large_xmv_kernel (+ vector kernels)",
             "achieved": achieved_tflops,
             "peak": FP32_VECTOR_PEAK_TFLOPS,
             "unit": "TFLOP/s",
@@ -146,7 +181,10 @@ def main() -> int:
 
     if args.cpu_sample > 0:
         from oracle import c_oracle as C
-        pi, pj = W.gram_pairs(G)
+        if pair_list is not None:
+            print("the CPU-baseline leg is defined for the Gram workloads only; use --cpu-sample 0",
+                  file=sys.stderr)
+            return 2
         sel = np.random.default_rng(0).choice(len(pi), min(args.cpu_sample, len(pi)), replace=False)
         C.pairs(wb, pi[sel[:1]], pj[sel[:1]], tier=0)   # build + load outside the clock
         t0 = time.perf_counter()

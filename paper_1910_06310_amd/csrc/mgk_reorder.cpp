@@ -260,51 +260,71 @@ void kway_refine(const MgkAdj& g, std::vector<int32_t>& part, int K, int max_pas
     std::vector<std::vector<int32_t>> members(K);
     for (int v = 0; v < g.n; ++v) members[part[v]].push_back(v);
 
-    struct Delta { int a, b, d; };
-    std::vector<Delta> touched;
-    auto bump = [&](int a, int b, int d) {
-        if (a > b) std::swap(a, b);
-        for (auto& t : touched)
-            if (t.a == a && t.b == b) { t.d += d; return; }
-        touched.push_back({a, b, d});
+    // Trading places of v (part A) and u (part B) only changes the edge counts
+    // of pairs (A, P) and (B, P): dA[P] / dB[P] hold those changes.
+    std::vector<int> dA(K, 0), dB(K, 0), touched;
+    std::vector<char> seen(K, 0);
+    auto touch = [&](int P) {
+        if (!seen[P]) { seen[P] = 1; touched.push_back(P); }
     };
-    // change of (connected pairs, cut edges) if v (part A) and u (part B) trade places
-    auto eval_swap = [&](int v, int u, int& dpairs, int& dcut) {
+    auto collect = [&](int v, int u) {
         const int A = part[v], B = part[u];
+        for (int P : touched) { dA[P] = dB[P] = 0; seen[P] = 0; }
         touched.clear();
         for (int k = g.ptr[v]; k < g.ptr[v + 1]; ++k) {
             int w = g.idx[k];
             if (w == u) continue;
-            bump(A, part[w], -1);
-            bump(B, part[w], +1);
+            const int P = part[w];
+            touch(P); dA[P] -= 1; dB[P] += 1;
         }
         for (int k = g.ptr[u]; k < g.ptr[u + 1]; ++k) {
             int w = g.idx[k];
             if (w == v) continue;
-            bump(B, part[w], -1);
-            bump(A, part[w], +1);
+            const int P = part[w];
+            touch(P); dB[P] -= 1; dA[P] += 1;
         }
+        (void)A; (void)B;
+    };
+    auto change = [&](int a, int b, int d) { const int c = C.get(a, b); return ((c + d) > 0) - (c > 0); };
+    // change of (connected pairs, cut edges) if v (part A) and u (part B) trade places
+    auto eval_swap = [&](int v, int u, int& dpairs, int& dcut) {
+        const int A = part[v], B = part[u];
+        collect(v, u);
         dpairs = 0; dcut = 0;
-        for (auto& t : touched) {
-            if (t.a == t.b || t.d == 0) continue;
-            int c = C.get(t.a, t.b);
-            dpairs += ((c + t.d) > 0) - (c > 0);
-            dcut += t.d;
+        for (int P : touched) {
+            if (P == A || P == B) continue;
+            if (dA[P]) { dpairs += change(A, P, dA[P]); dcut += dA[P]; }
+            if (dB[P]) { dpairs += change(B, P, dB[P]); dcut += dB[P]; }
         }
+        const int dab = dA[B] + dB[A];
+        if (dab) { dpairs += change(A, B, dab); dcut += dab; }
     };
     auto apply_swap = [&](int v, int u) {
         const int A = part[v], B = part[u];
-        int dp, dc;
-        eval_swap(v, u, dp, dc);
-        for (auto& t : touched) if (t.d) C.add(t.a, t.b, t.d);
+        collect(v, u);
+        for (int P : touched) {
+            if (P != A && P != B) {
+                if (dA[P]) C.add(A, P, dA[P]);
+                if (dB[P]) C.add(B, P, dB[P]);
+            }
+        }
+        const int dab = dA[B] + dB[A];
+        if (dab) C.add(A, B, dab);
+        // diagonal counts are never read
         part[v] = B; part[u] = A;
         std::replace(members[A].begin(), members[A].end(), v, u);
         std::replace(members[B].begin(), members[B].end(), u, v);
     };
 
+    int64_t connected = 0;  // current value of Eq. 3
+    for (int a = 0; a < K && C.dense; ++a)
+        for (int b = a + 1; b < K; ++b) connected += C.get(a, b) > 0;
+    if (!C.dense)
+        for (auto& kv : C.h) connected += (kv.first >> 32) != (kv.first & 0xffffffffu) && kv.second > 0;
     std::vector<int> cand_parts;
     for (int pass = 0; pass < max_pass; ++pass) {
         bool improved = false;
+        int64_t gained = 0;
         for (int v = 0; v < g.n; ++v) {
             const int A = part[v];
             cand_parts.clear();
@@ -326,9 +346,12 @@ void kway_refine(const MgkAdj& g, std::vector<int32_t>& part, int K, int max_pas
             if (best_u >= 0) {
                 apply_swap(v, best_u);
                 improved = true;
+                gained -= best_dp;
             }
         }
-        if (!improved) break;
+        connected -= gained;
+        // stop when a whole pass removes less than 0.5 % of the connected pairs
+        if (!improved || gained * 200 < connected) break;
     }
 }
 
@@ -338,6 +361,10 @@ std::vector<int32_t> mgk_order_pbr(const MgkAdj& g, int t) {
     const int n = g.n;
     const int K = (n + t - 1) / t;
     if (K <= 1) return mgk_order_identity(n);
+    // With an average degree of several tiles' width every pair of parts is
+    // connected whatever the order: nothing to gain, and the swap search would
+    // cost O(n K t deg^2).
+    if ((int64_t)g.idx.size() > (int64_t)4 * t * n) return mgk_order_identity(n);
     Bisector bis(g, t);
     bis.run();
     kway_refine(g, bis.part, K, 8);
