@@ -40,6 +40,7 @@ def main() -> int:
                     help="config4 (default, the benchmark line), config1, config2:<density>, config3")
     ap.add_argument("--waves", type=int, default=0, help="wavefronts per pair (0 = library default)")
     ap.add_argument("--reorder", type=int, default=1, help="0 none, 1 PBR, 2 RCM")
+    ap.add_argument("--tile-path", type=int, default=0, help="global-memory solver: 0 auto, 1 sparse, 2 dense")
     ap.add_argument("--cpu-sample", type=int, default=64, help="pairs timed on the CPU oracle (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -80,6 +81,7 @@ def main() -> int:
     solver.configure(wb.params)
     solver.set_solver(1e-6, 0)
     solver.set_launch(args.waves)
+    solver.set_tile_path(args.tile_path)
     t0 = time.perf_counter()
     B = solver.load_batch(wb, reorder=args.reorder)
     load_s = time.perf_counter() - t0
@@ -159,6 +161,7 @@ def main() -> int:
             "q": wb.params.q, "h": wb.params.h, "length_scale": wb.params.length_scale,
             "rtol": 1e-6, "reorder": {0: "none", 1: "pbr", 2: "rcm"}[args.reorder],
             "waves_per_pair": args.waves or "auto",
+            "tile_path": {0: "auto", 1: "sparse", 2: "dense"}[args.tile_path],
         },
         "matvec_element_pairs_per_s": element_pairs / kernel_s,
         "mean_iterations": pair_iterations / n_pairs,

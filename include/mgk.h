@@ -81,7 +81,11 @@ mgk_status mgk_set_edge_kernel_se(mgk_ctx* ctx, float length_scale);
 mgk_status mgk_set_edge_kernel_const(mgk_ctx* ctx, float c);
 mgk_status mgk_set_stop_prob(mgk_ctx* ctx, float q);
 mgk_status mgk_set_solver(mgk_ctx* ctx, float rtol, int32_t max_iter);
-/* Force the sparse or the dense tile-pair primitive, or choose per tile pair. */
+/* Tile-pair primitive of the global-memory solver: sparse (only the nnz * nnz'
+ * products of the nonzeros), dense (all 4096 products of every pair of
+ * non-empty octiles, no gathers), or automatic per graph pair from the mean
+ * fill of the two graphs' octiles.  The on-chip solver always uses the sparse
+ * product. */
 mgk_status mgk_set_tile_path(mgk_ctx* ctx, int32_t mode);
 /* Tuning knobs, safe to leave alone.  waves_per_pair: wavefronts of the
  * workgroup that solves one on-chip pair (1, 2, 4, 8 or 16; 0 = automatic by

@@ -34,8 +34,8 @@ struct JobList {
     MgkJob* dev = nullptr;
     int64_t n = 0;
     std::vector<JobBin> bins;
-    // pairs whose vectors do not fit on chip: [0] outer graph from X, [1] from Y
-    std::vector<MgkLargePair> large[2];
+    // pairs whose vectors do not fit on chip: [outer graph from X / from Y][sparse / dense tile path]
+    std::vector<MgkLargePair> large[2][2];
 };
 
 // growable device allocation owned by a context
@@ -65,6 +65,7 @@ struct mgk_batch {
     int gram_jobs_waves = 0;       // waves_per_pair setting the list was built for
     int gram_jobs_max_iter = 0;    // max_iter setting the list was built for
     int gram_jobs_limit = 0;       // on-chip limit the list was built for
+    int gram_jobs_tile_path = 0;   // tile path setting the list was built for
 };
 
 struct mgk_ctx {
@@ -82,6 +83,7 @@ struct mgk_ctx {
     bool pair_jobs_busy = false;
     // scratch of the global-memory solver
     DevBuf exp_outer[2], exp_inner[2];  // expanded entry lists of batch X / batch Y
+    DevBuf dense_tiles[2][3];           // dense 8x8 expansions (weight, label, log2 weight)
     DevBuf vec, lpairs, lstate, lactive;
     int* active_host = nullptr;         // pinned
 };
@@ -243,6 +245,20 @@ mgk_status ensure(mgk_ctx* ctx, DevBuf& b, size_t bytes) {
     return MGK_OK;
 }
 
+// Tile-pair primitive for a pair in the global-memory solver (Section IV-B,
+// "hybrid dense-sparse"): the dense primitive evaluates all 4096 products of a
+// tile pair, the sparse one only nnz * nnz' of them but pays gathers and row
+// sums; the dense one wins when both graphs' tiles are well filled.
+constexpr int kDenseMinNnzPerTile = 24;
+
+bool use_dense_tiles(const mgk_ctx* ctx, const MgkGraphDesc& a, const MgkGraphDesc& b) {
+    if (ctx->tile_path == MGK_TILE_DENSE) return true;
+    if (ctx->tile_path == MGK_TILE_SPARSE) return false;
+    return a.n_tiles > 0 && b.n_tiles > 0 &&
+           (int64_t)a.nnz >= (int64_t)kDenseMinNnzPerTile * a.n_tiles &&
+           (int64_t)b.nnz >= (int64_t)kDenseMinNnzPerTile * b.n_tiles;
+}
+
 // Plan of one pair for the global-memory solver (any size).
 MgkLargePair plan_large(const MgkGraphDesc& a, const MgkGraphDesc& b, int32_t ia, int32_t ib, bool* swap,
                         int max_iter_param) {
@@ -270,8 +286,8 @@ MgkLargePair plan_large(const MgkGraphDesc& a, const MgkGraphDesc& b, int32_t ia
 // A, inner from B).  Synchronises the stream: the host watches the number of
 // pairs still iterating.
 mgk_status solve_large(mgk_ctx* ctx, const mgk_batch* A, const mgk_batch* Bb, int ia, int ib,
-                       std::vector<MgkLargePair> pairs, float* K, int32_t* iters, int32_t* flags,
-                       hipStream_t stream, const MgkParams& prm, bool weighted) {
+                       std::vector<MgkLargePair> pairs, bool dense, float* K, int32_t* iters,
+                       int32_t* flags, hipStream_t stream, const MgkParams& prm, bool weighted) {
     const int n_pairs = (int)pairs.size();
     if (n_pairs == 0) return MGK_OK;
     int64_t total = 0;
@@ -284,7 +300,10 @@ mgk_status solve_large(mgk_ctx* ctx, const mgk_batch* A, const mgk_batch* Bb, in
         max_iter = std::max(max_iter, P.max_iter);
         const int chunks = Bb->graphs[P.g2].lane_len / 64;
         const int rb = (P.n1 + MGK_LARGE_ROWS_PER_BLOCK - 1) / MGK_LARGE_ROWS_PER_BLOCK;
-        xmv_blocks = std::max(xmv_blocks, rb * ((chunks + CPB - 1) / CPB));
+        if (dense)
+            xmv_blocks = std::max(xmv_blocks, (A->graphs[P.g1].n_tile_rows * Bb->graphs[P.g2].n_tile_rows + 3) / 4);
+        else
+            xmv_blocks = std::max(xmv_blocks, rb * ((chunks + CPB - 1) / CPB));
     }
     const int vec_blocks = std::max(1, std::min(2048, (max_npad + 1023) / 1024));
     mgk_status st;
@@ -297,8 +316,21 @@ mgk_status solve_large(mgk_ctx* ctx, const mgk_batch* A, const mgk_batch* Bb, in
     // expanded entry lists of the batches involved (label scaling depends on the parameters)
     const mgk_batch* bt[2] = {A, Bb};
     const int slot[2] = {ia, ib};
-    MgkExpanded ex[2];
-    for (int k = 0; k < 2; ++k) {
+    MgkExpanded ex[2] = {};
+    MgkDenseTiles dt[2] = {};
+    for (int k = 0; k < 2 && dense; ++k) {
+        if (k == 1 && Bb == A) { dt[1] = dt[0]; break; }
+        const size_t bytes = std::max<size_t>(16, (size_t)bt[k]->dev.n_tiles_total * 64 * sizeof(float));
+        for (int a = 0; a < 3; ++a)
+            if ((st = ensure(ctx, ctx->dense_tiles[slot[k]][a], bytes)) != MGK_OK) return st;
+        float* dw = (float*)ctx->dense_tiles[slot[k]][0].p;
+        float* de = (float*)ctx->dense_tiles[slot[k]][1].p;
+        float* dlw = (float*)ctx->dense_tiles[slot[k]][2].p;
+        hipError_t e = mgk_launch_expand_dense(bt[k]->dev, prm, dw, de, dlw, stream);
+        if (e != hipSuccess) return fail(ctx, MGK_EDEVICE, "expand launch failed: %s", hipGetErrorString(e));
+        dt[k].w = dw; dt[k].e = de; dt[k].lw = dlw;
+    }
+    for (int k = 0; k < 2 && !dense; ++k) {
         if (k == 1 && Bb == A) { ex[1] = ex[0]; break; }
         DevBuf& bo = ctx->exp_outer[slot[k]];
         DevBuf& bi = ctx->exp_inner[slot[k]];
@@ -325,7 +357,8 @@ mgk_status solve_large(mgk_ctx* ctx, const mgk_batch* A, const mgk_batch* Bb, in
     const int check_every = 4;
     for (int it = 0; it < max_iter; ++it) {
         e = mgk_launch_large_iteration(A->dev, Bb->dev, ex[0], ex[1], dpairs, dstate, vec, prm, weighted,
-                                       n_pairs, xmv_blocks, vec_blocks, dactive, it == 0, stream);
+                                       n_pairs, xmv_blocks, vec_blocks, dactive, it == 0,
+                                       dense ? &dt[0] : nullptr, dense ? &dt[1] : nullptr, stream);
         if (e != hipSuccess) return fail(ctx, MGK_EDEVICE, "iteration launch failed: %s", hipGetErrorString(e));
         if ((it + 1) % check_every == 0 || it + 1 == max_iter) {
             MGK_HIP(ctx, hipMemcpyAsync(ctx->active_host, dactive, sizeof(int), hipMemcpyDeviceToHost, stream));
@@ -355,9 +388,13 @@ mgk_status launch_jobs(mgk_ctx* ctx, const mgk_batch* X, const mgk_batch* Y, con
             done += chunk;
         }
     }
-    mgk_status st = solve_large(ctx, X, Y, 0, 1, jl.large[0], K, iters, flags, stream, prm, weighted);
-    if (st != MGK_OK) return st;
-    return solve_large(ctx, Y, X, 1, 0, jl.large[1], K, iters, flags, stream, prm, weighted);
+    for (int dense = 0; dense < 2; ++dense) {
+        mgk_status st = solve_large(ctx, X, Y, 0, 1, jl.large[0][dense], dense != 0, K, iters, flags, stream, prm, weighted);
+        if (st != MGK_OK) return st;
+        st = solve_large(ctx, Y, X, 1, 0, jl.large[1][dense], dense != 0, K, iters, flags, stream, prm, weighted);
+        if (st != MGK_OK) return st;
+    }
+    return MGK_OK;
 }
 
 }  // namespace
@@ -385,7 +422,9 @@ void mgk_destroy(mgk_ctx* ctx) {
     if (!ctx) return;
     if (ctx->pair_jobs.dev) (void)hipFree(ctx->pair_jobs.dev);
     for (DevBuf* b : {&ctx->exp_outer[0], &ctx->exp_outer[1], &ctx->exp_inner[0], &ctx->exp_inner[1],
-                      &ctx->vec, &ctx->lpairs, &ctx->lstate, &ctx->lactive})
+                      &ctx->vec, &ctx->lpairs, &ctx->lstate, &ctx->lactive,
+                      &ctx->dense_tiles[0][0], &ctx->dense_tiles[0][1], &ctx->dense_tiles[0][2],
+                      &ctx->dense_tiles[1][0], &ctx->dense_tiles[1][1], &ctx->dense_tiles[1][2]})
         if (b->p) (void)hipFree(b->p);
     if (ctx->active_host) (void)hipHostFree(ctx->active_host);
     delete ctx;
@@ -734,7 +773,7 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
     if (G * G >= (int64_t)1 << 31) return fail(ctx, MGK_ELIMIT, "Gram matrix too large for 32-bit output indices");
     if (batch->gram_jobs.dev != nullptr &&
         (batch->gram_jobs_waves != ctx->waves || batch->gram_jobs_max_iter != ctx->max_iter ||
-         batch->gram_jobs_limit != ctx->onchip_limit)) {
+         batch->gram_jobs_limit != ctx->onchip_limit || batch->gram_jobs_tile_path != ctx->tile_path)) {
         MGK_HIP(ctx, hipStreamSynchronize(stream));  // launch shape changed: rebuild the job list
         MGK_HIP(ctx, hipFree(batch->gram_jobs.dev));
         batch->gram_jobs.dev = nullptr;
@@ -743,8 +782,7 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
         // a4: job list, one job per unordered pair, kept with the batch
         std::vector<HostJob> jobs;
         jobs.reserve((size_t)(G * (G + 1) / 2));
-        batch->gram_jobs.large[0].clear();
-        batch->gram_jobs.large[1].clear();
+        for (auto& a : batch->gram_jobs.large) for (auto& v : a) v.clear();
         for (int64_t i = 0; i < G; ++i)
             for (int64_t j = i; j < G; ++j) {
                 const PairPlan pl = plan_pair(batch->graphs[i], batch->graphs[j], true, ctx->waves, ctx->onchip_limit);
@@ -766,7 +804,7 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
                     MgkLargePair P = plan_large(batch->graphs[i], batch->graphs[j], (int32_t)i, (int32_t)j, &sw, ctx->max_iter);
                     P.out0 = hj.job.out0;
                     P.out1 = hj.job.out1;
-                    batch->gram_jobs.large[0].push_back(P);
+                    batch->gram_jobs.large[0][use_dense_tiles(ctx, batch->graphs[i], batch->graphs[j]) ? 1 : 0].push_back(P);
                     continue;
                 }
                 jobs.push_back(hj);
@@ -775,6 +813,7 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
         batch->gram_jobs_waves = ctx->waves;
         batch->gram_jobs_max_iter = ctx->max_iter;
         batch->gram_jobs_limit = ctx->onchip_limit;
+        batch->gram_jobs_tile_path = ctx->tile_path;
         if (st != MGK_OK) return st;
     }
     return launch_jobs(ctx, batch, batch, batch->gram_jobs, K_dev, iters_dev, flag_dev, stream);
@@ -794,7 +833,7 @@ mgk_status mgk_pairs(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
     // Either graph of a pair may be the outer operand; jobs whose outer graph
     // comes from Y are launched with the batch arguments exchanged.
     std::vector<HostJob> jobs((size_t)n_pairs);
-    std::vector<MgkLargePair> large[2];
+    std::vector<MgkLargePair> large[2][2];
     for (int64_t k = 0; k < n_pairs; ++k) {
         const int32_t i = i_host[k], j = j_host[k];
         if (i < 0 || i >= X->n_graphs || j < 0 || j >= Y->n_graphs)
@@ -818,7 +857,7 @@ mgk_status mgk_pairs(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
             MgkLargePair P = plan_large(X->graphs[i], Y->graphs[j], i, j, &sw, ctx->max_iter);
             P.out0 = (int32_t)k;
             P.out1 = -1;
-            large[(sw && X != Y) ? 1 : 0].push_back(P);
+            large[(sw && X != Y) ? 1 : 0][use_dense_tiles(ctx, X->graphs[i], Y->graphs[j]) ? 1 : 0].push_back(P);
             hj.waves = 0;
         }
     }
@@ -830,8 +869,8 @@ mgk_status mgk_pairs(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
                jobs.end());
     mgk_status st = build_job_list(ctx, jobs, ctx->pair_jobs, stream, &ctx->pair_jobs_cap);
     if (st != MGK_OK) return st;
-    ctx->pair_jobs.large[0] = std::move(large[0]);
-    ctx->pair_jobs.large[1] = std::move(large[1]);
+    for (int a = 0; a < 2; ++a)
+        for (int b = 0; b < 2; ++b) ctx->pair_jobs.large[a][b] = std::move(large[a][b]);
     ctx->pair_jobs_stream = stream;
     ctx->pair_jobs_busy = true;
     return launch_jobs(ctx, X, Y, ctx->pair_jobs, K_dev, iters_dev, flag_dev, stream);

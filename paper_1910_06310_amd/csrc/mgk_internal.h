@@ -140,6 +140,13 @@ struct MgkExpanded {
     const MgkEntry* inner;
 };
 
+// Octiles of a batch expanded to dense 8x8 blocks (64 floats per tile each).
+struct MgkDenseTiles {
+    const float* w;    // A_ij, 0 where absent
+    const float* e;    // scaled label, 0 where absent
+    const float* lw;   // log2 A_ij, -inf where absent
+};
+
 // One pair solved with global-memory vectors.  Vector v of the pair starts at
 // vec + v * npad floats: 0 x, 1 r, 2 p, 3 M, 4 y (also holds z).
 struct MgkLargePair {

@@ -197,6 +197,113 @@ __global__ __launch_bounds__(kThreads) void mgk_large_xmv_kernel(
     }
 }
 
+// ---- dense tile-pair XMV (Section III-D "tiling-blocking" primitive as a function) ------
+// Octiles expanded to dense 8x8 blocks: weight (0 where absent), scaled label,
+// log2 weight (-inf where absent), 64 floats each per tile.
+template <int EK>
+__global__ __launch_bounds__(256) void mgk_expand_dense_kernel(MgkBatchDev B, MgkParams prm, float* dw,
+                                                               float* de, float* dlw) {
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= B.n_tiles_total) return;
+    const MgkGraphDesc g = B.graphs[B.tile_graph[t]];
+    const MgkTile tile = B.tiles[t];
+    float w = 0.f, el = 0.f, lw = __uint_as_float(0xff800000u);
+    if ((tile.bitmap >> lane) & 1ull) {
+        const int k = g.zoff + (int)tile.nzoff + __popcll(tile.bitmap & ((1ull << lane) - 1ull));
+        w = B.w[k];
+        el = (B.e[k] - prm.e_shift) * prm.e_scale;
+        lw = __log2f(w);
+    }
+    dw[(int64_t)t * 64 + lane] = w;
+    de[(int64_t)t * 64 + lane] = el;
+    dlw[(int64_t)t * 64 + lane] = lw;
+}
+
+// One wave per 8x8 block of outputs (tile row I of G x tile row I' of G'), lane
+// (i, i') = (lane / 8, lane % 8).  For every pair of non-empty tiles (T in row
+// I, T' in row I') the 64 p values of block (J, J') are staged in LDS and read
+// back as broadcasts; the lane keeps row i of T and row i' of T' in registers:
+//   y_ii' += sum_j A_ij sum_j' A'_i'j' kappa_e(E_ij, E'_i'j') p_jj'
+// with A' folded into the exponent.  3 VALU + 1 exp per product, no gathers, no
+// row sums; every product of the 8x8x8x8 block is evaluated, present or not.
+template <int EK>
+__global__ __launch_bounds__(256) void mgk_large_xmv_dense_kernel(
+    MgkBatchDev X, MgkBatchDev Y, MgkDenseTiles DX, MgkDenseTiles DY, const MgkLargePair* pairs,
+    const MgkPairState* state, float* vec, float ke_c) {
+    __shared__ __align__(16) float ptile[4][64];
+    if (state[blockIdx.y].done) return;
+    const MgkLargePair P = pairs[blockIdx.y];
+    const MgkGraphDesc g1 = X.graphs[P.g1], g2 = Y.graphs[P.g2];
+    const int ntr1 = g1.n_tile_rows, ntr2 = g2.n_tile_rows;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int ot = blockIdx.x * 4 + wave;        // output block index
+    if (ot >= ntr1 * ntr2) return;
+    const int I = ot / ntr2, Ip = ot - I * ntr2;
+    const int i = lane >> 3, ip = lane & 7;
+    const float* p = vec + P.vec + 2 * (int64_t)P.npad;
+    float* y = vec + P.vec + 4 * (int64_t)P.npad;
+    const int n1 = P.n1, n2 = P.n2;
+    const int32_t* trp1 = X.trow_ptr + g1.roff;
+    const int32_t* trp2 = Y.trow_ptr + g2.roff;
+    const int t1b = trp1[I], t1e = trp1[I + 1];
+    const int t2b = trp2[Ip], t2e = trp2[Ip + 1];
+    float acc = 0.f;
+    float* pt = ptile[wave];
+    for (int t1 = t1b; t1 < t1e; ++t1) {
+        const int gt1 = g1.toff + t1;
+        const int J = X.tiles[gt1].tc;
+        float wr[8], er[8];
+        {
+            const float4* a = reinterpret_cast<const float4*>(DX.w + (int64_t)gt1 * 64 + i * 8);
+            const float4* b = reinterpret_cast<const float4*>(DX.e + (int64_t)gt1 * 64 + i * 8);
+            const float4 a0 = a[0], a1 = a[1], b0 = b[0], b1 = b[1];
+            wr[0] = a0.x; wr[1] = a0.y; wr[2] = a0.z; wr[3] = a0.w; wr[4] = a1.x; wr[5] = a1.y; wr[6] = a1.z; wr[7] = a1.w;
+            er[0] = b0.x; er[1] = b0.y; er[2] = b0.z; er[3] = b0.w; er[4] = b1.x; er[5] = b1.y; er[6] = b1.z; er[7] = b1.w;
+        }
+        const int prow = J * 8 + i;               // this lane's row of the p block (as loader)
+        for (int t2 = t2b; t2 < t2e; ++t2) {
+            const int gt2 = g2.toff + t2;
+            const int Jp = Y.tiles[gt2].tc;
+            float f2[8], e2[8];                   // log2 weight (or weight) and label of row i' of T'
+            {
+                const float* src = EK == MGK_EK_SE ? DY.lw : DY.w;
+                const float4* a = reinterpret_cast<const float4*>(src + (int64_t)gt2 * 64 + ip * 8);
+                const float4* b = reinterpret_cast<const float4*>(DY.e + (int64_t)gt2 * 64 + ip * 8);
+                const float4 a0 = a[0], a1 = a[1], b0 = b[0], b1 = b[1];
+                f2[0] = a0.x; f2[1] = a0.y; f2[2] = a0.z; f2[3] = a0.w; f2[4] = a1.x; f2[5] = a1.y; f2[6] = a1.z; f2[7] = a1.w;
+                e2[0] = b0.x; e2[1] = b0.y; e2[2] = b0.z; e2[3] = b0.w; e2[4] = b1.x; e2[5] = b1.y; e2[6] = b1.z; e2[7] = b1.w;
+            }
+            const int pcol = Jp * 8 + ip;
+            const float pv = (prow < n1 && pcol < n2) ? p[(int64_t)prow * n2 + pcol] : 0.f;
+            __builtin_amdgcn_wave_barrier();
+            pt[lane] = pv;
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float4 pa = *reinterpret_cast<const float4*>(pt + j * 8);
+                const float4 pb = *reinterpret_cast<const float4*>(pt + j * 8 + 4);
+                const float pj[8] = {pa.x, pa.y, pa.z, pa.w, pb.x, pb.y, pb.z, pb.w};
+                float s = 0.f;
+#pragma unroll
+                for (int jp = 0; jp < 8; ++jp) {
+                    if (EK == MGK_EK_SE) {
+                        const float d = e2[jp] - er[j];
+                        s = __builtin_fmaf(__builtin_amdgcn_exp2f(__builtin_fmaf(-d, d, f2[jp])), pj[jp], s);
+                    } else {
+                        s = __builtin_fmaf(f2[jp], pj[jp], s);
+                    }
+                }
+                acc = __builtin_fmaf(wr[j], s, acc);
+            }
+        }
+    }
+    if (EK == MGK_EK_CONST) acc *= ke_c;
+    const int row = I * 8 + i, col = Ip * 8 + ip;
+    if (row < n1 && col < n2) y[(int64_t)row * n2 + col] = acc;
+}
+
 // ---- p^T a with a = M p - y ---------------------------------------------------------
 __global__ __launch_bounds__(256) void mgk_large_dot_kernel(const MgkLargePair* pairs,
                                                             MgkPairState* state, const float* vec) {
@@ -332,6 +439,18 @@ hipError_t mgk_launch_expand(const MgkBatchDev& B, const MgkParams& prm, MgkEntr
     return hipGetLastError();
 }
 
+hipError_t mgk_launch_expand_dense(const MgkBatchDev& B, const MgkParams& prm, float* dw, float* de,
+                                   float* dlw, hipStream_t stream) {
+    if (B.n_tiles_total > 0) {
+        const dim3 grid((B.n_tiles_total + 3) / 4);
+        if (prm.edge_kernel == MGK_EK_SE)
+            hipLaunchKernelGGL(mgk_expand_dense_kernel<MGK_EK_SE>, grid, dim3(256), 0, stream, B, prm, dw, de, dlw);
+        else
+            hipLaunchKernelGGL(mgk_expand_dense_kernel<MGK_EK_CONST>, grid, dim3(256), 0, stream, B, prm, dw, de, dlw);
+    }
+    return hipGetLastError();
+}
+
 hipError_t mgk_launch_large_init(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkLargePair* pairs,
                                  MgkPairState* state, float* vec, const MgkParams& prm, int n_pairs,
                                  int vec_blocks, hipStream_t stream) {
@@ -344,13 +463,21 @@ hipError_t mgk_launch_large_iteration(const MgkBatchDev& X, const MgkBatchDev& Y
                                       const MgkExpanded& EY, const MgkLargePair* pairs,
                                       MgkPairState* state, float* vec, const MgkParams& prm,
                                       bool weighted, int n_pairs, int xmv_blocks, int vec_blocks,
-                                      int* n_active, bool first, hipStream_t stream) {
+                                      int* n_active, bool first, const MgkDenseTiles* DX,
+                                      const MgkDenseTiles* DY, hipStream_t stream) {
     const dim3 gx(xmv_blocks, n_pairs), gv(vec_blocks, n_pairs), gs((n_pairs + 63) / 64);
+    if (DX != nullptr) {
+        if (prm.edge_kernel == MGK_EK_SE)
+            hipLaunchKernelGGL(mgk_large_xmv_dense_kernel<MGK_EK_SE>, gx, dim3(256), 0, stream, X, Y, *DX, *DY, pairs, state, vec, prm.ke_const);
+        else
+            hipLaunchKernelGGL(mgk_large_xmv_dense_kernel<MGK_EK_CONST>, gx, dim3(256), 0, stream, X, Y, *DX, *DY, pairs, state, vec, prm.ke_const);
+    } else {
 #define MGK_XMV(WT, EKV) \
     hipLaunchKernelGGL((mgk_large_xmv_kernel<WT, EKV>), gx, dim3(kThreads), 0, stream, X, Y, EX, EY, pairs, state, vec, prm.ke_const)
     if (prm.edge_kernel == MGK_EK_SE) { if (weighted) MGK_XMV(true, MGK_EK_SE); else MGK_XMV(false, MGK_EK_SE); }
     else { if (weighted) MGK_XMV(true, MGK_EK_CONST); else MGK_XMV(false, MGK_EK_CONST); }
 #undef MGK_XMV
+    }
     hipLaunchKernelGGL(mgk_large_dot_kernel, gv, dim3(256), 0, stream, pairs, state, vec);
     hipLaunchKernelGGL(mgk_large_scalar1_kernel, gs, dim3(64), 0, stream, state, n_pairs, prm.rtol2, first ? 1 : 0);
     hipLaunchKernelGGL(mgk_large_update_kernel, gv, dim3(256), 0, stream, pairs, state, vec);

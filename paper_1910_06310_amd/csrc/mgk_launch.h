@@ -44,17 +44,22 @@ static inline hipError_t mgk_launch_small(int waves, int ept, bool weighted, boo
 // layout) entry lists; `outer` holds B.nnz_total entries, `inner` B.lanes_total.
 hipError_t mgk_launch_expand(const MgkBatchDev& B, const MgkParams& prm, MgkEntry* outer, MgkEntry* inner,
                              hipStream_t stream);
+// Expand every octile of B to dense 8x8 blocks (64 * B.n_tiles_total floats per array).
+hipError_t mgk_launch_expand_dense(const MgkBatchDev& B, const MgkParams& prm, float* dw, float* de,
+                                   float* dlw, hipStream_t stream);
 // Set-up of Alg. 1 for n_pairs pairs (state must be zero-filled before).
 hipError_t mgk_launch_large_init(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkLargePair* pairs,
                                  MgkPairState* state, float* vec, const MgkParams& prm, int n_pairs,
                                  int vec_blocks, hipStream_t stream);
 // One iteration of Alg. 1 for all pairs that have not stopped; *n_active is
-// decremented for every pair that stops.
+// decremented for every pair that stops.  DX/DY non-null: dense tile-pair XMV
+// (xmv_blocks = workgroups of 4 output blocks), else the expanded sparse XMV.
 hipError_t mgk_launch_large_iteration(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkExpanded& EX,
                                       const MgkExpanded& EY, const MgkLargePair* pairs,
                                       MgkPairState* state, float* vec, const MgkParams& prm,
                                       bool weighted, int n_pairs, int xmv_blocks, int vec_blocks,
-                                      int* n_active, bool first, hipStream_t stream);
+                                      int* n_active, bool first, const MgkDenseTiles* DX,
+                                      const MgkDenseTiles* DY, hipStream_t stream);
 // K = p_x^T x and the per-pair outputs.
 hipError_t mgk_launch_large_final(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkLargePair* pairs,
                                   MgkPairState* state, const float* vec, int n_pairs, int vec_blocks,

@@ -287,3 +287,41 @@ def test_mixed_sizes_in_one_call(torch, solver):
     ref = C.pairs(wb, pi, pj, tier=1)
     np.testing.assert_allclose(K[pi, pj], ref, rtol=RTOL)
     assert (fl == 0).all() and (K == K.T).all()
+
+
+@pytest.mark.parametrize("weighted", [False, True])
+def test_dense_and_sparse_tile_paths_agree(torch, solver, weighted):
+    # sizes that are not multiples of 8 exercise the padded last tile row
+    rng = np.random.default_rng(44)
+    prm = W.KernelParams(q=0.05, h=0.5, length_scale=0.7)
+    wr = (0.3, 1.5) if weighted else (1.0, 1.0)
+    X = W.erdos_renyi_batch(rng, 3, 37, 61, 0.5, wr, (0.0, 2.0), 3, prm)
+    Y = W.erdos_renyi_batch(rng, 2, 19, 45, 0.15, wr, (0.0, 2.0), 3, prm)
+    both = W.concat_batches([X, Y], prm)
+    solver.configure(prm)
+    solver.set_solver(1e-6, 0)
+    solver.set_onchip_limit(0)
+    try:
+        BX = solver.load_batch(X); BY = solver.load_batch(Y, reorder=M.REORDER_NONE)
+        pi = np.repeat(np.arange(3), 2).astype(np.int32); pj = np.tile(np.arange(2), 3).astype(np.int32)
+        ref = C.pairs(both, pi, pj + 3, tier=0)
+        out = {}
+        for mode in (M.TILE_SPARSE, M.TILE_DENSE, M.TILE_AUTO):
+            solver.set_tile_path(mode)
+            K, it, fl = run_pairs(torch, solver, BX, BY, pi, pj)
+            np.testing.assert_allclose(K, ref, rtol=RTOL)
+            assert (fl == 0).all()
+            out[mode] = (K, it)
+        np.testing.assert_allclose(out[M.TILE_DENSE][0], out[M.TILE_SPARSE][0], rtol=2e-5)
+        assert np.abs(out[M.TILE_DENSE][1] - out[M.TILE_SPARSE][1]).max() <= 1
+        # constant edge kernel through the dense primitive
+        solver.set_edge_kernel_const(0.5)
+        solver.set_tile_path(M.TILE_DENSE)
+        qi, qj = W.gram_pairs(3)
+        Kd, _, _ = run_pairs(torch, solver, BX, BX, qi, qj)
+        solver.set_tile_path(M.TILE_SPARSE)
+        Ks, _, _ = run_pairs(torch, solver, BX, BX, qi, qj)
+        np.testing.assert_allclose(Kd, Ks, rtol=2e-5)
+    finally:
+        solver.set_tile_path(M.TILE_AUTO)
+        solver.set_onchip_limit(16384)
