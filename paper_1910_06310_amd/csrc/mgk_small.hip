@@ -35,11 +35,10 @@ __device__ __forceinline__ float wave_sum(float v) {
     v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
     v = dpp_add<0x141>(v);  // row_half_mirror
     v = dpp_add<0x140>(v);  // row_mirror: every lane holds the sum of its row of 16
-    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
-    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
-    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
-    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
-    return (r0 + r1) + (r2 + r3);
+    // row_bcast:15 into rows 1 and 3, then row_bcast:31 into rows 2 and 3: lane 63 holds the total
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x142, 0xa, 0xf, false));
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x143, 0xc, 0xf, false));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 template <int WAVES>
@@ -123,9 +122,17 @@ __device__ __forceinline__ void expand_tile(const MgkBatchDev& B, const MgkGraph
     }
 }
 
+// acc += m * (acc of the lane DIST places lower in the same 16-lane row, 0 if none):
+// one step of the masked shift-and-add that sums the lanes of an inner row.  A
+// single DPP multiply-add; the two wait states a DPP read needs after a VALU
+// write of the same register are spelled out because the instruction is
+// emitted by hand.
 template <int DIST>
-__device__ __forceinline__ float row_shr(float v) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x110 + DIST, 0xf, 0xf, true));
+__device__ __forceinline__ float shr_fmac(float acc, float m) {
+    asm volatile("s_nop 1\n\tv_fmac_f32_dpp %0, %0, %1 row_shr:%2 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+                 : "+v"(acc)
+                 : "v"(m), "n"(DIST));
+    return acc;
 }
 
 // position of the first set bit at or after `from` in a bit array of `words` words; `none` if absent
@@ -190,10 +197,10 @@ __device__ __forceinline__ void xmv_pass(const uint4* ent1, const uint4* ent2, c
                     acc = __builtin_fmaf(cu[u], pv[u], acc);
                     if ((window >> u) & 1u) {   // end of outer row i: sum over each inner row
                         if (EK == MGK_EK_CONST) acc *= ke_c * el2;  // el2 = A'_i'j' (0 on idle lanes)
-                        if (NSTEPS > 0) acc = __builtin_fmaf(m1, row_shr<1>(acc), acc);
-                        if (NSTEPS > 1) acc = __builtin_fmaf(m2, row_shr<2>(acc), acc);
-                        if (NSTEPS > 2) acc = __builtin_fmaf(m4, row_shr<4>(acc), acc);
-                        if (NSTEPS > 3) acc = __builtin_fmaf(m8, row_shr<8>(acc), acc);
+                        if (NSTEPS > 0) acc = shr_fmac<1>(acc, m1);
+                        if (NSTEPS > 1) acc = shr_fmac<2>(acc, m2);
+                        if (NSTEPS > 2) acc = shr_fmac<4>(acc, m4);
+                        if (NSTEPS > 3) acc = shr_fmac<8>(acc, m8);
                         if (last) {
                             float* dst = reinterpret_cast<float*>(ybytes + (e1[u].w + ip4));
                             if (ATOMIC)
@@ -453,6 +460,7 @@ hipError_t MGK_CAT(mgk_launch_small_w, MGK_SMALL_WAVES)(
     constexpr int W = MGK_SMALL_WAVES;
     switch (ept) {
         case 4: return launch_we<W, 4>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
+        case 12: return launch_we<W, 12>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
         case 8: return launch_we<W, 8>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
         case 16: return launch_we<W, 16>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
         default: return hipErrorInvalidValue;
