@@ -282,6 +282,7 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
     float xr[EPT], rr_[EPT], Mr[EPT], pr[EPT], zr[EPT];
     const float qq = prm.q * prm.q;
     const float inv_n2 = 1.0f / (float)n2;
+    const float inv_h = 1.0f / prm.h;
     float s_rz = 0.f, s_bb = 0.f;
 #pragma unroll
     for (int m = 0; m < EPT; ++m) {
@@ -290,11 +291,11 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
         const int ic = ok ? idx : 0;
         const int i = (int)(((float)ic + 0.5f) * inv_n2);
         const int ip = ic - i * n2;
-        const float kv = (lb1[i] == lb2[ip]) ? 1.f : prm.h;
+        const bool same = lb1[i] == lb2[ip];
         const float dd = dq1[i] * dq2[ip];
         const float b = ok ? dd * qq : 0.f;
-        const float z0 = ok ? kv * qq : 0.f;  // M^{-1} b
-        Mr[m] = ok ? dd / kv : 1.f;
+        const float z0 = ok ? (same ? qq : prm.h * qq) : 0.f;  // M^{-1} b = kappa_v q q'
+        Mr[m] = ok ? (same ? dd : dd * inv_h) : 1.f;           // d d' / kappa_v
         xr[m] = 0.f;
         rr_[m] = b;
         pr[m] = z0;
@@ -458,6 +459,14 @@ hipError_t MGK_CAT(mgk_launch_small_w, MGK_SMALL_WAVES)(
     int32_t* iters, int32_t* flags, hipStream_t stream) {
     if (n_jobs <= 0) return hipSuccess;
     constexpr int W = MGK_SMALL_WAVES;
+    if constexpr (W == 4) {  // the common size class gets a finer choice of register block
+        switch (ept) {
+            case 6: return launch_we<W, 6>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
+            case 10: return launch_we<W, 10>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
+            case 14: return launch_we<W, 14>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
+            default: break;
+        }
+    }
     switch (ept) {
         case 4: return launch_we<W, 4>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
         case 12: return launch_we<W, 12>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
