@@ -42,6 +42,9 @@ def main() -> int:
     ap.add_argument("--reorder", type=int, default=1, help="0 none, 1 PBR, 2 RCM")
     ap.add_argument("--tile-path", type=int, default=0, help="global-memory solver: 0 auto, 1 sparse, 2 dense")
     ap.add_argument("--cpu-sample", type=int, default=64, help="pairs timed on the CPU oracle (0 = skip)")
+    ap.add_argument("--calibrate-copy-mib", type=int, default=0,
+                    help="also run one device-to-device copy of this many MiB before the timed region; "
+                         "under `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` it calibrates the counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the pair list shards trivially across GPUs, but this "
@@ -101,6 +104,14 @@ def main() -> int:
 
         def step():
             solver.pairs(B, B, pair_list[0], pair_list[1], K, iters, flags)
+
+    if args.calibrate_copy_mib > 0:
+        src = torch.ones(args.calibrate_copy_mib * 262144, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     t0 = time.perf_counter()
     step()                                   # first call also builds the job list

@@ -165,7 +165,7 @@ struct MgkPairState {
     int32_t iters, done, flag, pad;
 };
 
-#define MGK_LARGE_ROWS_PER_BLOCK 16   // outer rows per workgroup of the large XMV
+#define MGK_LARGE_ROWS_PER_BLOCK 8    // outer rows per workgroup of the large XMV
 #define MGK_LARGE_CHUNKS_PER_WAVE 2   // 64-lane chunks of the inner layout per wave
 #define MGK_LARGE_WAVES 4
 

@@ -122,7 +122,8 @@ def test_invalid_graphs_are_rejected(solver):
 def test_parameter_validation_and_host_only_solve(solver):
     for fn, bad in [(solver.set_vertex_kernel_delta, 0.0), (solver.set_vertex_kernel_delta, 1.5),
                     (solver.set_edge_kernel_se, 0.0), (solver.set_edge_kernel_const, 1.1),
-                    (solver.set_stop_prob, 0.0), (solver.set_launch, 3), (solver.set_tile_path, 7)]:
+                    (solver.set_stop_prob, 0.0), (solver.set_launch, 3), (solver.set_tile_path, 7),
+                    (solver.set_onchip_limit, -1)]:
         with pytest.raises(M.MgkError):
             fn(bad)
     with pytest.raises(M.MgkError):
