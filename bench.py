@@ -37,7 +37,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--graphs", type=int, default=2000, help="graphs in the batch (2000 = the named workload)")
     ap.add_argument("--workload", default="config4",
-                    help="config4 (default, the benchmark line), config1, config2:<density>, config3")
+                    help="config4 (default, the benchmark line), config1, config2:<density>, config3, nws, ba")
     ap.add_argument("--waves", type=int, default=0, help="wavefronts per pair (0 = library default)")
     ap.add_argument("--reorder", type=int, default=1, help="0 none, 1 PBR, 2 RCM")
     ap.add_argument("--tile-path", type=int, default=0, help="global-memory solver: 0 auto, 1 sparse, 2 dense")
@@ -72,6 +72,9 @@ def main() -> int:
         wb = W.config2(rho)
         pair_list = (np.arange(0, 128, 2, dtype=np.int32), np.arange(1, 128, 2, dtype=np.int32))
         wl_name = "config2: 64 pairs of ER graphs, n=256, edge density %g" % rho
+    elif wl in ("nws", "ba"):
+        wb = W.paper_synthetic(wl)
+        wl_name = "paper synthetic set %s: Gram of 160 graphs of 96 nodes" % wl.upper()
     elif wl == "config3":
         wb = W.config3()
         pair_list = (np.arange(0, 32, 2, dtype=np.int32), np.arange(1, 32, 2, dtype=np.int32))
@@ -181,7 +184,7 @@ def main() -> int:
         "load_and_pack_s": load_s, "first_call_s": first_s,
         "roofline": {
             "bound": "alu",
-            "kernel": "mgk_pcg_small" if wl in ("config4", "config1") else "mgk_large_xmv_kernel (+ vector kernels)",
+            "kernel": "mgk_pcg_small" if wl in ("config4", "config1", "nws", "ba") else "mgk_large_xmv_kernel (+ vector kernels)",
             "achieved": achieved_tflops,
             "peak": FP32_VECTOR_PEAK_TFLOPS,
             "unit": "TFLOP/s",

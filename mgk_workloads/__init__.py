@@ -21,4 +21,5 @@ from .generators import (  # noqa: F401
     concat_batches,
     permute_vertices,
     gram_pairs,
+    paper_synthetic,
 )

@@ -327,3 +327,19 @@ def config4(n_graphs: int = 2000) -> GraphBatch:
     rng = np.random.default_rng(SEED_BASE + 4)
     return molecule_like_batch(rng, n_graphs, 20, 60,
                                KernelParams(q=0.05, h=0.3, length_scale=0.1), "config4")
+
+
+def paper_synthetic(kind: str, n_graphs: int = 160, n: int = 96) -> GraphBatch:
+    """The paper's synthetic benchmark sets (Section "Performance Measurement"):
+    160 graphs of 96 nodes, Newman-Watts-Strogatz with k=3, p=0.1 ("nws") or
+    Barabasi-Albert with m=6 ("ba").  The paper does not state labels or base
+    kernels for them: unit weights, 4 uniform vertex labels (h=0.5), edge labels
+    U(0,1) with a square-exponential kernel of length scale 1, q=0.05."""
+    prm = KernelParams(q=0.05, h=0.5, length_scale=1.0)
+    if kind == "nws":
+        rng = np.random.default_rng(SEED_BASE + 10)
+        return newman_watts_strogatz_batch(rng, n_graphs, n, 3, 0.1, 4, prm, "nws")
+    if kind == "ba":
+        rng = np.random.default_rng(SEED_BASE + 11)
+        return barabasi_albert_batch(rng, n_graphs, n, 6, 4, prm, "ba")
+    raise ValueError(kind)

@@ -73,8 +73,8 @@ __device__ __forceinline__ void block_sum2(float& u, float& v, float* red, int w
 // weight for the constant kernel), log2 weight, byte offset of y row i};
 // `rowend` gets bit k set when entry k is the last of its row.
 // Inner graph: lane layout (rows in adjacent lanes inside groups of 16), entry
-// = {i'*4 | rank in run << 20 | last-of-run << 31, j'*4, scaled label or
-// weight, log2 weight}.
+// = {i'*4 | rank in run << 20 | row-longer-than-16 << 30 | last-of-run << 31,
+// j'*4, scaled label or weight, log2 weight}.
 template <bool OUTER, bool WEIGHTED, int EK>
 __device__ __forceinline__ void expand_tile(const MgkBatchDev& B, const MgkGraphDesc& g,
                                             const MgkTile* tiles_lds, int t, int lane, uint4* ent,
@@ -114,7 +114,8 @@ __device__ __forceinline__ void expand_tile(const MgkBatchDev& B, const MgkGraph
         const int deg = rp1 - rp0;
         const uint32_t run_rank = (uint32_t)rank % MGK_LANE_GROUP;
         const uint32_t last = (rank + 1 == deg || run_rank == MGK_LANE_GROUP - 1) ? 1u : 0u;
-        v.x = (uint32_t)(row * 4) | (run_rank << 20) | (last << 31);
+        const uint32_t longrow = deg > MGK_LANE_GROUP ? 1u : 0u;   // row cut into several runs
+        v.x = (uint32_t)(row * 4) | (run_rank << 20) | (longrow << 30) | (last << 31);
         v.y = (uint32_t)(col * 4);
         v.z = __float_as_uint(EK == MGK_EK_SE ? el : w);
         v.w = __float_as_uint(WEIGHTED ? __log2f(w) : 0.f);
@@ -160,6 +161,7 @@ __device__ __forceinline__ void xmv_pass(const uint4* ent1, const uint4* ent2, c
         const uint32_t ip4 = e2.x & 0xfffffu, jp4 = e2.y;
         const uint32_t rank = (e2.x >> 20) & 0xffu;
         const bool last = (e2.x >> 31) != 0u;
+        const bool longrow = ((e2.x >> 30) & 1u) != 0u;
         const float el2 = __uint_as_float(e2.z);
         const float lw2 = __uint_as_float(e2.w);
         const float m1 = rank >= 1 ? 1.f : 0.f, m2 = rank >= 2 ? 1.f : 0.f;
@@ -203,7 +205,7 @@ __device__ __forceinline__ void xmv_pass(const uint4* ent1, const uint4* ent2, c
                         if (NSTEPS > 3) acc = shr_fmac<8>(acc, m8);
                         if (last) {
                             float* dst = reinterpret_cast<float*>(ybytes + (e1[u].w + ip4));
-                            if (ATOMIC)
+                            if (ATOMIC && longrow)   // several runs add up to one y_ii'
                                 __hip_atomic_fetch_add(dst, acc, __ATOMIC_RELAXED,
                                                        __HIP_MEMORY_SCOPE_WORKGROUP);
                             else
@@ -217,7 +219,7 @@ __device__ __forceinline__ void xmv_pass(const uint4* ent1, const uint4* ent2, c
     }
 }
 
-// ATOMIC: the inner graph has rows longer than 16 nonzeros; their runs are
+// ATOMIC: the inner graph has rows longer than 16 nonzeros; the runs of those rows are
 // combined with float atomics and y is cleared by its reader every iteration.
 template <int WAVES, int EPT, bool WEIGHTED, int EK, bool ATOMIC>
 __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(

@@ -325,3 +325,18 @@ def test_dense_and_sparse_tile_paths_agree(torch, solver, weighted):
     finally:
         solver.set_tile_path(M.TILE_AUTO)
         solver.set_onchip_limit(16384)
+
+
+@pytest.mark.parametrize("kind", ["nws", "ba"])
+def test_paper_synthetic_sets(torch, solver, kind):
+    """The paper's own synthetic families at full size (160 graphs of 96 nodes):
+    whole Gram on the device, sampled pairs against the oracle, matrix properties."""
+    wb = W.paper_synthetic(kind)
+    solver.set_solver(1e-6, 0)
+    K, it, fl = run_gram(torch, solver, wb)
+    assert np.isfinite(K).all() and (fl == 0).all() and (K == K.T).all()
+    pi, pj = W.gram_pairs(wb.n_graphs)
+    sel = np.random.default_rng(6).choice(len(pi), 60, replace=False)
+    np.testing.assert_allclose(K[pi[sel], pj[sel]], C.pairs(wb, pi[sel], pj[sel], tier=1), rtol=RTOL)
+    ev = np.linalg.eigvalsh(K)
+    assert ev.min() >= -1e-5 * ev.max()
