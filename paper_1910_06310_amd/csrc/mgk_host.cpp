@@ -134,7 +134,7 @@ MgkParams make_params(const mgk_ctx* ctx, const mgk_batch* X) {
 // Launch shapes of the on-chip solver: `waves` wavefronts per pair, `ept`
 // vector elements per thread; a pair fits when n n' <= waves * 64 * ept.
 struct SmallConfig { int waves, ept; };
-const SmallConfig kAutoConfigs[] = {{1, 4}, {2, 4}, {4, 4}, {4, 6}, {4, 8}, {4, 10}, {4, 12}, {4, 14}, {4, 16}, {8, 16}, {16, 16}};
+const SmallConfig kAutoConfigs[] = {{1, 4}, {2, 4}, {4, 4}, {4, 6}, {4, 8}, {4, 10}, {4, 12}, {4, 14}, {4, 16}, {8, 12}, {8, 16}, {16, 12}, {16, 16}};
 const int kEpts[] = {4, 8, 12, 16};
 
 // Orientation, launch shape and cost of one pair for the on-chip solver.  The

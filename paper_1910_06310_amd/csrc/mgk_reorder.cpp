@@ -365,13 +365,35 @@ std::vector<int32_t> mgk_order_pbr(const MgkAdj& g, int t) {
     // connected whatever the order: nothing to gain, and the swap search would
     // cost O(n K t deg^2).
     if ((int64_t)g.idx.size() > (int64_t)4 * t * n) return mgk_order_identity(n);
+    // Three starting partitions, each refined on Eq. 3; the best one wins:
+    // recursive bisection, blocks of t consecutive vertices in reverse
+    // Cuthill-McKee order (strong on banded / lattice-like graphs), and blocks
+    // of the given order (strong when the input already has locality).
+    auto blocks_of = [&](const std::vector<int32_t>& order) {
+        std::vector<int32_t> part(n);
+        for (int v = 0; v < n; ++v) part[v] = order[v] / t;
+        return part;
+    };
+    auto to_perm = [&](const std::vector<int32_t>& part) {
+        std::vector<int32_t> perm(n), fill(K, 0);
+        for (int v = 0; v < n; ++v) perm[v] = part[v] * t + fill[part[v]]++;
+        return perm;
+    };
     Bisector bis(g, t);
     bis.run();
-    kway_refine(g, bis.part, K, 8);
-    // new id = part * t + rank inside the part (by original id)
-    std::vector<int32_t> perm(n), fill(K, 0);
-    for (int v = 0; v < n; ++v) perm[v] = bis.part[v] * t + fill[bis.part[v]]++;
-    return perm;
+    std::vector<std::vector<int32_t>> starts;
+    starts.push_back(bis.part);
+    starts.push_back(blocks_of(mgk_order_rcm(g)));
+    starts.push_back(blocks_of(mgk_order_identity(n)));
+    std::vector<int32_t> best_perm;
+    int64_t best_count = -1;
+    for (auto& part : starts) {
+        kway_refine(g, part, K, 8);
+        std::vector<int32_t> perm = to_perm(part);
+        const int64_t count = mgk_count_offdiag_tiles(g, perm, t);
+        if (best_count < 0 || count < best_count) { best_count = count; best_perm.swap(perm); }
+    }
+    return best_perm;
 }
 
 int64_t mgk_count_offdiag_tiles(const MgkAdj& g, const std::vector<int32_t>& perm, int t) {
