@@ -249,9 +249,13 @@ __global__ __launch_bounds__(256) void mgk_large_xmv_dense_kernel(
     const int32_t* trp2 = Y.trow_ptr + g2.roff;
     const int t1b = trp1[I], t1e = trp1[I + 1];
     const int t2b = trp2[Ip], t2e = trp2[Ip + 1];
+    // Sums are kept in levels (product row -> tile pair -> outer tile -> total): a single
+    // running fp32 sum over the up to n n' products of a dense row would carry a rounding
+    // bias of their count times half an ulp, which ill-conditioned pairs amplify.
     float acc = 0.f;
     float* pt = ptile[wave];
     for (int t1 = t1b; t1 < t1e; ++t1) {
+        float acc_t1 = 0.f;
         const int gt1 = g1.toff + t1;
         const int J = X.tiles[gt1].tc;
         float wr[8], er[8];
@@ -280,6 +284,7 @@ __global__ __launch_bounds__(256) void mgk_large_xmv_dense_kernel(
             __builtin_amdgcn_wave_barrier();
             pt[lane] = pv;
             __builtin_amdgcn_wave_barrier();
+            float acc_pair = 0.f;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const float4 pa = *reinterpret_cast<const float4*>(pt + j * 8);
@@ -295,9 +300,11 @@ __global__ __launch_bounds__(256) void mgk_large_xmv_dense_kernel(
                         s = __builtin_fmaf(f2[jp], pj[jp], s);
                     }
                 }
-                acc = __builtin_fmaf(wr[j], s, acc);
+                acc_pair = __builtin_fmaf(wr[j], s, acc_pair);
             }
+            acc_t1 += acc_pair;
         }
+        acc += acc_t1;
     }
     if (EK == MGK_EK_CONST) acc *= ke_c;
     const int row = I * 8 + i, col = Ip * 8 + ip;
