@@ -151,6 +151,21 @@ mgk_status mgk_pairs(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
                      const int32_t* i_host, const int32_t* j_host, float* K_dev,
                      int32_t* iters_dev, int32_t* flag_dev, void* stream);
 
+/* mgk_pairs_nodal: as mgk_pairs, and also the node-wise similarity (Section I):
+ * the solution x = V_x r_inf of Eq. 1 itself.  For pair k the n x n' values, in
+ * the caller's original vertex numbering, row-major (vertex i of the X graph,
+ * vertex i' of the Y graph at i*n'+i'), are written at x_dev + x_off_host[k]
+ * (x_off_host: host array of n_pairs offsets in floats; the regions must not
+ * overlap).  K_dev[k] = sum_ii' p_i p'_i' x_ii'. */
+mgk_status mgk_pairs_nodal(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
+                           const int32_t* i_host, const int32_t* j_host, float* K_dev, float* x_dev,
+                           const int64_t* x_off_host, int32_t* iters_dev, int32_t* flag_dev,
+                           void* stream);
+
+/* Normalised Gram matrix (Section "Related Work"): K[i][j] /= sqrt(K[i][i] K[j][j])
+ * in place on the n x n row-major device matrix K_dev. */
+mgk_status mgk_normalize_gram(mgk_ctx* ctx, int32_t n, float* K_dev, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -26,7 +26,7 @@ EXPORTS = [
     "mgk_set_stop_prob", "mgk_set_solver", "mgk_set_tile_path", "mgk_set_launch",
     "mgk_set_onchip_limit",
     "mgk_load_graphs", "mgk_free_batch", "mgk_batch_stats", "mgk_batch_permutation",
-    "mgk_batch_get_tiles", "mgk_gram", "mgk_pairs",
+    "mgk_batch_get_tiles", "mgk_gram", "mgk_pairs", "mgk_pairs_nodal", "mgk_normalize_gram",
 ]
 
 
@@ -71,6 +71,8 @@ def load_library(path: Optional[str] = None):
     lib.mgk_batch_get_tiles.argtypes = [vp, i32, c.POINTER(i32), c.POINTER(i32), vp, vp, vp, vp, vp]
     lib.mgk_gram.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.mgk_pairs.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp, vp]
+    lib.mgk_pairs_nodal.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.mgk_normalize_gram.argtypes = [vp, i32, vp, vp]
     for name in EXPORTS:
         fn = getattr(lib, name)
         if name not in ("mgk_destroy", "mgk_free_batch", "mgk_last_error"):
@@ -233,6 +235,27 @@ class Solver:
         self._check(load_library().mgk_pairs(
             self._h, X._h, Y._h, n, pi, pj, _dev_ptr(K, "float32", n),
             _dev_ptr(iters, "int32", n), _dev_ptr(flags, "int32", n), _stream_ptr(stream)))
+
+    def pairs_nodal(self, X: Batch, Y: Batch, i_idx, j_idx, K, x, x_off, iters=None, flags=None,
+                    stream=None):
+        """x: flat float32 cuda tensor; x_off[k]: offset of pair k's n x n' block in it."""
+        ii, pi = _host(i_idx, np.int32)
+        jj, pj = _host(j_idx, np.int32)
+        off, po = _host(x_off, np.int64)
+        n = len(ii)
+        if len(jj) != n or len(off) != n:
+            raise ValueError("index arrays differ in length")
+        need = 0
+        for k in range(n):
+            nx = int(X.vtx_off[ii[k] + 1] - X.vtx_off[ii[k]]) * int(Y.vtx_off[jj[k] + 1] - Y.vtx_off[jj[k]])
+            need = max(need, int(off[k]) + nx)
+        self._check(load_library().mgk_pairs_nodal(
+            self._h, X._h, Y._h, n, pi, pj, _dev_ptr(K, "float32", n), _dev_ptr(x, "float32", need), po,
+            _dev_ptr(iters, "int32", n), _dev_ptr(flags, "int32", n), _stream_ptr(stream)))
+
+    def normalize_gram(self, n: int, K, stream=None):
+        self._check(load_library().mgk_normalize_gram(self._h, n, _dev_ptr(K, "float32", n * n),
+                                                      _stream_ptr(stream)))
 
     def configure(self, params):
         """Apply q, h and the square-exponential length scale of a workload."""

@@ -84,7 +84,7 @@ struct mgk_ctx {
     // scratch of the global-memory solver
     DevBuf exp_outer[2], exp_inner[2];  // expanded entry lists of batch X / batch Y
     DevBuf dense_tiles[2][3];           // dense 8x8 expansions (weight, label, log2 weight)
-    DevBuf vec, lpairs, lstate, lactive;
+    DevBuf vec, lpairs, lstate, lactive, nodal_off, diag;
     int* active_host = nullptr;         // pinned
 };
 
@@ -286,8 +286,8 @@ MgkLargePair plan_large(const MgkGraphDesc& a, const MgkGraphDesc& b, int32_t ia
 // A, inner from B).  Synchronises the stream: the host watches the number of
 // pairs still iterating.
 mgk_status solve_large(mgk_ctx* ctx, const mgk_batch* A, const mgk_batch* Bb, int ia, int ib,
-                       std::vector<MgkLargePair> pairs, bool dense, float* K, int32_t* iters,
-                       int32_t* flags, hipStream_t stream, const MgkParams& prm, bool weighted) {
+                       std::vector<MgkLargePair> pairs, bool dense, const MgkOutputs& out,
+                       hipStream_t stream, const MgkParams& prm, bool weighted) {
     const int n_pairs = (int)pairs.size();
     if (n_pairs == 0) return MGK_OK;
     int64_t total = 0;
@@ -366,13 +366,13 @@ mgk_status solve_large(mgk_ctx* ctx, const mgk_batch* A, const mgk_batch* Bb, in
             if (*ctx->active_host <= 0) break;
         }
     }
-    e = mgk_launch_large_final(A->dev, Bb->dev, dpairs, dstate, vec, n_pairs, vec_blocks, K, iters, flags, stream);
+    e = mgk_launch_large_final(A->dev, Bb->dev, dpairs, dstate, vec, n_pairs, vec_blocks, out, stream);
     if (e != hipSuccess) return fail(ctx, MGK_EDEVICE, "final launch failed: %s", hipGetErrorString(e));
     return MGK_OK;
 }
 
 mgk_status launch_jobs(mgk_ctx* ctx, const mgk_batch* X, const mgk_batch* Y, const JobList& jl,
-                       float* K, int32_t* iters, int32_t* flags, hipStream_t stream) {
+                       const MgkOutputs& out, hipStream_t stream) {
     const MgkParams prm = make_params(ctx, X);
     const bool weighted = X->weighted || Y->weighted;
     for (const JobBin& b : jl.bins) {
@@ -382,16 +382,16 @@ mgk_status launch_jobs(mgk_ctx* ctx, const mgk_batch* X, const mgk_batch* Y, con
             hipError_t e = mgk_launch_small(b.waves, b.ept, weighted, b.atomic_rows,
                                             b.swapped ? Y->dev : X->dev, b.swapped ? X->dev : Y->dev,
                                             jl.dev + b.first + done, (int)chunk, prm, b.lds_bytes,
-                                            K, iters, flags, stream);
+                                            out, stream);
             if (e != hipSuccess)
                 return fail(ctx, MGK_EDEVICE, "kernel launch failed: %s", hipGetErrorString(e));
             done += chunk;
         }
     }
     for (int dense = 0; dense < 2; ++dense) {
-        mgk_status st = solve_large(ctx, X, Y, 0, 1, jl.large[0][dense], dense != 0, K, iters, flags, stream, prm, weighted);
+        mgk_status st = solve_large(ctx, X, Y, 0, 1, jl.large[0][dense], dense != 0, out, stream, prm, weighted);
         if (st != MGK_OK) return st;
-        st = solve_large(ctx, Y, X, 1, 0, jl.large[1][dense], dense != 0, K, iters, flags, stream, prm, weighted);
+        st = solve_large(ctx, Y, X, 1, 0, jl.large[1][dense], dense != 0, out, stream, prm, weighted);
         if (st != MGK_OK) return st;
     }
     return MGK_OK;
@@ -422,7 +422,7 @@ void mgk_destroy(mgk_ctx* ctx) {
     if (!ctx) return;
     if (ctx->pair_jobs.dev) (void)hipFree(ctx->pair_jobs.dev);
     for (DevBuf* b : {&ctx->exp_outer[0], &ctx->exp_outer[1], &ctx->exp_inner[0], &ctx->exp_inner[1],
-                      &ctx->vec, &ctx->lpairs, &ctx->lstate, &ctx->lactive,
+                      &ctx->vec, &ctx->lpairs, &ctx->lstate, &ctx->lactive, &ctx->nodal_off, &ctx->diag,
                       &ctx->dense_tiles[0][0], &ctx->dense_tiles[0][1], &ctx->dense_tiles[0][2],
                       &ctx->dense_tiles[1][0], &ctx->dense_tiles[1][1], &ctx->dense_tiles[1][2]})
         if (b->p) (void)hipFree(b->p);
@@ -524,7 +524,7 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
     B->graphs.resize(n_graphs);
     B->vtx_off.assign(vtx_off, vtx_off + n_graphs + 1);
     B->perm.resize((size_t)tot_v);
-    std::vector<int32_t> vlabel((size_t)tot_v), rowptr((size_t)tot_v), lanepos((size_t)tot_v), trow_ptr, tile_graph;
+    std::vector<int32_t> vlabel((size_t)tot_v), rowptr((size_t)tot_v), lanepos((size_t)tot_v), iperm((size_t)tot_v), trow_ptr, tile_graph;
     int64_t lanes_total = 0;
     std::vector<float> rowsum((size_t)tot_v), start((size_t)tot_v);
     B->w.reserve((size_t)(2 * tot_e));
@@ -595,6 +595,7 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
         for (int i = 0; i < n; ++i) {
             const int ni = perm[i];
             vlabel[v0 + ni] = vtx_label[v0 + i];
+            iperm[v0 + ni] = i;
             start[v0 + ni] = start_prob ? start_prob[v0 + i] : 1.0f / (float)n;
             rowsum[v0 + ni] = (float)rs[ni];
         }
@@ -687,6 +688,7 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
     const size_t o_lp = append_bytes(blob, lanepos);
     const size_t o_tr = append_bytes(blob, trow_ptr);
     const size_t o_tg = append_bytes(blob, tile_graph);
+    const size_t o_ip = append_bytes(blob, iperm);
     B->dev.n_graphs = n_graphs;
     B->dev.n_tiles_total = (int32_t)B->tiles.size();
     B->dev.nnz_total = (int32_t)B->w.size();
@@ -711,6 +713,7 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
     B->dev.lanepos = reinterpret_cast<const int32_t*>(base + o_lp);
     B->dev.trow_ptr = reinterpret_cast<const int32_t*>(base + o_tr);
     B->dev.tile_graph = reinterpret_cast<const int32_t*>(base + o_tg);
+    B->dev.iperm = reinterpret_cast<const int32_t*>(base + o_ip);
 
     guard.b = nullptr;
     *out = B;
@@ -816,12 +819,14 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
         batch->gram_jobs_tile_path = ctx->tile_path;
         if (st != MGK_OK) return st;
     }
-    return launch_jobs(ctx, batch, batch, batch->gram_jobs, K_dev, iters_dev, flag_dev, stream);
+    const MgkOutputs out{K_dev, iters_dev, flag_dev, nullptr, nullptr};
+    return launch_jobs(ctx, batch, batch, batch->gram_jobs, out, stream);
 }
 
-mgk_status mgk_pairs(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
-                     const int32_t* i_host, const int32_t* j_host, float* K_dev, int32_t* iters_dev,
-                     int32_t* flag_dev, void* stream_) {
+static mgk_status pairs_impl(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
+                             const int32_t* i_host, const int32_t* j_host, float* K_dev,
+                             float* x_dev, const int64_t* x_off_host, int32_t* iters_dev,
+                             int32_t* flag_dev, void* stream_) {
     if (!ctx || !X || !Y) return fail(ctx, MGK_EINVAL, "null argument");
     if (X->owner != ctx || Y->owner != ctx) return fail(ctx, MGK_ESTATE, "batch belongs to another context");
     if (ctx->device < 0) return fail(ctx, MGK_ESTATE, "host-only context cannot solve");
@@ -843,7 +848,7 @@ mgk_status mgk_pairs(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
         hj.job.g1 = pl.swap ? j : i;
         hj.job.g2 = pl.swap ? i : j;
         hj.job.out0 = (int32_t)k;
-        hj.job.out1 = -1;
+        hj.job.out1 = pl.swap ? MGK_OUT1_SWAPPED : MGK_OUT1_NONE;
         hj.cost = pl.cost;
         hj.lds_words = (int32_t)pl.lds_words;
         hj.waves = (int16_t)pl.waves;
@@ -856,7 +861,7 @@ mgk_status mgk_pairs(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
             bool sw;
             MgkLargePair P = plan_large(X->graphs[i], Y->graphs[j], i, j, &sw, ctx->max_iter);
             P.out0 = (int32_t)k;
-            P.out1 = -1;
+            P.out1 = sw ? MGK_OUT1_SWAPPED : MGK_OUT1_NONE;
             large[(sw && X != Y) ? 1 : 0][use_dense_tiles(ctx, X->graphs[i], Y->graphs[j]) ? 1 : 0].push_back(P);
             hj.waves = 0;
         }
@@ -873,7 +878,42 @@ mgk_status mgk_pairs(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
         for (int b = 0; b < 2; ++b) ctx->pair_jobs.large[a][b] = std::move(large[a][b]);
     ctx->pair_jobs_stream = stream;
     ctx->pair_jobs_busy = true;
-    return launch_jobs(ctx, X, Y, ctx->pair_jobs, K_dev, iters_dev, flag_dev, stream);
+    MgkOutputs out{K_dev, iters_dev, flag_dev, nullptr, nullptr};
+    if (x_dev) {
+        if ((st = ensure(ctx, ctx->nodal_off, (size_t)n_pairs * sizeof(int64_t))) != MGK_OK) return st;
+        MGK_HIP(ctx, hipMemcpyAsync(ctx->nodal_off.p, x_off_host, (size_t)n_pairs * sizeof(int64_t),
+                                    hipMemcpyHostToDevice, stream));
+        MGK_HIP(ctx, hipStreamSynchronize(stream));  // caller's array may be pageable
+        out.nodal = x_dev;
+        out.nodal_off = (const int64_t*)ctx->nodal_off.p;
+    }
+    return launch_jobs(ctx, X, Y, ctx->pair_jobs, out, stream);
+}
+
+mgk_status mgk_pairs(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
+                     const int32_t* i_host, const int32_t* j_host, float* K_dev, int32_t* iters_dev,
+                     int32_t* flag_dev, void* stream_) {
+    return pairs_impl(ctx, X, Y, n_pairs, i_host, j_host, K_dev, nullptr, nullptr, iters_dev, flag_dev, stream_);
+}
+
+mgk_status mgk_pairs_nodal(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
+                           const int32_t* i_host, const int32_t* j_host, float* K_dev, float* x_dev,
+                           const int64_t* x_off_host, int32_t* iters_dev, int32_t* flag_dev,
+                           void* stream_) {
+    if (n_pairs > 0 && (!x_dev || !x_off_host)) return fail(ctx, MGK_EINVAL, "null nodal output");
+    return pairs_impl(ctx, X, Y, n_pairs, i_host, j_host, K_dev, x_dev, x_off_host, iters_dev, flag_dev, stream_);
+}
+
+mgk_status mgk_normalize_gram(mgk_ctx* ctx, int32_t n, float* K_dev, void* stream_) {
+    if (!ctx || n < 0 || (n > 0 && !K_dev)) return fail(ctx, MGK_EINVAL, "bad argument");
+    if (ctx->device < 0) return fail(ctx, MGK_ESTATE, "host-only context cannot solve");
+    if (n == 0) return MGK_OK;
+    MGK_HIP(ctx, hipSetDevice(ctx->device));
+    mgk_status st = ensure(ctx, ctx->diag, (size_t)n * sizeof(float));
+    if (st != MGK_OK) return st;
+    hipError_t e = mgk_launch_normalize(K_dev, (float*)ctx->diag.p, n, static_cast<hipStream_t>(stream_));
+    if (e != hipSuccess) return fail(ctx, MGK_EDEVICE, "normalize launch failed: %s", hipGetErrorString(e));
+    return MGK_OK;
 }
 
 }  // extern "C"

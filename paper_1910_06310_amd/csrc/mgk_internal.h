@@ -56,14 +56,30 @@ struct MgkBatchDev {
     const int32_t* lanepos;  // per vertex: first lane slot of its row (inner operand layout)
     const int32_t* trow_ptr; // per graph: tile-row pointers into its tile list
     const int32_t* tile_graph; // per tile: the graph it belongs to
+    const int32_t* iperm;    // per vertex: original id of the stored vertex
     int32_t n_graphs, n_tiles_total, nnz_total, lanes_total;
 };
 
 // One unit of work: solve the pair (outer graph g1 of batch X, inner graph g2
-// of batch Y) and write the value to out0 (and out1 if >= 0).
+// of batch Y) and write the value to out0 (and to out1 if >= 0).  out1 == -2
+// marks a job whose outer graph is the *second* graph of the requested pair
+// (the orientation was exchanged); only the nodal output cares.
 struct MgkJob {
     int32_t g1, g2;
     int32_t out0, out1;
+};
+#define MGK_OUT1_NONE (-1)
+#define MGK_OUT1_SWAPPED (-2)
+
+// Device pointers the solvers write to.  iters, flags, nodal may be null.
+// nodal: solution x of pair k (original vertex numbering of the requested pair,
+// row-major n x n') starts at nodal + nodal_off[out0].
+struct MgkOutputs {
+    float* K;
+    int32_t* iters;
+    int32_t* flags;
+    float* nodal;
+    const int64_t* nodal_off;
 };
 
 enum { MGK_EK_CONST = 0, MGK_EK_SE = 1 };

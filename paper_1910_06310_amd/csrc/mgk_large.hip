@@ -400,22 +400,33 @@ __global__ __launch_bounds__(256) void mgk_large_pupdate_kernel(const MgkLargePa
 // ---- K = p_x^T x ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void mgk_large_final_kernel(MgkBatchDev X, MgkBatchDev Y,
                                                               const MgkLargePair* pairs,
-                                                              MgkPairState* state, const float* vec) {
+                                                              MgkPairState* state, const float* vec,
+                                                              MgkOutputs out) {
     __shared__ float red[8];
     const MgkLargePair P = pairs[blockIdx.y];
     const int N = P.n1 * P.n2;
     const MgkGraphDesc g1 = X.graphs[P.g1], g2 = Y.graphs[P.g2];
     const float* x = vec + P.vec;
+    float* nodal = out.nodal ? out.nodal + out.nodal_off[P.out0] : nullptr;
+    const bool swapped = P.out1 == MGK_OUT1_SWAPPED;
     float s = 0.f;
     for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < N; idx += gridDim.x * blockDim.x) {
         const int i = idx / P.n2, ip = idx - i * P.n2;
-        s = __builtin_fmaf(X.start[g1.voff + i] * Y.start[g2.voff + ip], x[idx], s);
+        const float xv = x[idx];
+        s = __builtin_fmaf(X.start[g1.voff + i] * Y.start[g2.voff + ip], xv, s);
+        if (nodal) {
+            const int64_t oi = X.iperm[g1.voff + i], oip = Y.iperm[g2.voff + ip];
+            nodal[swapped ? oip * P.n1 + oi : oi * P.n2 + oip] = xv;
+        }
     }
     block_accumulate(s, &state[blockIdx.y].kval, red);
 }
 
 __global__ void mgk_large_store_kernel(const MgkLargePair* pairs, const MgkPairState* state,
-                                       int n_pairs, float* K, int32_t* iters, int32_t* flags) {
+                                       int n_pairs, MgkOutputs out) {
+    float* K = out.K;
+    int32_t* iters = out.iters;
+    int32_t* flags = out.flags;
     const int k = blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= n_pairs) return;
     const MgkLargePair P = pairs[k];
@@ -424,6 +435,19 @@ __global__ void mgk_large_store_kernel(const MgkLargePair* pairs, const MgkPairS
     if (P.out1 >= 0) K[P.out1] = s.kval;
     if (iters) { iters[P.out0] = s.iters; if (P.out1 >= 0) iters[P.out1] = s.iters; }
     if (flags) { flags[P.out0] = s.flag; if (P.out1 >= 0) flags[P.out1] = s.flag; }
+}
+
+// ---- normalised Gram matrix: K_ij / sqrt(K_ii K_jj) --------------------------------------
+__global__ void mgk_diag_kernel(const float* K, float* diag, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) diag[i] = K[(int64_t)i * n + i];
+}
+
+__global__ void mgk_normalize_kernel(float* K, const float* diag, int n) {
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= (int64_t)n * n) return;
+    const int i = (int)(k / n), j = (int)(k - (int64_t)i * n);
+    K[k] = K[k] / sqrtf(diag[i] * diag[j]);
 }
 
 }  // namespace
@@ -495,10 +519,18 @@ hipError_t mgk_launch_large_iteration(const MgkBatchDev& X, const MgkBatchDev& Y
 
 hipError_t mgk_launch_large_final(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkLargePair* pairs,
                                   MgkPairState* state, const float* vec, int n_pairs, int vec_blocks,
-                                  float* K, int32_t* iters, int32_t* flags, hipStream_t stream) {
+                                  const MgkOutputs& out, hipStream_t stream) {
     hipLaunchKernelGGL(mgk_large_final_kernel, dim3(vec_blocks, n_pairs), dim3(256), 0, stream, X, Y, pairs,
-                       state, vec);
+                       state, vec, out);
     hipLaunchKernelGGL(mgk_large_store_kernel, dim3((n_pairs + 63) / 64), dim3(64), 0, stream, pairs, state,
-                       n_pairs, K, iters, flags);
+                       n_pairs, out);
+    return hipGetLastError();
+}
+
+hipError_t mgk_launch_normalize(float* K, float* diag, int n, hipStream_t stream) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(mgk_diag_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, K, diag, n);
+    const int64_t nn = (int64_t)n * n;
+    hipLaunchKernelGGL(mgk_normalize_kernel, dim3((unsigned)((nn + 255) / 256)), dim3(256), 0, stream, K, diag, n);
     return hipGetLastError();
 }

@@ -16,8 +16,8 @@
 #define MGK_DECL_SMALL(W)                                                                         \
     hipError_t mgk_launch_small_w##W(int ept, bool weighted, bool atomic_rows, const MgkBatchDev& X, \
                                      const MgkBatchDev& Y, const MgkJob* jobs_dev, int n_jobs,    \
-                                     const MgkParams& prm, size_t lds_bytes, float* K,            \
-                                     int32_t* iters, int32_t* flags, hipStream_t stream);
+                                     const MgkParams& prm, size_t lds_bytes,                      \
+                                     const MgkOutputs& out, hipStream_t stream);
 MGK_DECL_SMALL(1)
 MGK_DECL_SMALL(2)
 MGK_DECL_SMALL(4)
@@ -27,14 +27,14 @@ MGK_DECL_SMALL(16)
 
 static inline hipError_t mgk_launch_small(int waves, int ept, bool weighted, bool atomic_rows, const MgkBatchDev& X,
                                           const MgkBatchDev& Y, const MgkJob* jobs_dev, int n_jobs,
-                                          const MgkParams& prm, size_t lds_bytes, float* K,
-                                          int32_t* iters, int32_t* flags, hipStream_t stream) {
+                                          const MgkParams& prm, size_t lds_bytes,
+                                          const MgkOutputs& out, hipStream_t stream) {
     switch (waves) {
-        case 1: return mgk_launch_small_w1(ept, weighted, atomic_rows, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
-        case 2: return mgk_launch_small_w2(ept, weighted, atomic_rows, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
-        case 4: return mgk_launch_small_w4(ept, weighted, atomic_rows, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
-        case 8: return mgk_launch_small_w8(ept, weighted, atomic_rows, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
-        case 16: return mgk_launch_small_w16(ept, weighted, atomic_rows, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
+        case 1: return mgk_launch_small_w1(ept, weighted, atomic_rows, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+        case 2: return mgk_launch_small_w2(ept, weighted, atomic_rows, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+        case 4: return mgk_launch_small_w4(ept, weighted, atomic_rows, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+        case 8: return mgk_launch_small_w8(ept, weighted, atomic_rows, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+        case 16: return mgk_launch_small_w16(ept, weighted, atomic_rows, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
         default: return hipErrorInvalidValue;
     }
 }
@@ -63,6 +63,8 @@ hipError_t mgk_launch_large_iteration(const MgkBatchDev& X, const MgkBatchDev& Y
 // K = p_x^T x and the per-pair outputs.
 hipError_t mgk_launch_large_final(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkLargePair* pairs,
                                   MgkPairState* state, const float* vec, int n_pairs, int vec_blocks,
-                                  float* K, int32_t* iters, int32_t* flags, hipStream_t stream);
+                                  const MgkOutputs& out, hipStream_t stream);
+// In-place normalisation K[i][j] /= sqrt(K[i][i] K[j][j]) of an n x n matrix; diag holds n floats.
+hipError_t mgk_launch_normalize(float* K, float* diag, int n, hipStream_t stream);
 
 #endif

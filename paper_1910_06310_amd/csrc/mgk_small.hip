@@ -223,8 +223,7 @@ __device__ __forceinline__ void xmv_pass(const uint4* ent1, const uint4* ent2, c
 // combined with float atomics and y is cleared by its reader every iteration.
 template <int WAVES, int EPT, bool WEIGHTED, int EK, bool ATOMIC>
 __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
-    MgkBatchDev X, MgkBatchDev Y, const MgkJob* __restrict__ jobs, MgkParams prm,
-    float* __restrict__ K_out, int32_t* __restrict__ iters_out, int32_t* __restrict__ flag_out) {
+    MgkBatchDev X, MgkBatchDev Y, const MgkJob* __restrict__ jobs, MgkParams prm, MgkOutputs out) {
     extern __shared__ __align__(16) uint32_t lds[];
     constexpr int NT = WAVES * 64;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -397,23 +396,37 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
     }
     const float Kval = block_sum<WAVES>(s_k, red + 48, wave, lane);
     if (tid == 0) {
-        K_out[job.out0] = Kval;
-        if (job.out1 >= 0) K_out[job.out1] = Kval;
-        if (iters_out) {
-            iters_out[job.out0] = it;
-            if (job.out1 >= 0) iters_out[job.out1] = it;
+        out.K[job.out0] = Kval;
+        if (job.out1 >= 0) out.K[job.out1] = Kval;
+        if (out.iters) {
+            out.iters[job.out0] = it;
+            if (job.out1 >= 0) out.iters[job.out1] = it;
         }
-        if (flag_out) {
-            flag_out[job.out0] = flag;
-            if (job.out1 >= 0) flag_out[job.out1] = flag;
+        if (out.flags) {
+            out.flags[job.out0] = flag;
+            if (job.out1 >= 0) out.flags[job.out1] = flag;
+        }
+    }
+    // ---- nodal similarity: x itself, in the original numbering of the requested pair
+    if (out.nodal) {
+        float* dst = out.nodal + out.nodal_off[job.out0];
+        const bool swapped = job.out1 == MGK_OUT1_SWAPPED;
+#pragma unroll
+        for (int m = 0; m < EPT; ++m) {
+            const int idx = tid + m * NT;
+            if (idx < N) {
+                const int i = (int)(((float)idx + 0.5f) * inv_n2);
+                const int ip = idx - i * n2;
+                const int oi = X.iperm[g1.voff + i], oip = Y.iperm[g2.voff + ip];
+                dst[swapped ? oip * n1 + oi : oi * n2 + oip] = xr[m];
+            }
         }
     }
 }
 
 template <int WAVES, int EPT, bool WEIGHTED, int EK, bool ATOMIC>
 hipError_t launch_one(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkJob* jobs, int n_jobs,
-                      const MgkParams& prm, size_t lds_bytes, float* K, int32_t* iters,
-                      int32_t* flags, hipStream_t stream) {
+                      const MgkParams& prm, size_t lds_bytes, const MgkOutputs& out, hipStream_t stream) {
     auto kern = mgk_pcg_small<WAVES, EPT, WEIGHTED, EK, ATOMIC>;
     static bool configured = false;  // per instantiation
     if (!configured) {
@@ -423,17 +436,16 @@ hipError_t launch_one(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkJob* 
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL(kern, dim3(n_jobs), dim3(WAVES * 64), lds_bytes, stream, X, Y, jobs, prm, K,
-                       iters, flags);
+    hipLaunchKernelGGL(kern, dim3(n_jobs), dim3(WAVES * 64), lds_bytes, stream, X, Y, jobs, prm, out);
     return hipGetLastError();
 }
 
 template <int WAVES, int EPT>
 hipError_t launch_we(bool weighted, bool atomic_rows, int ek, const MgkBatchDev& X,
                      const MgkBatchDev& Y, const MgkJob* jobs, int n_jobs, const MgkParams& prm,
-                     size_t lds_bytes, float* K, int32_t* iters, int32_t* flags, hipStream_t stream) {
+                     size_t lds_bytes, const MgkOutputs& out, hipStream_t stream) {
 #define MGK_GO(WT, EKV, AT) \
-    return launch_one<WAVES, EPT, WT, EKV, AT>(X, Y, jobs, n_jobs, prm, lds_bytes, K, iters, flags, stream)
+    return launch_one<WAVES, EPT, WT, EKV, AT>(X, Y, jobs, n_jobs, prm, lds_bytes, out, stream)
     if (ek == MGK_EK_SE) {
         if (weighted) { if (atomic_rows) MGK_GO(true, MGK_EK_SE, true); MGK_GO(true, MGK_EK_SE, false); }
         if (atomic_rows) MGK_GO(false, MGK_EK_SE, true);
@@ -457,23 +469,23 @@ hipError_t launch_we(bool weighted, bool atomic_rows, int ek, const MgkBatchDev&
 // One translation unit per workgroup size keeps the build parallel.
 hipError_t MGK_CAT(mgk_launch_small_w, MGK_SMALL_WAVES)(
     int ept, bool weighted, bool atomic_rows, const MgkBatchDev& X, const MgkBatchDev& Y,
-    const MgkJob* jobs_dev, int n_jobs, const MgkParams& prm, size_t lds_bytes, float* K,
-    int32_t* iters, int32_t* flags, hipStream_t stream) {
+    const MgkJob* jobs_dev, int n_jobs, const MgkParams& prm, size_t lds_bytes,
+    const MgkOutputs& out, hipStream_t stream) {
     if (n_jobs <= 0) return hipSuccess;
     constexpr int W = MGK_SMALL_WAVES;
     if constexpr (W == 4) {  // the common size class gets a finer choice of register block
         switch (ept) {
-            case 6: return launch_we<W, 6>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
-            case 10: return launch_we<W, 10>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
-            case 14: return launch_we<W, 14>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
+            case 6: return launch_we<W, 6>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+            case 10: return launch_we<W, 10>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+            case 14: return launch_we<W, 14>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
             default: break;
         }
     }
     switch (ept) {
-        case 4: return launch_we<W, 4>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
-        case 12: return launch_we<W, 12>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
-        case 8: return launch_we<W, 8>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
-        case 16: return launch_we<W, 16>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, K, iters, flags, stream);
+        case 4: return launch_we<W, 4>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+        case 12: return launch_we<W, 12>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+        case 8: return launch_we<W, 8>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+        case 16: return launch_we<W, 16>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
         default: return hipErrorInvalidValue;
     }
 }

@@ -340,3 +340,50 @@ def test_paper_synthetic_sets(torch, solver, kind):
     np.testing.assert_allclose(K[pi[sel], pj[sel]], C.pairs(wb, pi[sel], pj[sel], tier=1), rtol=RTOL)
     ev = np.linalg.eigvalsh(K)
     assert ev.min() >= -1e-5 * ev.max()
+
+
+def test_nodal_similarity_and_normalized_gram(torch, solver):
+    """x itself (node-wise similarity) in the caller's vertex numbering, for both
+    orientations, both solvers and with reordering on; then K / sqrt(K_ii K_jj)."""
+    rng = np.random.default_rng(17)
+    prm = W.KernelParams(q=0.05, h=0.4, length_scale=0.6)
+    X = W.permute_vertices(W.erdos_renyi_batch(rng, 3, 9, 40, 0.15, (0.3, 1.2), (0.0, 2.0), 3, prm), rng)
+    Y = W.permute_vertices(W.erdos_renyi_batch(rng, 3, 30, 80, 0.08, (0.3, 1.2), (0.0, 2.0), 3, prm), rng)
+    solver.configure(prm)
+    solver.set_solver(1e-6, 0)
+    BX = solver.load_batch(X); BY = solver.load_batch(Y)
+    pi = np.repeat(np.arange(3), 3).astype(np.int32); pj = np.tile(np.arange(3), 3).astype(np.int32)
+    sizes = X.sizes()[pi] * Y.sizes()[pj]
+    off = np.concatenate([[0], np.cumsum(sizes)[:-1]]).astype(np.int64)
+    refs = [C.pair_nodal(X.graph(int(i)), Y.graph(int(j)), prm.q, prm.h, prm.length_scale) for i, j in zip(pi, pj)]
+    try:
+        for limit in (16384, 0):
+            solver.set_onchip_limit(limit)
+            K = torch.zeros(9, dtype=torch.float32, device="cuda")
+            x = torch.full((int(sizes.sum()),), float("nan"), dtype=torch.float32, device="cuda")
+            solver.pairs_nodal(BX, BY, pi, pj, K, x, off)
+            torch.cuda.synchronize()
+            xs = x.cpu().numpy().astype(np.float64); Ks = K.cpu().numpy()
+            for k, (Kref, xref) in enumerate(refs):
+                got = xs[off[k]:off[k] + sizes[k]].reshape(xref.shape)
+                np.testing.assert_allclose(got, xref, rtol=RTOL, atol=RTOL * np.abs(xref).max())
+                assert Ks[k] == pytest.approx(Kref, rel=RTOL)
+            # the other argument order returns the transposed blocks
+            K2 = torch.zeros(9, dtype=torch.float32, device="cuda")
+            x2 = torch.zeros_like(x)
+            solver.pairs_nodal(BY, BX, pj, pi, K2, x2, off)
+            torch.cuda.synchronize()
+            x2s = x2.cpu().numpy()
+            for k, (_, xref) in enumerate(refs):
+                got = x2s[off[k]:off[k] + sizes[k]].reshape(xref.shape[::-1]).T
+                np.testing.assert_allclose(got, xref, rtol=RTOL, atol=RTOL * np.abs(xref).max())
+    finally:
+        solver.set_onchip_limit(16384)
+    wb = W.config1(12)
+    Kg, _, _ = run_gram(torch, solver, wb)
+    Kt = torch.tensor(Kg, dtype=torch.float32, device="cuda")
+    solver.normalize_gram(12, Kt)
+    torch.cuda.synchronize()
+    dg = np.sqrt(np.diag(Kg))
+    np.testing.assert_allclose(Kt.cpu().numpy(), Kg / np.outer(dg, dg), rtol=1e-5)
+    assert np.allclose(np.diag(Kt.cpu().numpy()), 1.0, atol=1e-6)

@@ -290,3 +290,17 @@ def test_c_oracle_rejects_bad_edges():
     g = G(2, [0, 0], [(0, 0)])
     with pytest.raises(RuntimeError):
         C.pair_nodal(g, g, Q, 0.5, 1.0)
+
+
+def test_c_oracle_nodal_solution_matches_numpy():
+    rng = np.random.default_rng(23)
+    g1 = random_graph(rng, 7)
+    g2 = random_graph(rng, 5)
+    k0, x0 = O.kernel_value(g1, g2, Q, 0.5, 0.8, return_nodal=True)
+    for tier in (0, 1):
+        k1, x1 = C.pair_nodal(g1, g2, Q, 0.5, 0.8, tier=tier)
+        assert k1 == pytest.approx(k0, rel=1e-10)
+        np.testing.assert_allclose(x1, x0, rtol=1e-9)
+    # x of (G', G) is the transpose
+    _, xt = O.kernel_value(g2, g1, Q, 0.5, 0.8, return_nodal=True)
+    np.testing.assert_allclose(xt.T, x0, rtol=1e-10)
