@@ -42,7 +42,7 @@ def load_library(path: Optional[str] = None):
     global _lib
     if _lib is not None:
         return _lib
-    path = path or _LIB_PATH
+    path = path or os.environ.get("MGK_LIBRARY_PATH") or _LIB_PATH
     if not os.path.exists(path):
         raise ImportError(
             "HIP library %s is not built; run `python -m paper_1910_06310_amd.build`" % path)

@@ -67,8 +67,11 @@ __device__ __forceinline__ void block_sum2(float& u, float& v, float* red, int w
     v = sv;
 }
 
-// Expand one octile (one wave, lane <-> bit of the bitmap) into the entry list
-// of its graph.
+// Expand packed nonzero k of a graph (one thread per nonzero) into the entry
+// list of its graph: find its octile in the staged tile list, its bit in the
+// occupancy bitmap, and from the bitmaps of the tile row its position in the
+// row.  (Octiles of these graphs hold only a few nonzeros, so a thread per
+// nonzero wastes far fewer lanes than a lane per bit of every bitmap.)
 // Outer graph: CSR order, entry = {byte offset of p row j, scaled label (or
 // weight for the constant kernel), log2 weight, byte offset of y row i};
 // `rowend` gets bit k set when entry k is the last of its row.
@@ -76,31 +79,35 @@ __device__ __forceinline__ void block_sum2(float& u, float& v, float* red, int w
 // = {i'*4 | rank in run << 20 | row-longer-than-16 << 30 | last-of-run << 31,
 // j'*4, scaled label or weight, log2 weight}.
 template <bool OUTER, bool WEIGHTED, int EK>
-__device__ __forceinline__ void expand_tile(const MgkBatchDev& B, const MgkGraphDesc& g,
-                                            const MgkTile* tiles_lds, int t, int lane, uint4* ent,
-                                            uint32_t* rowend, int n_inner, const MgkParams& prm) {
-    const MgkTile tile = tiles_lds[t];
-    const int r = lane >> 3, c = lane & 7;
-    const bool set = (tile.bitmap >> lane) & 1ull;
-    const int row = (int)tile.tr * 8 + r, col = (int)tile.tc * 8 + c;
-    const uint64_t below = tile.bitmap & ((1ull << lane) - 1ull);
-    const int k = (int)tile.nzoff + __popcll(below);
-    float w = 1.f, el = 0.f;
-    int rp0 = 0, rp1 = 0, lp = 0;
-    if (set) {
-        w = B.w[g.zoff + k];
-        el = (B.e[g.zoff + k] - prm.e_shift) * prm.e_scale;
-        rp0 = B.rowptr[g.voff + row];
-        rp1 = (row + 1 < g.n) ? B.rowptr[g.voff + row + 1] : g.nnz;
-        if (!OUTER) lp = B.lanepos[g.voff + row];
+__device__ __forceinline__ void expand_nonzero(const MgkBatchDev& B, const MgkGraphDesc& g,
+                                               const MgkTile* tiles_lds, int k, uint4* ent,
+                                               uint32_t* rowend, int n_inner, const MgkParams& prm) {
+    int lo = 0, hi = g.n_tiles;   // last tile whose first packed nonzero is <= k
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if ((int)tiles_lds[mid].nzoff <= k) lo = mid; else hi = mid;
     }
-    // nonzeros of this row in earlier tiles of the same tile row
-    int prior = 0;
+    const int t = lo;
+    const MgkTile tile = tiles_lds[t];
+    int rest = k - (int)tile.nzoff;   // index of the nonzero among the set bits of the bitmap
+    int r = 0;
+    uint32_t rowbyte = (uint32_t)tile.bitmap & 0xffu;
+    while (rest >= __popc(rowbyte)) {  // ends: the tile holds more than `rest` nonzeros
+        rest -= __popc(rowbyte);
+        ++r;
+        rowbyte = (uint32_t)(tile.bitmap >> (8 * r)) & 0xffu;
+    }
+    uint32_t bits = rowbyte;
+    for (int q = 0; q < rest; ++q) bits &= bits - 1u;
+    const int c = __ffs(bits) - 1;
+    const int row = (int)tile.tr * 8 + r, col = (int)tile.tc * 8 + c;
+    int rank = rest;                  // position inside the row: earlier tiles of the tile row first
     for (int tp = t - 1; tp >= 0 && tiles_lds[tp].tr == tile.tr; --tp)
-        prior += __popc((uint32_t)(tiles_lds[tp].bitmap >> (8 * r)) & 0xffu);
-    if (!set) return;
-    const uint32_t rowbyte = (uint32_t)(tile.bitmap >> (8 * r)) & 0xffu;
-    const int rank = prior + __popc(rowbyte & ((1u << c) - 1u));  // position inside the row
+        rank += __popc((uint32_t)(tiles_lds[tp].bitmap >> (8 * r)) & 0xffu);
+    const float w = B.w[g.zoff + k];
+    const float el = (B.e[g.zoff + k] - prm.e_shift) * prm.e_scale;
+    const int rp0 = B.rowptr[g.voff + row];
+    const int rp1 = (row + 1 < g.n) ? B.rowptr[g.voff + row + 1] : g.nnz;
     uint4 v;
     if (OUTER) {
         const int pos = rp0 + rank;
@@ -111,6 +118,7 @@ __device__ __forceinline__ void expand_tile(const MgkBatchDev& B, const MgkGraph
         ent[pos] = v;
         if (pos + 1 == rp1) atomicOr(&rowend[pos >> 5], 1u << (pos & 31));
     } else {
+        const int lp = B.lanepos[g.voff + row];
         const int deg = rp1 - rp0;
         const uint32_t run_rank = (uint32_t)rank % MGK_LANE_GROUP;
         const uint32_t last = (rank + 1 == deg || run_rank == MGK_LANE_GROUP - 1) ? 1u : 0u;
@@ -270,12 +278,12 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
     for (int k = tid; k < L.y; k += NT) y[k] = 0.f;  // entries no row pair reaches stay 0
     __syncthreads();
 
-    // ---- expand the octiles ---------------------------------------------------
-    for (int t = wave; t < g1.n_tiles + g2.n_tiles; t += WAVES) {
-        if (t < g1.n_tiles)
-            expand_tile<true, WEIGHTED, EK>(X, g1, tl1, t, lane, ent1, rowend, n2, prm);
+    // ---- expand the octiles, one thread per packed nonzero --------------------
+    for (int k = tid; k < z1 + g2.nnz; k += NT) {
+        if (k < z1)
+            expand_nonzero<true, WEIGHTED, EK>(X, g1, tl1, k, ent1, rowend, n2, prm);
         else
-            expand_tile<false, WEIGHTED, EK>(Y, g2, tl2, t - g1.n_tiles, lane, ent2, nullptr, n2, prm);
+            expand_nonzero<false, WEIGHTED, EK>(Y, g2, tl2, k - z1, ent2, nullptr, n2, prm);
     }
 
     // ---- Alg. 1 set-up: M = D_x V_x^{-1}, x = 0, r = b = D_x q_x, z = M^{-1} r,
@@ -353,7 +361,7 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
             s_pa = __builtin_fmaf(pr[m], zr[m], s_pa);
         }
         const float pa = block_sum<WAVES>(s_pa, red + 32, wave, lane);
-        const float alpha = rho / pa;
+        const float alpha = rho * __builtin_amdgcn_rcpf(pa);
 
         // ---- x += alpha p; r -= alpha a; z = M^{-1} r; rho' = r^T z
         float s_rz2 = 0.f, s_rr = 0.f;
@@ -372,7 +380,7 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
         if (s_rr <= thresh) { flag = 0; break; }
 
         // ---- p = z + beta p
-        const float beta = s_rz2 / rho;
+        const float beta = s_rz2 * __builtin_amdgcn_rcpf(rho);
         rho = s_rz2;
 #pragma unroll
         for (int m = 0; m < EPT; ++m) {
