@@ -30,6 +30,17 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3   # MI355X published fp32 vector peak (packed FM
 FLOPS_PER_ELEMENT_PAIR = 8        # SE-labeled element pair: 3 + kappa_e (sub, square, scale, exp, mul)
 
 
+def hbm_traffic(workload, args):
+    """HBM bytes per step from the committed counter summary (two rocprofv3 --pmc
+    runs, FETCH_SIZE and WRITE_SIZE, each scaled by what the counter reads for a
+    copy of known size).  Only for the exact workload it was measured on."""
+    path = os.path.join(ROOT, "profiles", "mgk_pcg_small_config4_hbm.json")
+    if workload != "config4" or args.graphs != 2000 or not os.path.exists(path):
+        return None
+    with open(path) as fh:
+        return json.load(fh)["bytes_per_step"]
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -184,12 +195,13 @@ def main() -> int:
         "load_and_pack_s": load_s, "first_call_s": first_s,
         "roofline": {
             "bound": "alu",
-            "kernel": "mgk_pcg_small" if wl in ("config4", "config1", "nws", "ba") else "mgk_large_xmv_kernel (+ vector kernels)",
+            "kernel": "mgk_pcg_small" if wl in ("config4", "config1", "nws", "ba")
+                      else "mgk_large_xmv_dense_kernel / mgk_large_xmv_kernel (+ vector kernels)",
             "achieved": achieved_tflops,
             "peak": FP32_VECTOR_PEAK_TFLOPS,
             "unit": "TFLOP/s",
             "frac": achieved_tflops / FP32_VECTOR_PEAK_TFLOPS,
-            "traffic": None,
+            "traffic": hbm_traffic(wl, args),
             "flops_per_element_pair": FLOPS_PER_ELEMENT_PAIR,
             "element_pairs_per_step": element_pairs,
             "kernel_ms_per_step": kernel_s * 1e3,
