@@ -387,3 +387,34 @@ def test_nodal_similarity_and_normalized_gram(torch, solver):
     dg = np.sqrt(np.diag(Kg))
     np.testing.assert_allclose(Kt.cpu().numpy(), Kg / np.outer(dg, dg), rtol=1e-5)
     assert np.allclose(np.diag(Kt.cpu().numpy()), 1.0, atol=1e-6)
+
+
+def test_edge_cases(torch, solver):
+    """Empty requests, single graphs, single-vertex and edgeless graphs on both solvers,
+    and the largest product size the on-chip solver takes."""
+    from mgk_workloads.generators import _assemble
+    prm = W.KernelParams(q=0.05, h=0.5, length_scale=1.0)
+    solver.configure(prm)
+    solver.set_solver(1e-6, 0)
+    e = np.zeros(0)
+    rng = np.random.default_rng(3)
+    big = W.erdos_renyi_batch(rng, 2, 128, 128, 0.03, (0.5, 1.0), (0.0, 1.0), 3, prm)   # N = 16384
+    graphs = [(1, [2], [], [], e, e), (5, [0, 1, 2, 0, 1], [], [], e, e), big.graph(0), big.graph(1)]
+    wb = _assemble(graphs, prm, "edge")
+    B = solver.load_batch(wb)
+    K = torch.zeros(1, dtype=torch.float32, device="cuda")
+    solver.pairs(B, B, np.zeros(0, np.int32), np.zeros(0, np.int32), K)       # nothing to do
+    pi, pj = W.gram_pairs(4)
+    ref = C.pairs(wb, pi, pj, tier=1)
+    try:
+        for limit in (16384, 0):
+            solver.set_onchip_limit(limit)
+            Kp, it, fl = run_pairs(torch, solver, B, B, pi, pj)
+            np.testing.assert_allclose(Kp, ref, rtol=RTOL)
+            assert (fl == 0).all()
+    finally:
+        solver.set_onchip_limit(16384)
+    one = solver.load_batch(_assemble(graphs[:1], prm, "one"))
+    K1, _, _ = run_gram(torch, solver, _assemble(graphs[:1], prm, "one"))
+    assert K1.shape == (1, 1) and K1[0, 0] == pytest.approx(0.0025, rel=1e-6)
+    one.free()
