@@ -174,7 +174,7 @@ PairPlan plan_pair(const MgkGraphDesc& a, const MgkGraphDesc& b, bool may_swap, 
     if (pl.waves == 0) return pl;
     const MgkGraphDesc& o = pl.swap ? b : a;
     const MgkGraphDesc& i = pl.swap ? a : b;
-    pl.lds_words = mgk_small_plan(o.n, i.n, o.nnz, i.lane_len, o.n_tiles, i.n_tiles, pl.waves).total;
+    pl.lds_words = mgk_small_plan(o.n, i.n, o.nnz, i.lane_len, o.n_tiles, i.n_tiles, pl.waves, pl.ept).total;
     if (pl.lds_words * 4 > MGK_LDS_LIMIT_BYTES) pl.waves = pl.ept = 0;
     return pl;
 }

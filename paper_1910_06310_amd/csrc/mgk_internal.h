@@ -99,7 +99,7 @@ struct MgkParams {
 // All offsets in 4-byte words from the start of dynamic LDS.  Computed the same
 // way on the host (to size the launch) and in the kernel.
 struct MgkSmallPlan {
-    int32_t p, y;            // vectors, N words each (padded to 4)
+    int32_t p, y;            // vectors, padded to waves * 64 * ept words each
     int32_t ent1, ent2;      // expanded nonzeros, 4 words each
     int32_t rowend;          // bit k set: outer entry k is the last of its row
     int32_t tiles1, tiles2;  // staged octile headers, 4 words each
@@ -113,9 +113,10 @@ struct MgkSmallPlan {
 
 static inline MGK_HD MgkSmallPlan mgk_small_plan(int32_t n1, int32_t n2, int32_t z1,
                                                  int32_t lane_len2, int32_t t1, int32_t t2,
-                                                 int32_t waves) {
+                                                 int32_t waves, int32_t ept) {
     MgkSmallPlan L;
-    const int32_t np = (n1 * n2 + 3) & ~3;
+    const int32_t np = waves * 64 * ept;   // >= n1 * n2: every thread owns ept elements
+    (void)n1;
     L.z1pad = ((z1 + 3) & ~3) + 4;
     L.share = (z1 + waves - 1) / waves;
     if (L.share < 1) L.share = 1;

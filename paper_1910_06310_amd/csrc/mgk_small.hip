@@ -35,9 +35,13 @@ __device__ __forceinline__ float wave_sum(float v) {
     v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
     v = dpp_add<0x141>(v);  // row_half_mirror
     v = dpp_add<0x140>(v);  // row_mirror: every lane holds the sum of its row of 16
-    // row_bcast:15 into rows 1 and 3, then row_bcast:31 into rows 2 and 3: lane 63 holds the total
-    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x142, 0xa, 0xf, false));
-    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x143, 0xc, 0xf, false));
+    // row_bcast:15 into rows 1 and 3, then row_bcast:31 into rows 2 and 3: lane 63 holds the
+    // total.  Written out so that each step is one DPP add (rows outside the row mask keep
+    // their value); the wait states a DPP read needs after a VALU write are explicit.
+    asm("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+                 "s_nop 1\n\tv_add_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf\n\t"
+                 "s_nop 0"   // one more before the lane read below
+                 : "+v"(v));
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
@@ -240,7 +244,7 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
     const MgkGraphDesc g1 = X.graphs[job.g1];
     const MgkGraphDesc g2 = Y.graphs[job.g2];
     const int n1 = g1.n, n2 = g2.n, N = n1 * n2, z1 = g1.nnz, len2 = g2.lane_len;
-    const MgkSmallPlan L = mgk_small_plan(n1, n2, z1, len2, g1.n_tiles, g2.n_tiles, WAVES);
+    const MgkSmallPlan L = mgk_small_plan(n1, n2, z1, len2, g1.n_tiles, g2.n_tiles, WAVES, EPT);
 
     float* p = reinterpret_cast<float*>(lds + L.p);
     float* y = reinterpret_cast<float*>(lds + L.y);
@@ -275,7 +279,8 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
     // lane slots of the inner layout: weight 0, address 0, never the end of a run
     for (int k = z1 + tid; k < L.z1pad; k += NT) ent1[k] = make_uint4(0u, 0u, 0u, 0u);
     for (int k = tid; k < len2; k += NT) ent2[k] = make_uint4(0u, 0u, 0u, 0xff800000u);  // log2 w = -inf
-    for (int k = tid; k < L.y; k += NT) y[k] = 0.f;  // entries no row pair reaches stay 0
+#pragma unroll
+    for (int m = 0; m < EPT; ++m) y[tid + m * NT] = 0.f;  // entries no row pair reaches stay 0
     __syncthreads();
 
     // ---- expand the octiles, one thread per packed nonzero --------------------
@@ -308,7 +313,7 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
         xr[m] = 0.f;
         rr_[m] = b;
         pr[m] = z0;
-        if (ok) p[idx] = z0;
+        p[idx] = z0;   // p and y are padded to NT * EPT; the padding stays 0
         s_rz = __builtin_fmaf(b, z0, s_rz);
         s_bb = __builtin_fmaf(b, b, s_bb);
     }
@@ -351,12 +356,8 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
         float s_pa = 0.f;
 #pragma unroll
         for (int m = 0; m < EPT; ++m) {
-            const int idx = tid + m * NT;
-            float yv = 0.f;
-            if (idx < N) {
-                yv = y[idx];
-                if (ATOMIC) y[idx] = 0.f;
-            }
+            const float yv = y[tid + m * NT];
+            if (ATOMIC) y[tid + m * NT] = 0.f;
             zr[m] = __builtin_fmaf(Mr[m], pr[m], -yv);
             s_pa = __builtin_fmaf(pr[m], zr[m], s_pa);
         }
@@ -377,19 +378,19 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
         }
         block_sum2<WAVES>(s_rz2, s_rr, red, wave, lane);
         ++it;
-        if (s_rr <= thresh) { flag = 0; break; }
 
-        // ---- p = z + beta p
+        // ---- p = z + beta p (also after the last iteration, where it is not used: the
+        //      loop then has a single exit and the register blocks stay in place)
         const float beta = s_rz2 * __builtin_amdgcn_rcpf(rho);
         rho = s_rz2;
 #pragma unroll
         for (int m = 0; m < EPT; ++m) {
-            const int idx = tid + m * NT;
             const float pn = __builtin_fmaf(beta, pr[m], zr[m]);
             pr[m] = pn;
-            if (idx < N) p[idx] = pn;
+            p[tid + m * NT] = pn;
         }
         __syncthreads();
+        if (s_rr <= thresh) { flag = 0; break; }
     }
 
     // ---- K = p_x^T x (Eq. 1)
