@@ -52,6 +52,8 @@ def main() -> int:
     ap.add_argument("--waves", type=int, default=0, help="wavefronts per pair (0 = library default)")
     ap.add_argument("--reorder", type=int, default=1, help="0 none, 1 PBR, 2 RCM")
     ap.add_argument("--tile-path", type=int, default=0, help="global-memory solver: 0 auto, 1 sparse, 2 dense")
+    ap.add_argument("--product-cache", type=int, default=1,
+                    help="on-chip solver: 1 keep the matrix entries of small pairs in registers, 0 regenerate them")
     ap.add_argument("--cpu-sample", type=int, default=64, help="pairs timed on the CPU oracle (0 = skip)")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also run one device-to-device copy of this many MiB before the timed region; "
@@ -99,6 +101,7 @@ def main() -> int:
     solver.set_solver(1e-6, 0)
     solver.set_launch(args.waves)
     solver.set_tile_path(args.tile_path)
+    solver.set_product_cache(bool(args.product_cache))
     t0 = time.perf_counter()
     B = solver.load_batch(wb, reorder=args.reorder)
     load_s = time.perf_counter() - t0
@@ -187,6 +190,7 @@ def main() -> int:
             "rtol": 1e-6, "reorder": {0: "none", 1: "pbr", 2: "rcm"}[args.reorder],
             "waves_per_pair": args.waves or "auto",
             "tile_path": {0: "auto", 1: "sparse", 2: "dense"}[args.tile_path],
+            "product_cache": bool(args.product_cache),
         },
         "matvec_element_pairs_per_s": element_pairs / kernel_s,
         "mean_iterations": pair_iterations / n_pairs,

@@ -97,6 +97,15 @@ mgk_status mgk_set_launch(mgk_ctx* ctx, int32_t waves_per_pair);
  * memory and run one kernel per step of Alg. 1.  Default and upper bound:
  * 16384.  0 sends every pair to the global-memory solver. */
 mgk_status mgk_set_onchip_limit(mgk_ctx* ctx, int32_t max_product);
+/* On-chip solver, where the off-diagonal entries A_ij A'_i'j' kappa_e(E_ij,
+ * E'_i'j') come from in each iteration.  0: regenerated from the two graphs in
+ * every product, as Alg. 2 does.  1 (default): for a pair small enough that its
+ * nnz * nnz' entries fit in the vector registers of one workgroup they are
+ * generated once per solve and kept there (they are never written to memory);
+ * other pairs are handled as with 0.  Both give the same iterates up to the
+ * rounding of the entries.  Ignored while mgk_set_launch forces a workgroup
+ * size. */
+mgk_status mgk_set_product_cache(mgk_ctx* ctx, int32_t enable);
 
 /* ---- graphs -----------------------------------------------------------------
  * Load n_graphs graphs given in flat host arrays (all caller-owned, copied):

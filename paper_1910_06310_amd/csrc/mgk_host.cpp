@@ -26,6 +26,7 @@ struct JobBin {
     int64_t count = 0;
     size_t lds_bytes = 0;
     int waves = 0, ept = 0;
+    int chunks = 0;            // > 0: register-resident solver with this many inner chunks
     bool atomic_rows = false;  // an inner graph has a row longer than one lane group
     bool swapped = false;      // outer graphs come from batch Y, inner from X
 };
@@ -66,6 +67,7 @@ struct mgk_batch {
     int gram_jobs_max_iter = 0;    // max_iter setting the list was built for
     int gram_jobs_limit = 0;       // on-chip limit the list was built for
     int gram_jobs_tile_path = 0;   // tile path setting the list was built for
+    int gram_jobs_cache = 0;       // product-cache setting the list was built for
 };
 
 struct mgk_ctx {
@@ -77,6 +79,7 @@ struct mgk_ctx {
     int tile_path = MGK_TILE_AUTO;
     int waves = 0;
     int onchip_limit = MGK_SMALL_MAX_N;  // largest n n' given to the on-chip solver
+    int product_cache = 1;      // small pairs keep their matrix entries in registers
     JobList pair_jobs;          // reused by mgk_pairs
     int64_t pair_jobs_cap = 0;
     hipStream_t pair_jobs_stream = nullptr;
@@ -147,10 +150,29 @@ struct PairPlan {
     int64_t cost = 0;
     int64_t lds_words = 0;
     int waves = 0, ept = 0;  // 0: does not fit
+    int chunks = 0;          // > 0: register-resident solver
 };
 
+// Register-resident solver for (outer o, inner i) with `waves` wavefronts: every
+// wavefront's run of outer rows must fit the unrolled loop, the inner layout the
+// chunk registers, the vectors the register blocks.  Returns the cost in wave
+// instructions of one iteration, or -1 if the pair does not fit.
+int64_t regs_cost(const MgkGraphDesc& o, const MgkGraphDesc& i, int waves) {
+    const int chunks = std::max(1, i.lane_len / 64);
+    if (chunks > MGK_REGS_MAX_CHUNKS || i.max_deg > MGK_REGS_MAX_DEG) return -1;
+    const int smax = waves == 4 ? MGK_REGS_SMAX_W4 : MGK_REGS_SMAX_W8;
+    const int share = std::max((o.nnz + waves - 1) / waves, 1);
+    if (share + std::max(o.max_deg, 1) - 1 > smax) return -1;
+    const int64_t N = (int64_t)o.n * i.n;
+    const int64_t ept = std::max<int64_t>(1, (N + waves * 64 - 1) / (waves * 64));
+    // register blocks that keep four wavefronts per SIMD resident
+    if (ept > (waves == 4 && chunks == 2 ? 6 : MGK_REGS_MAX_EPT)) return -1;
+    return (int64_t)o.nnz * (1 + 2 * chunks) + (int64_t)o.n * (1 + 4 * chunks) +
+           (int64_t)waves * (8 * ept + 45);
+}
+
 PairPlan plan_pair(const MgkGraphDesc& a, const MgkGraphDesc& b, bool may_swap, int forced_waves,
-                   int onchip_limit) {
+                   int onchip_limit, bool product_cache) {
     // wave iterations of one XMV: outer nonzeros x 64-lane chunks of the inner layout
     auto passes = [](const MgkGraphDesc& o, const MgkGraphDesc& i) {
         return (int64_t)o.nnz * (i.lane_len / 64) + 2 * (int64_t)o.n * (i.lane_len / 64);
@@ -163,6 +185,24 @@ PairPlan plan_pair(const MgkGraphDesc& a, const MgkGraphDesc& b, bool may_swap, 
     const int64_t N = (int64_t)a.n * b.n;
     pl.cost = (pl.swap ? swp : keep) * 64 + 16 * N;
     if (N > MGK_SMALL_MAX_N || N > onchip_limit) return pl;
+    if (product_cache && forced_waves == 0) {
+        int64_t best = -1;
+        for (int w = 4; w <= 8; w *= 2)
+            for (int sw = 0; sw < (may_swap ? 2 : 1); ++sw) {
+                const int64_t c = sw ? regs_cost(b, a, w) : regs_cost(a, b, w);
+                if (c >= 0 && (best < 0 || c < best)) { best = c; pl.waves = w; pl.swap = sw != 0; }
+            }
+        if (best >= 0) {
+            const MgkGraphDesc& o = pl.swap ? b : a;
+            const MgkGraphDesc& i = pl.swap ? a : b;
+            pl.atomic_rows = false;
+            pl.ept = (int)std::max<int64_t>(1, (N + pl.waves * 64 - 1) / (pl.waves * 64));
+            pl.chunks = std::max(1, i.lane_len / 64);
+            pl.cost = best * 16 + 16 * N;
+            pl.lds_words = mgk_regs_plan(o.n, i.n, pl.waves, pl.ept).total;
+            return pl;
+        }
+    }
     if (forced_waves > 0) {  // requested workgroup size, doubled until the pair fits
         for (int w = forced_waves; w <= 16 && pl.waves == 0; w *= 2)
             for (int e : kEpts)
@@ -183,7 +223,7 @@ struct HostJob {
     MgkJob job;
     int64_t cost;
     int32_t lds_words;
-    int16_t waves, ept;
+    int16_t waves, ept, chunks;
     bool atomic_rows, swapped;
 };
 
@@ -194,6 +234,7 @@ mgk_status build_job_list(mgk_ctx* ctx, std::vector<HostJob>& jobs, JobList& out
         const int ka = a.waves * 64 * a.ept, kb = b.waves * 64 * b.ept;
         if (ka != kb) return ka > kb;
         if (a.waves != b.waves) return a.waves > b.waves;
+        if (a.chunks != b.chunks) return a.chunks > b.chunks;
         if (a.atomic_rows != b.atomic_rows) return a.atomic_rows;
         if (a.swapped != b.swapped) return b.swapped;
         return a.cost > b.cost;
@@ -204,12 +245,14 @@ mgk_status build_job_list(mgk_ctx* ctx, std::vector<HostJob>& jobs, JobList& out
     for (size_t k = 0; k < jobs.size(); ++k) {
         flat[k] = jobs[k].job;
         if (out.bins.empty() || jobs[k].waves != out.bins.back().waves ||
-            jobs[k].ept != out.bins.back().ept || jobs[k].atomic_rows != out.bins.back().atomic_rows ||
+            jobs[k].ept != out.bins.back().ept || jobs[k].chunks != out.bins.back().chunks ||
+            jobs[k].atomic_rows != out.bins.back().atomic_rows ||
             jobs[k].swapped != out.bins.back().swapped) {
             JobBin b;
             b.first = (int64_t)k;
             b.waves = jobs[k].waves;
             b.ept = jobs[k].ept;
+            b.chunks = jobs[k].chunks;
             b.atomic_rows = jobs[k].atomic_rows;
             b.swapped = jobs[k].swapped;
             out.bins.push_back(b);
@@ -379,10 +422,13 @@ mgk_status launch_jobs(mgk_ctx* ctx, const mgk_batch* X, const mgk_batch* Y, con
         int64_t done = 0;
         while (done < b.count) {  // grid dimension limit
             const int64_t chunk = std::min<int64_t>(b.count - done, (int64_t)1 << 30);
-            hipError_t e = mgk_launch_small(b.waves, b.ept, weighted, b.atomic_rows,
-                                            b.swapped ? Y->dev : X->dev, b.swapped ? X->dev : Y->dev,
-                                            jl.dev + b.first + done, (int)chunk, prm, b.lds_bytes,
-                                            out, stream);
+            const MgkBatchDev& o = b.swapped ? Y->dev : X->dev;
+            const MgkBatchDev& i = b.swapped ? X->dev : Y->dev;
+            hipError_t e = b.chunks > 0
+                ? mgk_launch_regs(b.waves, b.chunks, b.ept, weighted, o, i, jl.dev + b.first + done, (int)chunk,
+                                  prm, b.lds_bytes, out, stream)
+                : mgk_launch_small(b.waves, b.ept, weighted, b.atomic_rows, o, i,
+                                   jl.dev + b.first + done, (int)chunk, prm, b.lds_bytes, out, stream);
             if (e != hipSuccess)
                 return fail(ctx, MGK_EDEVICE, "kernel launch failed: %s", hipGetErrorString(e));
             done += chunk;
@@ -485,6 +531,13 @@ mgk_status mgk_set_onchip_limit(mgk_ctx* ctx, int32_t max_product) {
     return MGK_OK;
 }
 
+mgk_status mgk_set_product_cache(mgk_ctx* ctx, int32_t enable) {
+    if (!ctx) return MGK_EINVAL;
+    if (enable != 0 && enable != 1) return fail(ctx, MGK_EINVAL, "product cache must be 0 or 1, got %d", enable);
+    ctx->product_cache = enable;
+    return MGK_OK;
+}
+
 mgk_status mgk_set_launch(mgk_ctx* ctx, int32_t waves_per_pair) {
     if (!ctx) return MGK_EINVAL;
     const int w = waves_per_pair;
@@ -525,6 +578,8 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
     B->vtx_off.assign(vtx_off, vtx_off + n_graphs + 1);
     B->perm.resize((size_t)tot_v);
     std::vector<int32_t> vlabel((size_t)tot_v), rowptr((size_t)tot_v), lanepos((size_t)tot_v), iperm((size_t)tot_v), trow_ptr, tile_graph;
+    std::vector<MgkEntry> list_outer, list_inner;   // nonzero lists for the register-resident solver
+    list_outer.reserve((size_t)(2 * tot_e));
     int64_t lanes_total = 0;
     std::vector<float> rowsum((size_t)tot_v), start((size_t)tot_v);
     B->w.reserve((size_t)(2 * tot_e));
@@ -668,6 +723,29 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
         gd.reserved = 0;
         lanes_total += gd.lane_len;
         if (lanes_total >= (int64_t)1 << 31) return fail(ctx, MGK_ELIMIT, "batch too large for 32-bit offsets");
+        // the same nonzeros as plain lists: CSR order (columns ascending inside a row, which is
+        // the order the octiles hold them in) and lane order
+        list_outer.resize((size_t)gd.zoff + nz.size());
+        list_inner.resize((size_t)gd.loff + gd.lane_len, MgkEntry{0u, 0u, 0u, 0u});
+        std::vector<int32_t> filled(n, 0);
+        for (size_t k = 0; k < nz.size(); ++k) {
+            const uint64_t tile_id = nz[k].key >> 6;
+            const int bit = (int)(nz[k].key & 63);
+            const uint32_t i = (uint32_t)(tile_id / ntr) * kTile + bit / 8;
+            const uint32_t j = (uint32_t)(tile_id % ntr) * kTile + bit % 8;
+            const int rank = filled[i]++;
+            uint32_t wbits, ebits;
+            memcpy(&wbits, &nz[k].w, 4);
+            memcpy(&ebits, &nz[k].e, 4);
+            const bool row_end = rank + 1 == deg[i];
+            list_outer[(size_t)gd.zoff + rowptr[v0 + i] + rank] =
+                MgkEntry{i, j, ebits, wbits | (row_end ? 0x80000000u : 0u)};
+            const uint32_t run_rank = (uint32_t)rank % MGK_LANE_GROUP;
+            const uint32_t last = (row_end || run_rank == MGK_LANE_GROUP - 1) ? 1u : 0u;
+            const uint32_t longrow = deg[i] > MGK_LANE_GROUP ? 1u : 0u;
+            list_inner[(size_t)gd.loff + lanepos[v0 + i] + rank] =
+                MgkEntry{i | (run_rank << 20) | (longrow << 30) | (last << 31), j, ebits, wbits};
+        }
         tile_graph.resize(B->tiles.size(), g);
     }
     B->n_vertices = tot_v;
@@ -689,6 +767,8 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
     const size_t o_tr = append_bytes(blob, trow_ptr);
     const size_t o_tg = append_bytes(blob, tile_graph);
     const size_t o_ip = append_bytes(blob, iperm);
+    const size_t o_lo = append_bytes(blob, list_outer);
+    const size_t o_li = append_bytes(blob, list_inner);
     B->dev.n_graphs = n_graphs;
     B->dev.n_tiles_total = (int32_t)B->tiles.size();
     B->dev.nnz_total = (int32_t)B->w.size();
@@ -714,6 +794,8 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
     B->dev.trow_ptr = reinterpret_cast<const int32_t*>(base + o_tr);
     B->dev.tile_graph = reinterpret_cast<const int32_t*>(base + o_tg);
     B->dev.iperm = reinterpret_cast<const int32_t*>(base + o_ip);
+    B->dev.list_outer = reinterpret_cast<const MgkEntry*>(base + o_lo);
+    B->dev.list_inner = reinterpret_cast<const MgkEntry*>(base + o_li);
 
     guard.b = nullptr;
     *out = B;
@@ -776,7 +858,8 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
     if (G * G >= (int64_t)1 << 31) return fail(ctx, MGK_ELIMIT, "Gram matrix too large for 32-bit output indices");
     if (batch->gram_jobs.dev != nullptr &&
         (batch->gram_jobs_waves != ctx->waves || batch->gram_jobs_max_iter != ctx->max_iter ||
-         batch->gram_jobs_limit != ctx->onchip_limit || batch->gram_jobs_tile_path != ctx->tile_path)) {
+         batch->gram_jobs_limit != ctx->onchip_limit || batch->gram_jobs_tile_path != ctx->tile_path ||
+         batch->gram_jobs_cache != ctx->product_cache)) {
         MGK_HIP(ctx, hipStreamSynchronize(stream));  // launch shape changed: rebuild the job list
         MGK_HIP(ctx, hipFree(batch->gram_jobs.dev));
         batch->gram_jobs.dev = nullptr;
@@ -788,7 +871,7 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
         for (auto& a : batch->gram_jobs.large) for (auto& v : a) v.clear();
         for (int64_t i = 0; i < G; ++i)
             for (int64_t j = i; j < G; ++j) {
-                const PairPlan pl = plan_pair(batch->graphs[i], batch->graphs[j], true, ctx->waves, ctx->onchip_limit);
+                const PairPlan pl = plan_pair(batch->graphs[i], batch->graphs[j], true, ctx->waves, ctx->onchip_limit, ctx->product_cache != 0);
                 HostJob hj;
                 hj.job.g1 = (int32_t)(pl.swap ? j : i);
                 hj.job.g2 = (int32_t)(pl.swap ? i : j);
@@ -798,6 +881,7 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
                 hj.lds_words = (int32_t)pl.lds_words;
                 hj.waves = (int16_t)pl.waves;
                 hj.ept = (int16_t)pl.ept;
+                hj.chunks = (int16_t)pl.chunks;
                 hj.atomic_rows = pl.atomic_rows;
                 hj.swapped = false;  // one batch: swapping is done through the indices
                 if (pl.waves == 0) {  // vectors do not fit on chip
@@ -817,6 +901,7 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
         batch->gram_jobs_max_iter = ctx->max_iter;
         batch->gram_jobs_limit = ctx->onchip_limit;
         batch->gram_jobs_tile_path = ctx->tile_path;
+        batch->gram_jobs_cache = ctx->product_cache;
         if (st != MGK_OK) return st;
     }
     const MgkOutputs out{K_dev, iters_dev, flag_dev, nullptr, nullptr};
@@ -843,7 +928,7 @@ static mgk_status pairs_impl(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n
         const int32_t i = i_host[k], j = j_host[k];
         if (i < 0 || i >= X->n_graphs || j < 0 || j >= Y->n_graphs)
             return fail(ctx, MGK_EINVAL, "pair %lld: graph index out of range", (long long)k);
-        const PairPlan pl = plan_pair(X->graphs[i], Y->graphs[j], true, ctx->waves, ctx->onchip_limit);
+        const PairPlan pl = plan_pair(X->graphs[i], Y->graphs[j], true, ctx->waves, ctx->onchip_limit, ctx->product_cache != 0);
         HostJob& hj = jobs[(size_t)k];
         hj.job.g1 = pl.swap ? j : i;
         hj.job.g2 = pl.swap ? i : j;
@@ -853,6 +938,7 @@ static mgk_status pairs_impl(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n
         hj.lds_words = (int32_t)pl.lds_words;
         hj.waves = (int16_t)pl.waves;
         hj.ept = (int16_t)pl.ept;
+        hj.chunks = (int16_t)pl.chunks;
         hj.atomic_rows = pl.atomic_rows;
         hj.swapped = pl.swap && X != Y;
         if (pl.waves == 0) {

@@ -57,6 +57,8 @@ struct MgkBatchDev {
     const int32_t* trow_ptr; // per graph: tile-row pointers into its tile list
     const int32_t* tile_graph; // per tile: the graph it belongs to
     const int32_t* iperm;    // per vertex: original id of the stored vertex
+    const struct MgkEntry* list_outer;  // per nonzero (CSR order, index zoff + k), see MgkEntry
+    const struct MgkEntry* list_inner;  // per lane slot (index loff + slot)
     int32_t n_graphs, n_tiles_total, nnz_total, lanes_total;
 };
 
@@ -141,6 +143,37 @@ static inline MGK_HD MgkSmallPlan mgk_small_plan(int32_t n1, int32_t n2, int32_t
 
 #define MGK_LDS_LIMIT_BYTES (160 * 1024)
 
+// ---- register-resident on-chip solver ----------------------------------------
+// Four or eight wavefronts per pair.  Each wavefront owns a run of whole outer
+// rows of at most SMAX nonzeros and keeps the off-diagonal matrix entries
+// A_ij A'_i'j' kappa_e(E_ij, E'_i'j') of (its outer nonzeros) x (all inner lane
+// slots) in registers for the whole solve; the inner graph takes `chunks`
+// 64-lane chunks and has rows of at most 4 nonzeros.  LDS holds p, y and x
+// (padded to the register blocks), the per-vertex data of both graphs and the
+// reduction scratch.
+#define MGK_REGS_SMAX_W4 24      // longest run of outer nonzeros per wavefront, 4 wavefronts
+#define MGK_REGS_SMAX_W8 20      // the same with 8 wavefronts
+#define MGK_REGS_MAX_CHUNKS 2
+#define MGK_REGS_MAX_EPT 8
+#define MGK_REGS_MAX_DEG 4       // inner rows: two shift-and-add steps
+
+struct MgkRegsPlan {
+    int32_t p, y, x, vtx1, vtx2, red, total;  // words
+};
+
+static inline MGK_HD MgkRegsPlan mgk_regs_plan(int32_t n1, int32_t n2, int32_t waves, int32_t ept) {
+    MgkRegsPlan L;
+    const int32_t np = waves * 64 * ept;
+    L.p = 0;
+    L.y = np;
+    L.x = 2 * np;
+    L.vtx1 = 3 * np;
+    L.vtx2 = L.vtx1 + 3 * n1;
+    L.red = (L.vtx2 + 3 * n2 + 3) & ~3;
+    L.total = L.red + 64;
+    return L;
+}
+
 // ---- solver with vectors in global memory (pairs too large for LDS) ---------
 // Expanded nonzero lists of a whole batch, rebuilt per call because the label
 // scaling depends on the edge-kernel parameters:
@@ -151,6 +184,15 @@ static inline MGK_HD MgkSmallPlan mgk_small_plan(int32_t n1, int32_t n2, int32_t
 struct alignas(16) MgkEntry {
     uint32_t x, y, z, w;
 };
+
+// Parameter-free nonzero lists written once at load (list_outer / list_inner of
+// MgkBatchDev) for the register-resident on-chip solver, which reads a graph's
+// nonzeros straight into lanes:
+//   list_outer[zoff + k], CSR order: {row, col, label bits, weight bits | bit 31
+//     set when k is the last nonzero of its row (weights are > 0)}
+//   list_inner[loff + slot], lane layout: {row | rank in run << 20 | row longer
+//     than a lane group << 30 | last of run << 31, col, label bits, weight bits
+//     (0.0f for an idle slot)}
 
 struct MgkExpanded {
     const MgkEntry* outer;

@@ -39,6 +39,34 @@ static inline hipError_t mgk_launch_small(int waves, int ept, bool weighted, boo
     }
 }
 
+// Register-resident on-chip solver (mgk_regs.hip): `waves` (4 or 8) wavefronts
+// per job, `chunks` 64-lane chunks of the inner graph, ept * waves * 64 >= n n'
+// of every job, `lds_bytes` the largest MgkRegsPlan::total of the jobs.  One
+// definition per (waves, chunks), each in its own translation unit.
+#define MGK_DECL_REGS(W, C)                                                                       \
+    hipError_t mgk_launch_regs_w##W##_c##C(int ept, bool weighted, const MgkBatchDev& X,          \
+                                           const MgkBatchDev& Y, const MgkJob* jobs_dev,          \
+                                           int n_jobs, const MgkParams& prm, size_t lds_bytes,    \
+                                           const MgkOutputs& out, hipStream_t stream);
+MGK_DECL_REGS(4, 1)
+MGK_DECL_REGS(4, 2)
+MGK_DECL_REGS(8, 1)
+MGK_DECL_REGS(8, 2)
+#undef MGK_DECL_REGS
+
+static inline hipError_t mgk_launch_regs(int waves, int chunks, int ept, bool weighted,
+                                         const MgkBatchDev& X, const MgkBatchDev& Y,
+                                         const MgkJob* jobs_dev, int n_jobs, const MgkParams& prm,
+                                         size_t lds_bytes, const MgkOutputs& out, hipStream_t stream) {
+    switch (waves * 10 + chunks) {
+        case 41: return mgk_launch_regs_w4_c1(ept, weighted, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+        case 42: return mgk_launch_regs_w4_c2(ept, weighted, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+        case 81: return mgk_launch_regs_w8_c1(ept, weighted, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+        case 82: return mgk_launch_regs_w8_c2(ept, weighted, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 // ---- solver with vectors in global memory (mgk_large.hip) --------------------
 // Expand every octile of batch B into the outer (CSR order) and inner (lane
 // layout) entry lists; `outer` holds B.nnz_total entries, `inner` B.lanes_total.

@@ -1,0 +1,422 @@
+// Register-resident on-chip solver: one workgroup of four wavefronts runs the
+// whole preconditioned CG iteration (Alg. 1) for one graph pair whose
+// off-diagonal matrix fits in the register file.
+//
+// Alg. 2 regenerates the entries A_ij A'_i'j' kappa_e(E_ij, E'_i'j') in every
+// iteration because the N x N matrix cannot be kept in memory.  For a pair of
+// small graphs the nonzero ones (nnz x nnz' of them, a few thousand) do fit in
+// the 512 KB of vector registers of a compute unit, so they are generated once
+// per solve, straight into registers, and never touch memory at all: each lane
+// owns one nonzero (i', j') of the inner graph per 64-lane chunk, each
+// wavefront owns a run of whole rows of the outer graph, and register
+// kap[c][k] of a lane holds the entry for the wavefront's k-th outer nonzero
+// and the lane's inner nonzero of chunk c.  One XMV then costs, per entry, an
+// address add, a gathered LDS read of p_jj' and a multiply-add; the loop over k
+// is unrolled completely so that the register index is static.  The sum over
+// the lanes of an inner row at the end of an outer row, the single-writer store
+// of y_ii' and the vector part of the iteration are as in the streaming kernel.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mgk_internal.h"
+#include "mgk_launch.h"
+#include "mgk_wave.h"
+
+namespace {
+
+
+__device__ __forceinline__ uint32_t lane_value(uint32_t v, int k) {
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, k);
+}
+__device__ __forceinline__ float lane_value(float v, int k) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), k));
+}
+
+
+// The loops over the wave's outer nonzeros are unrolled by template recursion,
+// four nonzeros per step, so that every index into the register array kap is a
+// compile-time constant.
+
+// Matrix entries of outer nonzeros K0 .. SMAX-1 (lanes K0.. of e1s / l1) against this
+// lane's inner nonzeros: square-exponential kernel on prescaled labels,
+// exp2(log2 A + log2 A' - (e - e')^2).  Lanes of e1s past the wave's run hold a huge
+// label and idle inner slots hold l2 = -inf, so both give exactly 0.
+template <int K0, int SMAX, int C, bool WEIGHTED>
+__device__ __forceinline__ void fill_se(float (&kap)[C][SMAX], int S, const float (&e2s)[C],
+                                        const float (&l2)[C], float e1s, float l1) {
+    if constexpr (K0 < SMAX) {
+        if (K0 < S) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float e1 = lane_value(e1s, K0 + u);
+                const float la = WEIGHTED ? lane_value(l1, K0 + u) : 0.f;
+#pragma unroll
+                for (int c = 0; c < C; ++c) {
+                    const float d = e2s[c] - e1;
+                    kap[c][K0 + u] = __builtin_amdgcn_exp2f(__builtin_fmaf(-d, d, WEIGHTED ? l2[c] + la : l2[c]));
+                }
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int c = 0; c < C; ++c) kap[c][K0 + u] = 0.f;
+        }
+        fill_se<K0 + 4, SMAX, C, WEIGHTED>(kap, S, e2s, l2, e1s, l1);
+    }
+}
+
+// the same for the constant edge kernel: A_ij * (A'_i'j' kappa_e); w1 is 0 past the run
+template <int K0, int SMAX, int C>
+__device__ __forceinline__ void fill_const(float (&kap)[C][SMAX], int S, const float (&w2c)[C], float w1) {
+    if constexpr (K0 < SMAX) {
+        if (K0 < S) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float wa = lane_value(w1, K0 + u);
+#pragma unroll
+                for (int c = 0; c < C; ++c) kap[c][K0 + u] = w2c[c] * wa;
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int c = 0; c < C; ++c) kap[c][K0 + u] = 0.f;
+        }
+        fill_const<K0 + 4, SMAX, C>(kap, S, w2c, w1);
+    }
+}
+
+// per-lane constants of the inner nonzeros, one set per chunk
+template <int C>
+struct InnerLanes {
+    uint32_t jp[C], ip[C];            // byte offsets of column j' in a p row, of row i' in a y row
+    float m1[C], m2[C];               // 1 if the lane is at least that far into its run, else 0
+    bool last[C];                     // the lane writes the row sum
+};
+
+// Gathered reads of p for outer nonzeros K0 .. K0+3 (lanes past the wave's run hold
+// offset 0, so the reads stay inside p).
+template <int K0, int C>
+__device__ __forceinline__ void gather4(float (&pv)[4][C], const InnerLanes<C>& in, uint32_t v_poff,
+                                        const char* pbytes) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const uint32_t po = lane_value(v_poff, K0 + u);
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+            pv[u][c] = *reinterpret_cast<const float*>(pbytes + (po + in.jp[c]));
+    }
+}
+
+// XMV steps K0 .. : the reads of p for the next four outer nonzeros are issued
+// before the four already read are used, so that the LDS latency overlaps the
+// arithmetic.  Multiply-add per entry; at the end of an outer row (wave-uniform
+// test) each inner row is summed over its lanes (rows of at most 4 nonzeros:
+// two shift-and-add steps) and y_ii' stored from the last lane of the row.
+template <int K0, int SMAX, int C>
+__device__ __forceinline__ void xmv_steps(const float (&kap)[C][SMAX], const InnerLanes<C>& in,
+                                          float (&acc)[C], const float (&pv)[4][C], int S,
+                                          uint64_t rowmask, uint32_t v_poff, uint32_t v_yoff,
+                                          const char* pbytes, char* ybytes) {
+    if constexpr (K0 < SMAX) {
+        if (K0 >= S) return;
+        float nx[4][C];
+        if constexpr (K0 + 4 < SMAX) {
+            if (K0 + 4 < S) gather4<K0 + 4, C>(nx, in, v_poff, pbytes);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int c = 0; c < C; ++c) acc[c] = __builtin_fmaf(kap[c][K0 + u], pv[u][c], acc[c]);
+            if ((rowmask >> (K0 + u)) & 1ull) {
+                const uint32_t yo = lane_value(v_yoff, K0 + u);
+#pragma unroll
+                for (int c = 0; c < C; ++c) acc[c] = shr_fmac<1>(acc[c], in.m1[c]);
+#pragma unroll
+                for (int c = 0; c < C; ++c) acc[c] = shr_fmac<2>(acc[c], in.m2[c]);
+#pragma unroll
+                for (int c = 0; c < C; ++c) {
+                    if (in.last[c]) *reinterpret_cast<float*>(ybytes + (yo + in.ip[c])) = acc[c];
+                    acc[c] = 0.f;
+                }
+            }
+        }
+        if constexpr (K0 + 4 < SMAX)
+            xmv_steps<K0 + 4, SMAX, C>(kap, in, acc, nx, S, rowmask, v_poff, v_yoff, pbytes, ybytes);
+    }
+}
+
+template <int W, int SMAX, int EPT, int C>
+__global__ __launch_bounds__(W * 64) void mgk_pcg_regs(MgkBatchDev X, MgkBatchDev Y,
+                                                   const MgkJob* __restrict__ jobs, MgkParams prm,
+                                                   MgkOutputs out, int weighted) {
+    extern __shared__ __align__(16) uint32_t lds[];
+    constexpr int NT = W * 64;
+    constexpr int NP = NT * EPT;   // p, y and x are padded to the register blocks
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    const MgkJob job = jobs[blockIdx.x];
+    const MgkGraphDesc g1 = X.graphs[job.g1];
+    const MgkGraphDesc g2 = Y.graphs[job.g2];
+    const int n1 = g1.n, n2 = g2.n, N = n1 * n2, z1 = g1.nnz, len2 = g2.lane_len;
+    const MgkRegsPlan L = mgk_regs_plan(n1, n2, W, EPT);
+
+    float* p = reinterpret_cast<float*>(lds);          // L.p == 0
+    float* y = reinterpret_cast<float*>(lds) + NP;     // L.y == NP
+    float* x = reinterpret_cast<float*>(lds) + 2 * NP; // L.x == 2 NP
+    float* dq1 = reinterpret_cast<float*>(lds + L.vtx1);   // d_i = rowsum + q
+    float* st1 = dq1 + n1;                                 // start probability
+    int* lb1 = reinterpret_cast<int*>(st1 + n1);           // vertex label
+    float* dq2 = reinterpret_cast<float*>(lds + L.vtx2);
+    float* st2 = dq2 + n2;
+    int* lb2 = reinterpret_cast<int*>(st2 + n2);
+    float* red = reinterpret_cast<float*>(lds + L.red);
+
+    // ---- stage per-vertex data; clear y (entries no row pair reaches stay 0) ----
+    for (int v = tid; v < n1; v += NT) {
+        dq1[v] = X.rowsum[g1.voff + v] + prm.q;
+        st1[v] = X.start[g1.voff + v];
+        lb1[v] = X.vlabel[g1.voff + v];
+    }
+    for (int v = tid; v < n2; v += NT) {
+        dq2[v] = Y.rowsum[g2.voff + v] + prm.q;
+        st2[v] = Y.start[g2.voff + v];
+        lb2[v] = Y.vlabel[g2.voff + v];
+    }
+#pragma unroll
+    for (int m = 0; m < EPT; ++m) y[tid + m * NT] = 0.f;
+
+    // ---- this wave's outer rows: whole rows, about z1 / W nonzeros ----------------
+    // first row whose first nonzero is at or after `target` (rowptr is non-decreasing)
+    const int share = max((z1 + W - 1) / W, 1);
+    int rbeg = 0, rend = n1;
+    {
+        int cb = 0, ce = 0;
+        for (int r0 = 0; r0 < n1; r0 += 64) {
+            const int r = r0 + lane;
+            const int rp = r < n1 ? X.rowptr[g1.voff + r] : 0x7fffffff;
+            cb += __popcll(__ballot(rp < wave * share));
+            ce += __popcll(__ballot(rp < (wave + 1) * share));
+        }
+        if (wave > 0) rbeg = cb;
+        if (wave < W - 1) rend = ce;
+    }
+    int kbeg = rbeg < n1 ? X.rowptr[g1.voff + rbeg] : z1;
+    int kend = rend < n1 ? X.rowptr[g1.voff + rend] : z1;
+    kbeg = __builtin_amdgcn_readfirstlane(kbeg);
+    kend = __builtin_amdgcn_readfirstlane(kend);
+    const int S = min(kend - kbeg, SMAX);   // the host only sends pairs whose runs fit
+
+    // lane l < S holds the wave's l-th outer nonzero
+    const bool live1 = lane < S;
+    const MgkEntry o = live1 ? X.list_outer[g1.zoff + kbeg + lane] : MgkEntry{0u, 0u, 0u, 0u};
+    const uint32_t v_poff = o.y * (uint32_t)(n2 * 4);   // byte offset of row j of p
+    const uint32_t v_yoff = o.x * (uint32_t)(n2 * 4);   // byte offset of row i of y
+    const uint64_t rowmask = __ballot(live1 && (o.w >> 31) != 0u);
+    const float w1 = live1 ? __uint_as_float(o.w & 0x7fffffffu) : 0.f;
+    // lanes past the run: a label so far away that kappa_e underflows to exactly 0
+    const float e1s = live1 ? (__uint_as_float(o.z) - prm.e_shift) * prm.e_scale : 1e18f;
+    const float l1 = weighted ? __log2f(live1 ? w1 : 1.f) : 0.f;
+
+    // ---- inner nonzeros of this lane, one per chunk; matrix entries into registers --
+    InnerLanes<C> in;
+    float kap[C][SMAX];
+    {
+        float e2s[C], l2[C], w2c[C];
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const int slot = c * 64 + lane;
+            const MgkEntry e = slot < len2 ? Y.list_inner[g2.loff + slot] : MgkEntry{0u, 0u, 0u, 0u};
+            in.ip[c] = (e.x & 0xfffffu) * 4u;
+            in.jp[c] = e.y * 4u;
+            const uint32_t rank = (e.x >> 20) & 0xffu;
+            in.last[c] = (e.x >> 31) != 0u;
+            in.m1[c] = rank >= 1 ? 1.f : 0.f;
+            in.m2[c] = rank >= 2 ? 1.f : 0.f;
+            const float w2 = __uint_as_float(e.w);   // 0 on idle slots
+            e2s[c] = (__uint_as_float(e.z) - prm.e_shift) * prm.e_scale;
+            l2[c] = w2 > 0.f ? (weighted ? __log2f(w2) : 0.f) : -__builtin_inff();
+            w2c[c] = w2 * prm.ke_const;
+        }
+        if (prm.edge_kernel == MGK_EK_SE) {
+            if (weighted) fill_se<0, SMAX, C, true>(kap, S, e2s, l2, e1s, l1);
+            else fill_se<0, SMAX, C, false>(kap, S, e2s, l2, e1s, l1);
+        } else {
+            fill_const<0, SMAX, C>(kap, S, w2c, w1);
+        }
+    }
+    __syncthreads();   // per-vertex data staged
+
+    // ---- Alg. 1 set-up: M = D_x V_x^{-1}, x = 0, r = b = D_x q_x, z = M^{-1} r,
+    //      p = z, rho = r^T z ----------------------------------------------------
+    float rr_[EPT], Mr[EPT], pr[EPT], zr[EPT];   // x stays in LDS: touched once per iteration
+    const float qq = prm.q * prm.q;
+    const float inv_n2 = 1.0f / (float)n2;
+    const float inv_h = 1.0f / prm.h;
+    float s_rz = 0.f, s_bb = 0.f;
+#pragma unroll
+    for (int m = 0; m < EPT; ++m) {
+        const int idx = tid + m * NT;
+        const bool ok = idx < N;
+        const int ic = ok ? idx : 0;
+        const int i = (int)(((float)ic + 0.5f) * inv_n2);
+        const int i2 = ic - i * n2;
+        const bool same = lb1[i] == lb2[i2];
+        const float dd = dq1[i] * dq2[i2];
+        const float b = ok ? dd * qq : 0.f;
+        const float z0 = ok ? (same ? qq : prm.h * qq) : 0.f;  // M^{-1} b = kappa_v q q'
+        Mr[m] = ok ? (same ? dd : dd * inv_h) : 1.f;           // d d' / kappa_v
+        rr_[m] = b;
+        pr[m] = z0;
+        p[idx] = z0;                                           // padding holds 0
+        x[idx] = 0.f;
+        s_rz = __builtin_fmaf(b, z0, s_rz);
+        s_bb = __builtin_fmaf(b, b, s_bb);
+    }
+    block_sum2<W>(s_rz, s_bb, red, wave, lane);
+    float rho = s_rz;
+    const float thresh = prm.rtol2 * s_bb;
+    int max_iter = prm.max_iter;
+    if (max_iter <= 0) max_iter = min(2 * N, 1000);
+    __syncthreads();  // p and the cleared y are complete
+
+    const char* pbytes = reinterpret_cast<const char*>(p);
+    char* ybytes = reinterpret_cast<char*>(y);
+
+    int it = 0;
+    int flag = 1;
+    while (it < max_iter) {
+        // ---- XMV: y_ii' = sum_{j,j'} A_ij A'_i'j' kappa_e(E_ij,E'_i'j') p_jj', entries from registers
+        if (S > 0) {
+            float acc[C], pv[4][C];
+#pragma unroll
+            for (int c = 0; c < C; ++c) acc[c] = 0.f;
+            gather4<0, C>(pv, in, v_poff, pbytes);
+            xmv_steps<0, SMAX, C>(kap, in, acc, pv, S, rowmask, v_poff, v_yoff, pbytes, ybytes);
+        }
+        __syncthreads();
+
+        // ---- a = M p - y ; alpha = rho / p^T a
+        float s_pa = 0.f;
+#pragma unroll
+        for (int m = 0; m < EPT; ++m) {
+            zr[m] = __builtin_fmaf(Mr[m], pr[m], -y[tid + m * NT]);
+            s_pa = __builtin_fmaf(pr[m], zr[m], s_pa);
+        }
+        const float pa = block_sum<W>(s_pa, red + 32, wave, lane);
+        const float alpha = rho * __builtin_amdgcn_rcpf(pa);
+
+        // ---- x += alpha p; r -= alpha a; z = M^{-1} r; rho' = r^T z
+        float s_rz2 = 0.f, s_rr = 0.f;
+#pragma unroll
+        for (int m = 0; m < EPT; ++m) {
+            x[tid + m * NT] = __builtin_fmaf(alpha, pr[m], x[tid + m * NT]);
+            const float rv = __builtin_fmaf(-alpha, zr[m], rr_[m]);
+            rr_[m] = rv;
+            const float zv = rv * __builtin_amdgcn_rcpf(Mr[m]);
+            zr[m] = zv;
+            s_rz2 = __builtin_fmaf(rv, zv, s_rz2);
+            s_rr = __builtin_fmaf(rv, rv, s_rr);
+        }
+        block_sum2<W>(s_rz2, s_rr, red, wave, lane);
+        ++it;
+
+        // ---- p = z + beta p (also after the last iteration, where it is not used: the
+        //      loop then has a single exit and the register blocks stay in place)
+        const float beta = s_rz2 * __builtin_amdgcn_rcpf(rho);
+        rho = s_rz2;
+#pragma unroll
+        for (int m = 0; m < EPT; ++m) {
+            const float pn = __builtin_fmaf(beta, pr[m], zr[m]);
+            pr[m] = pn;
+            p[tid + m * NT] = pn;
+        }
+        __syncthreads();
+        if (s_rr <= thresh) { flag = 0; break; }
+    }
+
+    // ---- K = p_x^T x (Eq. 1); every thread reads back the x elements it wrote
+    float s_k = 0.f;
+#pragma unroll
+    for (int m = 0; m < EPT; ++m) {
+        const int idx = tid + m * NT;
+        const int ic = idx < N ? idx : 0;
+        const int i = (int)(((float)ic + 0.5f) * inv_n2);
+        const int i2 = ic - i * n2;
+        s_k = __builtin_fmaf(st1[i] * st2[i2], x[idx], s_k);  // x is 0 beyond N
+    }
+    const float Kval = block_sum<W>(s_k, red + 48, wave, lane);
+    if (tid == 0) {
+        out.K[job.out0] = Kval;
+        if (job.out1 >= 0) out.K[job.out1] = Kval;
+        if (out.iters) {
+            out.iters[job.out0] = it;
+            if (job.out1 >= 0) out.iters[job.out1] = it;
+        }
+        if (out.flags) {
+            out.flags[job.out0] = flag;
+            if (job.out1 >= 0) out.flags[job.out1] = flag;
+        }
+    }
+    // ---- nodal similarity: x itself, in the original numbering of the requested pair
+    if (out.nodal) {
+        float* dst = out.nodal + out.nodal_off[job.out0];
+        const bool swapped = job.out1 == MGK_OUT1_SWAPPED;
+#pragma unroll
+        for (int m = 0; m < EPT; ++m) {
+            const int idx = tid + m * NT;
+            if (idx < N) {
+                const int i = (int)(((float)idx + 0.5f) * inv_n2);
+                const int i2 = idx - i * n2;
+                const int oi = X.iperm[g1.voff + i], oi2 = Y.iperm[g2.voff + i2];
+                dst[swapped ? oi2 * n1 + oi : oi * n2 + oi2] = x[idx];
+            }
+        }
+    }
+}
+
+template <int W, int SMAX, int EPT, int C>
+hipError_t launch_one(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkJob* jobs, int n_jobs,
+                      const MgkParams& prm, bool weighted, size_t lds_bytes, const MgkOutputs& out,
+                      hipStream_t stream) {
+    auto kern = mgk_pcg_regs<W, SMAX, EPT, C>;
+    static bool configured = false;  // per instantiation
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           MGK_LDS_LIMIT_BYTES);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(n_jobs), dim3(W * 64), lds_bytes, stream, X, Y, jobs, prm, out,
+                       weighted ? 1 : 0);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+#if !defined(MGK_REGS_CHUNKS) || !defined(MGK_REGS_WAVES)
+#error "compile with -DMGK_REGS_WAVES=<4|8> -DMGK_REGS_CHUNKS=<1|2>"
+#endif
+
+#define MGK_CAT2(a, b, c, d) a##b##c##d
+#define MGK_CAT(a, b, c, d) MGK_CAT2(a, b, c, d)
+
+// One translation unit per (wavefronts, chunk count) keeps the build parallel.
+hipError_t MGK_CAT(mgk_launch_regs_w, MGK_REGS_WAVES, _c, MGK_REGS_CHUNKS)(
+    int ept, bool weighted, const MgkBatchDev& X, const MgkBatchDev& Y, const MgkJob* jobs_dev,
+    int n_jobs, const MgkParams& prm, size_t lds_bytes, const MgkOutputs& out, hipStream_t stream) {
+    if (n_jobs <= 0) return hipSuccess;
+    constexpr int C = MGK_REGS_CHUNKS;
+    constexpr int W = MGK_REGS_WAVES;
+    constexpr int SMAX = W == 4 ? MGK_REGS_SMAX_W4 : MGK_REGS_SMAX_W8;
+    switch (ept) {
+#define MGK_CASE(E) \
+    case E: return launch_one<W, SMAX, E, C>(X, Y, jobs_dev, n_jobs, prm, weighted, lds_bytes, out, stream);
+        MGK_CASE(1) MGK_CASE(2) MGK_CASE(3) MGK_CASE(4) MGK_CASE(5) MGK_CASE(6) MGK_CASE(7) MGK_CASE(8)
+#undef MGK_CASE
+        default: return hipErrorInvalidValue;
+    }
+}

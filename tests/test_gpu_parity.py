@@ -60,7 +60,7 @@ def test_config0_full_gram(torch, solver):
     assert (fl == 0).all() and (it > 0).all()
 
 
-@pytest.mark.parametrize("waves", [1, 2, 4, 8, 16])
+@pytest.mark.parametrize("waves", [0, 1, 2, 4, 8, 16])
 def test_config1_full_gram_all_workgroup_sizes(torch, solver, waves):
     wb = W.config1()
     solver.set_solver(1e-6, 0)
@@ -387,6 +387,57 @@ def test_nodal_similarity_and_normalized_gram(torch, solver):
     dg = np.sqrt(np.diag(Kg))
     np.testing.assert_allclose(Kt.cpu().numpy(), Kg / np.outer(dg, dg), rtol=1e-5)
     assert np.allclose(np.diag(Kt.cpu().numpy()), 1.0, atol=1e-6)
+
+
+@pytest.mark.parametrize("cache", [True, False])
+def test_small_weighted_pairs_on_both_onchip_solvers(torch, solver, cache):
+    """Molecule-sized weighted graphs from two batches, with the matrix entries kept in
+    registers (cache) and regenerated every iteration: values and nodal solutions in
+    both argument orders, square-exponential and constant edge kernels."""
+    rng = np.random.default_rng(23)
+    prm = W.KernelParams(q=0.07, h=0.4, length_scale=0.3)
+    X = W.molecule_like_batch(rng, 5, 12, 30, prm)
+    Y = W.molecule_like_batch(rng, 4, 30, 60, prm)
+    for b in (X, Y):
+        b.weight = rng.uniform(0.4, 1.6, len(b.weight)).astype(np.float32)
+    X = W.permute_vertices(X, rng)
+    Y = W.permute_vertices(Y, rng)
+    solver.configure(prm)
+    solver.set_solver(1e-6, 0)
+    solver.set_launch(0)
+    solver.set_product_cache(cache)
+    try:
+        BX = solver.load_batch(X); BY = solver.load_batch(Y)
+        pi = np.repeat(np.arange(5), 4).astype(np.int32); pj = np.tile(np.arange(4), 5).astype(np.int32)
+        sizes = X.sizes()[pi] * Y.sizes()[pj]
+        off = np.concatenate([[0], np.cumsum(sizes)[:-1]]).astype(np.int64)
+        refs = [C.pair_nodal(X.graph(int(i)), Y.graph(int(j)), prm.q, prm.h, prm.length_scale) for i, j in zip(pi, pj)]
+        for (A, B, ai, bi, transposed) in ((BX, BY, pi, pj, False), (BY, BX, pj, pi, True)):
+            K = torch.zeros(len(pi), dtype=torch.float32, device="cuda")
+            x = torch.full((int(sizes.sum()),), float("nan"), dtype=torch.float32, device="cuda")
+            fl = torch.full((len(pi),), -1, dtype=torch.int32, device="cuda")
+            solver.pairs_nodal(A, B, ai, bi, K, x, off, None, fl)
+            torch.cuda.synchronize()
+            xs = x.cpu().numpy().astype(np.float64); Ks = K.cpu().numpy()
+            assert (fl.cpu().numpy() == 0).all()
+            for k, (Kref, xref) in enumerate(refs):
+                got = xs[off[k]:off[k] + sizes[k]]
+                got = got.reshape(xref.shape[::-1]).T if transposed else got.reshape(xref.shape)
+                np.testing.assert_allclose(got, xref, rtol=RTOL, atol=RTOL * np.abs(xref).max())
+                assert Ks[k] == pytest.approx(Kref, rel=RTOL)
+        # constant edge kernel on the same weighted graphs: labels all equal in the oracle
+        solver.set_edge_kernel_const(1.0)
+        Kc, _, flc = run_pairs(torch, solver, BX, BY, pi, pj)
+        X0 = W.GraphBatch(X.vtx_off, X.vtx_label, X.edge_off, X.src, X.dst, X.weight,
+                          np.zeros_like(X.edge_label), prm)
+        Y0 = W.GraphBatch(Y.vtx_off, Y.vtx_label, Y.edge_off, Y.src, Y.dst, Y.weight,
+                          np.zeros_like(Y.edge_label), prm)
+        refc = [C.pair_nodal(X0.graph(int(i)), Y0.graph(int(j)), prm.q, prm.h, prm.length_scale)[0]
+                for i, j in zip(pi, pj)]
+        np.testing.assert_allclose(Kc, refc, rtol=RTOL)
+        assert (flc == 0).all()
+    finally:
+        solver.set_product_cache(True)
 
 
 def test_edge_cases(torch, solver):
