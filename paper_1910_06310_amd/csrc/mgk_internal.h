@@ -148,8 +148,8 @@ static inline MGK_HD MgkSmallPlan mgk_small_plan(int32_t n1, int32_t n2, int32_t
 // rows of at most SMAX nonzeros and keeps the off-diagonal matrix entries
 // A_ij A'_i'j' kappa_e(E_ij, E'_i'j') of (its outer nonzeros) x (all inner lane
 // slots) in registers for the whole solve; the inner graph takes `chunks`
-// 64-lane chunks and has rows of at most 4 nonzeros.  LDS holds p, y and x
-// (padded to the register blocks), the per-vertex data of both graphs and the
+// 64-lane chunks and has rows of at most 4 nonzeros.  LDS holds p, y, x and a
+// dump area (each padded to the register blocks), the per-vertex data of both graphs and the
 // reduction scratch.
 #define MGK_REGS_SMAX_W4 24      // longest run of outer nonzeros per wavefront, 4 wavefronts
 #define MGK_REGS_SMAX_W8 20      // the same with 8 wavefronts
@@ -158,7 +158,7 @@ static inline MGK_HD MgkSmallPlan mgk_small_plan(int32_t n1, int32_t n2, int32_t
 #define MGK_REGS_MAX_DEG 4       // inner rows: two shift-and-add steps
 
 struct MgkRegsPlan {
-    int32_t p, y, x, vtx1, vtx2, red, total;  // words
+    int32_t p, y, x, dump, vtx1, vtx2, red, total;  // words
 };
 
 static inline MGK_HD MgkRegsPlan mgk_regs_plan(int32_t n1, int32_t n2, int32_t waves, int32_t ept) {
@@ -167,7 +167,8 @@ static inline MGK_HD MgkRegsPlan mgk_regs_plan(int32_t n1, int32_t n2, int32_t w
     L.p = 0;
     L.y = np;
     L.x = 2 * np;
-    L.vtx1 = 3 * np;
+    L.dump = 3 * np;   // same shape as y, 2 np behind it: where lanes that hold no row sum store
+    L.vtx1 = 4 * np;
     L.vtx2 = L.vtx1 + 3 * n1;
     L.red = (L.vtx2 + 3 * n2 + 3) & ~3;
     L.total = L.red + 64;

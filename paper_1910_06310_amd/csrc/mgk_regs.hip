@@ -90,9 +90,10 @@ __device__ __forceinline__ void fill_const(float (&kap)[C][SMAX], int S, const f
 // per-lane constants of the inner nonzeros, one set per chunk
 template <int C>
 struct InnerLanes {
-    uint32_t jp[C], ip[C];            // byte offsets of column j' in a p row, of row i' in a y row
+    uint32_t jp[C];                   // byte offset of column j' in a row of p
+    uint32_t ip[C];                   // byte offset of row i' in a row of y; lanes that are not the
+                                      // last of their run point the same distance into the dump area
     float m1[C], m2[C];               // 1 if the lane is at least that far into its run, else 0
-    bool last[C];                     // the lane writes the row sum
 };
 
 // Gathered reads of p for outer nonzeros K0 .. K0+3 (lanes past the wave's run hold
@@ -109,42 +110,74 @@ __device__ __forceinline__ void gather4(float (&pv)[4][C], const InnerLanes<C>& 
     }
 }
 
-// XMV steps K0 .. : the reads of p for the next four outer nonzeros are issued
-// before the four already read are used, so that the LDS latency overlaps the
-// arithmetic.  Multiply-add per entry; at the end of an outer row (wave-uniform
-// test) each inner row is summed over its lanes (rows of at most 4 nonzeros:
-// two shift-and-add steps) and y_ii' stored from the last lane of the row.
+// acc[c] += m1 * (acc[c] one lane down) and then += m2 * (two lanes down), inside rows of
+// 16 lanes: the sum over an inner row of at most 4 nonzeros arrives in its last lane.
+// The DPP reads need two wait states after the write of the register they read; with two
+// chunks the steps of one chunk fill part of the other's.
+template <int C>
+__device__ __forceinline__ void row_sums(float (&acc)[C], const InnerLanes<C>& in) {
+    static_assert(C == 1 || C == 2, "one or two chunks");
+    if constexpr (C == 1) {
+        asm volatile(
+            "s_nop 1\n\tv_fmac_f32_dpp %0, %0, %1 row_shr:1 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+            "s_nop 1\n\tv_fmac_f32_dpp %0, %0, %2 row_shr:2 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+            : "+v"(acc[0])
+            : "v"(in.m1[0]), "v"(in.m2[0]));
+    } else {
+        asm volatile(
+            "s_nop 1\n\tv_fmac_f32_dpp %0, %0, %2 row_shr:1 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+            "v_fmac_f32_dpp %1, %1, %3 row_shr:1 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+            "s_nop 0\n\tv_fmac_f32_dpp %0, %0, %4 row_shr:2 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+            "v_fmac_f32_dpp %1, %1, %5 row_shr:2 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+            : "+v"(acc[0]), "+v"(acc[1])
+            : "v"(in.m1[0]), "v"(in.m1[1]), "v"(in.m2[0]), "v"(in.m2[1]));
+    }
+}
+
+// Multiply-add of outer nonzeros K0 .. K0+3 (p values already read into pv); at the
+// end of an outer row (wave-uniform test) each inner row is summed over its lanes
+// (rows of at most 4 nonzeros: two shift-and-add steps) and y_ii' stored from the
+// last lane of the row.
+template <int K0, int SMAX, int C>
+__device__ __forceinline__ void use4(const float (&kap)[C][SMAX], const InnerLanes<C>& in,
+                                     float (&acc)[C], const float (&pv)[4][C], uint64_t rowmask,
+                                     uint32_t v_yoff, char* ybytes) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+#pragma unroll
+        for (int c = 0; c < C; ++c) acc[c] = __builtin_fmaf(kap[c][K0 + u], pv[u][c], acc[c]);
+        if ((rowmask >> (K0 + u)) & 1ull) {
+            const uint32_t yo = lane_value(v_yoff, K0 + u);
+            row_sums<C>(acc, in);
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                // every lane stores: the last lane of an inner row to y_ii', the others to
+                // the same place in a dump area behind y (no divergent region)
+                *reinterpret_cast<float*>(ybytes + (yo + in.ip[c])) = acc[c];
+                acc[c] = 0.f;
+            }
+        }
+    }
+}
+
+// XMV steps K0 .. (K0 < S on entry): the reads of p for the next four outer
+// nonzeros are issued before the four already read are used, so that the LDS
+// latency overlaps the arithmetic.
 template <int K0, int SMAX, int C>
 __device__ __forceinline__ void xmv_steps(const float (&kap)[C][SMAX], const InnerLanes<C>& in,
                                           float (&acc)[C], const float (&pv)[4][C], int S,
                                           uint64_t rowmask, uint32_t v_poff, uint32_t v_yoff,
                                           const char* pbytes, char* ybytes) {
-    if constexpr (K0 < SMAX) {
-        if (K0 >= S) return;
-        float nx[4][C];
-        if constexpr (K0 + 4 < SMAX) {
-            if (K0 + 4 < S) gather4<K0 + 4, C>(nx, in, v_poff, pbytes);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-#pragma unroll
-            for (int c = 0; c < C; ++c) acc[c] = __builtin_fmaf(kap[c][K0 + u], pv[u][c], acc[c]);
-            if ((rowmask >> (K0 + u)) & 1ull) {
-                const uint32_t yo = lane_value(v_yoff, K0 + u);
-#pragma unroll
-                for (int c = 0; c < C; ++c) acc[c] = shr_fmac<1>(acc[c], in.m1[c]);
-#pragma unroll
-                for (int c = 0; c < C; ++c) acc[c] = shr_fmac<2>(acc[c], in.m2[c]);
-#pragma unroll
-                for (int c = 0; c < C; ++c) {
-                    if (in.last[c]) *reinterpret_cast<float*>(ybytes + (yo + in.ip[c])) = acc[c];
-                    acc[c] = 0.f;
-                }
-            }
-        }
-        if constexpr (K0 + 4 < SMAX)
+    if constexpr (K0 + 4 < SMAX) {
+        if (K0 + 4 < S) {   // wave-uniform
+            float nx[4][C];
+            gather4<K0 + 4, C>(nx, in, v_poff, pbytes);
+            use4<K0, SMAX, C>(kap, in, acc, pv, rowmask, v_yoff, ybytes);
             xmv_steps<K0 + 4, SMAX, C>(kap, in, acc, nx, S, rowmask, v_poff, v_yoff, pbytes, ybytes);
+            return;
+        }
     }
+    use4<K0, SMAX, C>(kap, in, acc, pv, rowmask, v_yoff, ybytes);
 }
 
 template <int W, int SMAX, int EPT, int C>
@@ -165,7 +198,7 @@ __global__ __launch_bounds__(W * 64) void mgk_pcg_regs(MgkBatchDev X, MgkBatchDe
 
     float* p = reinterpret_cast<float*>(lds);          // L.p == 0
     float* y = reinterpret_cast<float*>(lds) + NP;     // L.y == NP
-    float* x = reinterpret_cast<float*>(lds) + 2 * NP; // L.x == 2 NP
+    float* x = reinterpret_cast<float*>(lds) + 2 * NP; // L.x == 2 NP; 3 NP .. 4 NP: dump area
     float* dq1 = reinterpret_cast<float*>(lds + L.vtx1);   // d_i = rowsum + q
     float* st1 = dq1 + n1;                                 // start probability
     int* lb1 = reinterpret_cast<int*>(st1 + n1);           // vertex label
@@ -229,10 +262,9 @@ __global__ __launch_bounds__(W * 64) void mgk_pcg_regs(MgkBatchDev X, MgkBatchDe
         for (int c = 0; c < C; ++c) {
             const int slot = c * 64 + lane;
             const MgkEntry e = slot < len2 ? Y.list_inner[g2.loff + slot] : MgkEntry{0u, 0u, 0u, 0u};
-            in.ip[c] = (e.x & 0xfffffu) * 4u;
+            in.ip[c] = (e.x & 0xfffffu) * 4u + ((e.x >> 31) != 0u ? 0u : (uint32_t)(2 * NP * 4));
             in.jp[c] = e.y * 4u;
             const uint32_t rank = (e.x >> 20) & 0xffu;
-            in.last[c] = (e.x >> 31) != 0u;
             in.m1[c] = rank >= 1 ? 1.f : 0.f;
             in.m2[c] = rank >= 2 ? 1.f : 0.f;
             const float w2 = __uint_as_float(e.w);   // 0 on idle slots
