@@ -166,7 +166,7 @@ int64_t regs_cost(const MgkGraphDesc& o, const MgkGraphDesc& i, int waves) {
     const int64_t N = (int64_t)o.n * i.n;
     const int64_t ept = std::max<int64_t>(1, (N + waves * 64 - 1) / (waves * 64));
     // register blocks that keep four wavefronts per SIMD resident
-    if (ept > (waves == 4 && chunks == 2 ? 6 : MGK_REGS_MAX_EPT)) return -1;
+    if (ept > MGK_REGS_MAX_EPT) return -1;
     return (int64_t)o.nnz * (1 + 2 * chunks) + (int64_t)o.n * (1 + 4 * chunks) +
            (int64_t)waves * (8 * ept + 45);
 }

@@ -347,7 +347,7 @@ __global__ __launch_bounds__(W * 64) void mgk_pcg_regs(MgkBatchDev X, MgkBatchDe
             x[tid + m * NT] = __builtin_fmaf(alpha, pr[m], x[tid + m * NT]);
             const float rv = __builtin_fmaf(-alpha, zr[m], rr_[m]);
             rr_[m] = rv;
-            const float zv = rv * __builtin_amdgcn_rcpf(Mr[m]);
+            const float zv = rv * __builtin_amdgcn_rcpf(Mr[m]);   // 1/M is hoisted by the compiler
             zr[m] = zv;
             s_rz2 = __builtin_fmaf(rv, zv, s_rz2);
             s_rr = __builtin_fmaf(rv, rv, s_rr);
