@@ -34,8 +34,9 @@ def hbm_traffic(workload, args):
     """HBM bytes per step from the committed counter summary (two rocprofv3 --pmc
     runs, FETCH_SIZE and WRITE_SIZE, each scaled by what the counter reads for a
     copy of known size).  Only for the exact workload it was measured on."""
-    path = os.path.join(ROOT, "profiles", "mgk_pcg_small_config4_hbm.json")
-    if workload != "config4" or args.graphs != 2000 or not os.path.exists(path):
+    path = os.path.join(ROOT, "profiles", "mgk_pcg_regs_config4_hbm.json")
+    if (workload != "config4" or args.graphs != 2000 or not args.product_cache or args.waves
+            or not os.path.exists(path)):
         return None
     with open(path) as fh:
         return json.load(fh)["bytes_per_step"]
@@ -199,8 +200,9 @@ def main() -> int:
         "load_and_pack_s": load_s, "first_call_s": first_s,
         "roofline": {
             "bound": "alu",
-            "kernel": "mgk_pcg_small" if wl in ("config4", "config1", "nws", "ba")
-                      else "mgk_large_xmv_dense_kernel / mgk_large_xmv_kernel (+ vector kernels)",
+            "kernel": ("mgk_pcg_regs" if wl in ("config4", "config1") and args.product_cache and not args.waves
+                       else "mgk_pcg_small" if wl in ("config4", "config1", "nws", "ba")
+                       else "mgk_large_xmv_dense_kernel / mgk_large_xmv_kernel (+ vector kernels)"),
             "achieved": achieved_tflops,
             "peak": FP32_VECTOR_PEAK_TFLOPS,
             "unit": "TFLOP/s",
