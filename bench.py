@@ -42,6 +42,88 @@ def hbm_traffic(workload, args):
         return json.load(fh)["bytes_per_step"]
 
 
+def _time_steps(torch, step, steps):
+    step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def ablation(args, torch, W, M) -> int:
+    """The paper's incremental study (Section VI, time to solution per optimisation level)
+    mapped onto this library's switches, on the paper's two synthetic sets and on the
+    benchmark workload, then Gram time and few-pair latency against the workgroup size.
+    Levels, each keeping everything of the one before:
+      tiles        non-empty octiles only, dense tile-pair product, vectors in global memory,
+                   graphs in the given vertex order            (paper: Sparse)
+      +reorder     PBR vertex order                            (paper: +Reorder)
+      +adaptive    dense or sparse product chosen per pair     (paper: +Adaptive)
+      +block       whole solve in one workgroup, both graphs and p, y shared in LDS,
+                   jobs in the given order                     (paper: +Block)
+      +dynsched    most expensive pairs first                  (paper: +DynSched)
+      +registers   off-diagonal entries of small pairs kept in registers (not in the paper)
+    The compact octile format (paper: +Compact) is the only storage format built, so it is
+    part of every level; the paper's naive dense level is not built."""
+    levels = [
+        ("tiles", dict(reorder=0, onchip=0, tile_path=2, sched=0, cache=0)),
+        ("+reorder", dict(reorder=1, onchip=0, tile_path=2, sched=0, cache=0)),
+        ("+adaptive", dict(reorder=1, onchip=0, tile_path=0, sched=0, cache=0)),
+        ("+block", dict(reorder=1, onchip=16384, tile_path=0, sched=0, cache=0)),
+        ("+dynsched", dict(reorder=1, onchip=16384, tile_path=0, sched=1, cache=0)),
+        ("+registers", dict(reorder=1, onchip=16384, tile_path=0, sched=1, cache=1)),
+    ]
+    solver = M.Solver(0)
+    for name in ("nws", "ba", "config4"):
+        wb = W.paper_synthetic(name) if name != "config4" else W.config4(args.graphs)
+        G = wb.n_graphs
+        K = torch.zeros((G, G), dtype=torch.float32, device="cuda")
+        solver.configure(wb.params)
+        solver.set_solver(1e-6, 0)
+        solver.set_launch(0)
+        batches = {}
+        for label, lv in levels:
+            if name == "config4" and lv["onchip"] == 0:
+                continue   # two million pairs with vectors in global memory do not fit
+            if lv["reorder"] not in batches:
+                batches[lv["reorder"]] = solver.load_batch(wb, reorder=lv["reorder"])
+            B = batches[lv["reorder"]]
+            solver.set_onchip_limit(lv["onchip"])
+            solver.set_tile_path(lv["tile_path"])
+            solver.set_schedule(bool(lv["sched"]))
+            solver.set_product_cache(bool(lv["cache"]))
+            ms = _time_steps(torch, lambda: solver.gram(B, K), args.steps)
+            print(json.dumps({"study": "levels", "workload": name, "level": label, "ms_per_gram": ms,
+                              "pairs_per_s": G * (G + 1) / 2 / (ms * 1e-3)}), flush=True)
+        for b in batches.values():
+            b.free()
+    # workgroup size against throughput (whole Gram) and latency (4 pairs alone), streaming
+    # on-chip kernel, graphs of 10-40 vertices (a size every workgroup size can hold; a
+    # pair too large for the requested size gets the next larger one)
+    wb = W.config1()
+    solver.configure(wb.params)
+    solver.set_product_cache(False)
+    B = solver.load_batch(wb)
+    K = torch.zeros((100, 100), dtype=torch.float32, device="cuda")
+    order = np.argsort(-wb.sizes())[:8].astype(np.int32)   # the four largest pairs
+    K4 = torch.zeros(4, dtype=torch.float32, device="cuda")
+    for waves in (1, 2, 4, 8, 16):
+        solver.set_launch(waves)
+        ms_g = _time_steps(torch, lambda: solver.gram(B, K), 20)
+        ms_p = _time_steps(torch, lambda: solver.pairs(B, B, order[:4], order[4:], K4), 50)
+        print(json.dumps({"study": "workgroup size", "workload": "config1", "waves_per_pair": waves,
+                          "ms_per_gram": ms_g, "ms_4_largest_pairs": ms_p}), flush=True)
+    solver.set_launch(0)
+    solver.set_product_cache(True)
+    ms_g = _time_steps(torch, lambda: solver.gram(B, K), 20)
+    ms_p = _time_steps(torch, lambda: solver.pairs(B, B, order[:4], order[4:], K4), 50)
+    print(json.dumps({"study": "workgroup size", "workload": "config1", "waves_per_pair": "auto, registers",
+                      "ms_per_gram": ms_g, "ms_4_largest_pairs": ms_p}), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -55,6 +137,9 @@ def main() -> int:
     ap.add_argument("--tile-path", type=int, default=0, help="global-memory solver: 0 auto, 1 sparse, 2 dense")
     ap.add_argument("--product-cache", type=int, default=1,
                     help="on-chip solver: 1 keep the matrix entries of small pairs in registers, 0 regenerate them")
+    ap.add_argument("--ablation", action="store_true",
+                    help="instead of the benchmark line: time the optimisation levels of the paper's "
+                         "incremental study and a workgroup-size sweep, one JSON line each")
     ap.add_argument("--cpu-sample", type=int, default=64, help="pairs timed on the CPU oracle (0 = skip)")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also run one device-to-device copy of this many MiB before the timed region; "
@@ -72,6 +157,9 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
+
+    if args.ablation:
+        return ablation(args, torch, W, M)
 
     wl = args.workload
     pair_list = None

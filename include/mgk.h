@@ -106,6 +106,12 @@ mgk_status mgk_set_onchip_limit(mgk_ctx* ctx, int32_t max_product);
  * rounding of the entries.  Ignored while mgk_set_launch forces a workgroup
  * size. */
 mgk_status mgk_set_product_cache(mgk_ctx* ctx, int32_t enable);
+/* Order of the on-chip jobs inside a launch (Section V-B, dynamic scheduling).
+ * 1 (default): most expensive pairs first, so that the hardware dispatcher,
+ * which hands workgroups to compute units as they free up, ends the launch with
+ * the cheapest pairs.  0: in the order the pairs were given.  The values do not
+ * depend on it. */
+mgk_status mgk_set_schedule(mgk_ctx* ctx, int32_t cost_sorted);
 
 /* ---- graphs -----------------------------------------------------------------
  * Load n_graphs graphs given in flat host arrays (all caller-owned, copied):

@@ -24,7 +24,7 @@ EXPORTS = [
     "mgk_create", "mgk_destroy", "mgk_last_error",
     "mgk_set_vertex_kernel_delta", "mgk_set_edge_kernel_se", "mgk_set_edge_kernel_const",
     "mgk_set_stop_prob", "mgk_set_solver", "mgk_set_tile_path", "mgk_set_launch",
-    "mgk_set_onchip_limit", "mgk_set_product_cache",
+    "mgk_set_onchip_limit", "mgk_set_product_cache", "mgk_set_schedule",
     "mgk_load_graphs", "mgk_free_batch", "mgk_batch_stats", "mgk_batch_permutation",
     "mgk_batch_get_tiles", "mgk_gram", "mgk_pairs", "mgk_pairs_nodal", "mgk_normalize_gram",
 ]
@@ -64,6 +64,7 @@ def load_library(path: Optional[str] = None):
     lib.mgk_set_launch.argtypes = [vp, i32]
     lib.mgk_set_onchip_limit.argtypes = [vp, i32]
     lib.mgk_set_product_cache.argtypes = [vp, i32]
+    lib.mgk_set_schedule.argtypes = [vp, i32]
     lib.mgk_load_graphs.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, c.POINTER(vp)]
     lib.mgk_free_batch.argtypes = [vp, vp]
     lib.mgk_free_batch.restype = None
@@ -198,6 +199,9 @@ class Solver:
 
     def set_onchip_limit(self, max_product: int = 16384):
         self._check(load_library().mgk_set_onchip_limit(self._h, max_product))
+
+    def set_schedule(self, cost_sorted: bool = True):
+        self._check(load_library().mgk_set_schedule(self._h, 1 if cost_sorted else 0))
 
     def set_product_cache(self, enable: bool = True):
         self._check(load_library().mgk_set_product_cache(self._h, 1 if enable else 0))

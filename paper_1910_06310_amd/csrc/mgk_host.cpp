@@ -68,6 +68,7 @@ struct mgk_batch {
     int gram_jobs_limit = 0;       // on-chip limit the list was built for
     int gram_jobs_tile_path = 0;   // tile path setting the list was built for
     int gram_jobs_cache = 0;       // product-cache setting the list was built for
+    int gram_jobs_sorted = 0;      // schedule setting the list was built for
 };
 
 struct mgk_ctx {
@@ -80,6 +81,7 @@ struct mgk_ctx {
     int waves = 0;
     int onchip_limit = MGK_SMALL_MAX_N;  // largest n n' given to the on-chip solver
     int product_cache = 1;      // small pairs keep their matrix entries in registers
+    int cost_sorted = 1;        // expensive pairs first inside a launch
     JobList pair_jobs;          // reused by mgk_pairs
     int64_t pair_jobs_cap = 0;
     hipStream_t pair_jobs_stream = nullptr;
@@ -227,17 +229,75 @@ struct HostJob {
     bool atomic_rows, swapped;
 };
 
+// A launch shape with few jobs costs more in launch and drain time than its pairs
+// gain from the exact fit: such jobs move to the closest larger shape that can run
+// them (same solver and workgroup size, at least as many elements per thread and
+// inner chunks).  Only the vector blocks grow, so the LDS need grows by the
+// difference of the padded vector lengths.
+constexpr int64_t kMinJobsPerLaunch = 4096;
+
+void merge_small_shapes(std::vector<HostJob>& jobs) {
+    struct Shape { int waves, ept, chunks; bool atomic_rows, swapped; int64_t count; };
+    auto same = [](const Shape& s, const HostJob& j) {
+        return s.waves == j.waves && s.ept == j.ept && s.chunks == j.chunks &&
+               s.atomic_rows == j.atomic_rows && s.swapped == j.swapped;
+    };
+    std::vector<Shape> frozen;   // shapes whose jobs would outgrow LDS in the larger shape
+    for (int round = 0; round < 64; ++round) {
+        std::vector<Shape> shapes;
+        for (const HostJob& j : jobs) {
+            auto it = std::find_if(shapes.begin(), shapes.end(), [&](const Shape& s) { return same(s, j); });
+            if (it == shapes.end()) shapes.push_back({j.waves, j.ept, j.chunks, j.atomic_rows, j.swapped, 1});
+            else it->count++;
+        }
+        // smallest shape below the threshold that has somewhere to go
+        const Shape* from = nullptr;
+        const Shape* to = nullptr;
+        for (const Shape& a : shapes) {
+            if (a.count >= kMinJobsPerLaunch) continue;
+            if (std::any_of(frozen.begin(), frozen.end(), [&](const Shape& f) {
+                    return f.waves == a.waves && f.ept == a.ept && f.chunks == a.chunks &&
+                           f.atomic_rows == a.atomic_rows && f.swapped == a.swapped; }))
+                continue;
+            const Shape* best = nullptr;
+            for (const Shape& b : shapes) {
+                if (&a == &b || a.waves != b.waves || a.atomic_rows != b.atomic_rows || a.swapped != b.swapped ||
+                    (a.chunks > 0) != (b.chunks > 0) || b.chunks < a.chunks || b.ept < a.ept)
+                    continue;
+                if (!best || b.ept * 4 + b.chunks < best->ept * 4 + best->chunks) best = &b;
+            }
+            if (best && (!from || a.ept * 4 + a.chunks < from->ept * 4 + from->chunks)) { from = &a; to = best; }
+        }
+        if (!from) return;
+        const int vectors = from->chunks > 0 ? 4 : 2;   // padded vectors in the LDS plan of each solver
+        bool fits = true;
+        for (const HostJob& j : jobs)
+            if (same(*from, j) &&
+                ((int64_t)j.lds_words + vectors * j.waves * 64 * (to->ept - j.ept)) * 4 > MGK_LDS_LIMIT_BYTES)
+                fits = false;
+        if (!fits) { frozen.push_back(*from); continue; }
+        for (HostJob& j : jobs)
+            if (same(*from, j)) {
+                j.lds_words += vectors * j.waves * 64 * (to->ept - j.ept);
+                j.ept = (int16_t)to->ept;
+                j.chunks = (int16_t)to->chunks;
+            }
+    }
+}
+
 mgk_status build_job_list(mgk_ctx* ctx, std::vector<HostJob>& jobs, JobList& out,
                           hipStream_t stream, int64_t* capacity) {
+    merge_small_shapes(jobs);
     // group by launch shape (largest first), inside a group big pairs start first
-    std::stable_sort(jobs.begin(), jobs.end(), [](const HostJob& a, const HostJob& b) {
+    const bool by_cost = ctx->cost_sorted != 0;
+    std::stable_sort(jobs.begin(), jobs.end(), [by_cost](const HostJob& a, const HostJob& b) {
         const int ka = a.waves * 64 * a.ept, kb = b.waves * 64 * b.ept;
         if (ka != kb) return ka > kb;
         if (a.waves != b.waves) return a.waves > b.waves;
         if (a.chunks != b.chunks) return a.chunks > b.chunks;
         if (a.atomic_rows != b.atomic_rows) return a.atomic_rows;
         if (a.swapped != b.swapped) return b.swapped;
-        return a.cost > b.cost;
+        return by_cost && a.cost > b.cost;
     });
     out.bins.clear();
     out.n = (int64_t)jobs.size();
@@ -535,6 +595,13 @@ mgk_status mgk_set_product_cache(mgk_ctx* ctx, int32_t enable) {
     if (!ctx) return MGK_EINVAL;
     if (enable != 0 && enable != 1) return fail(ctx, MGK_EINVAL, "product cache must be 0 or 1, got %d", enable);
     ctx->product_cache = enable;
+    return MGK_OK;
+}
+
+mgk_status mgk_set_schedule(mgk_ctx* ctx, int32_t cost_sorted) {
+    if (!ctx) return MGK_EINVAL;
+    if (cost_sorted != 0 && cost_sorted != 1) return fail(ctx, MGK_EINVAL, "schedule must be 0 or 1, got %d", cost_sorted);
+    ctx->cost_sorted = cost_sorted;
     return MGK_OK;
 }
 
@@ -859,7 +926,7 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
     if (batch->gram_jobs.dev != nullptr &&
         (batch->gram_jobs_waves != ctx->waves || batch->gram_jobs_max_iter != ctx->max_iter ||
          batch->gram_jobs_limit != ctx->onchip_limit || batch->gram_jobs_tile_path != ctx->tile_path ||
-         batch->gram_jobs_cache != ctx->product_cache)) {
+         batch->gram_jobs_cache != ctx->product_cache || batch->gram_jobs_sorted != ctx->cost_sorted)) {
         MGK_HIP(ctx, hipStreamSynchronize(stream));  // launch shape changed: rebuild the job list
         MGK_HIP(ctx, hipFree(batch->gram_jobs.dev));
         batch->gram_jobs.dev = nullptr;
@@ -902,6 +969,7 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
         batch->gram_jobs_limit = ctx->onchip_limit;
         batch->gram_jobs_tile_path = ctx->tile_path;
         batch->gram_jobs_cache = ctx->product_cache;
+        batch->gram_jobs_sorted = ctx->cost_sorted;
         if (st != MGK_OK) return st;
     }
     const MgkOutputs out{K_dev, iters_dev, flag_dev, nullptr, nullptr};
