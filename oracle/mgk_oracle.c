@@ -13,7 +13,9 @@
  *
  * Readings: product index (i,i') -> i*n'+i'; d_i = sum_j A_ij + q; q_i = q;
  * p_i = 1/n unless given; kappa_v = 1 if labels equal else h;
- * kappa_e = exp(-(e-e')^2 / (2 l^2)).
+ * kappa_e = exp(-(e-e')^2 / (2 l^2)), or one of the other examples of Appendix B
+ * chosen with mgk_oracle_set_edge_kernel (compact polynomial, Kronecker product
+ * of square exponentials over label attributes, R-convolution over label parts).
  *
  * Parallelism (OpenMP) is over pairs in tier 0 and over rows of G inside a
  * pair in tier 1; it changes no arithmetic of a single pair in tier 0.
@@ -26,6 +28,23 @@
 #include <omp.h>
 #endif
 
+/* Edge base kernel in force (process-wide; the callers are single-threaded at this
+ * level).  kind 0: square exponential with the length scale each call passes.
+ * kind 1: compact polynomial, par = {rho, number of coefficients, c0, c1, ...}:
+ *   sum_i c_i r^i for r = |e-e'|/rho < 1, else 0.
+ * kind 2: product over dim attributes of exp(-(e_a-e'_a)^2/(2 l_a^2)), par = {l_0, ...}.
+ * kind 3: (1/dim^2) sum_a sum_b exp(-(e_a-e'_b)^2/(2 l^2)), par = {l}. */
+typedef struct { int kind, dim; double par[16]; } okern;
+static okern g_kern = {0, 1, {0}};
+
+int mgk_oracle_set_edge_kernel(int32_t kind, int32_t dim, const double* par, int32_t n_par) {
+    if (kind < 0 || kind > 3 || dim < 1 || dim > 8 || n_par < 0 || n_par > 16) return -5;
+    if (kind < 2 && dim != 1) return -5;
+    g_kern.kind = kind; g_kern.dim = dim;
+    for (int i = 0; i < 16; ++i) g_kern.par[i] = i < n_par ? par[i] : 0.0;
+    return 0;
+}
+
 typedef struct {
     int n;           /* vertices */
     int z;           /* directed (stored) nonzeros = 2 * edges */
@@ -34,7 +53,7 @@ typedef struct {
     int* rowptr;     /* [n+1] CSR over directed edges */
     int* col;        /* [z] */
     double* w;       /* [z] */
-    double* e;       /* [z] */
+    double* e;       /* [z][dim]: dim label attributes per nonzero */
     double* deg;     /* [n], sum_j A_ij + q */
 } ograph;
 
@@ -45,7 +64,8 @@ static int build_graph(ograph* g, int n, const int32_t* label, const double* sta
     g->rowptr = (int*)calloc((size_t)n + 1, sizeof(int));
     g->col = (int*)malloc(sizeof(int) * (size_t)(2 * m + 1));
     g->w = (double*)malloc(sizeof(double) * (size_t)(2 * m + 1));
-    g->e = (double*)malloc(sizeof(double) * (size_t)(2 * m + 1));
+    const int dim = g_kern.dim;
+    g->e = (double*)malloc(sizeof(double) * (size_t)(2 * m + 1) * (size_t)dim);
     g->deg = (double*)malloc(sizeof(double) * (size_t)(n + 1));
     if (!g->rowptr || !g->col || !g->w || !g->e || !g->deg) return -1;
     for (int k = 0; k < m; ++k) {
@@ -59,8 +79,12 @@ static int build_graph(ograph* g, int n, const int32_t* label, const double* sta
     for (int k = 0; k < m; ++k) {
         int a = src[k], b = dst[k];
         int pa = cur[a]++, pb = cur[b]++;
-        g->col[pa] = b; g->w[pa] = (double)weight[k]; g->e[pa] = (double)elabel[k];
-        g->col[pb] = a; g->w[pb] = (double)weight[k]; g->e[pb] = (double)elabel[k];
+        g->col[pa] = b; g->w[pa] = (double)weight[k];
+        g->col[pb] = a; g->w[pb] = (double)weight[k];
+        for (int t = 0; t < dim; ++t) {
+            g->e[(size_t)pa * dim + t] = (double)elabel[(size_t)k * dim + t];
+            g->e[(size_t)pb * dim + t] = (double)elabel[(size_t)k * dim + t];
+        }
     }
     free(cur);
     for (int i = 0; i < n; ++i) {
@@ -76,7 +100,34 @@ static void free_graph(ograph* g) {
 }
 
 static double kv(int a, int b, double h) { return a == b ? 1.0 : h; }
-static double ke(double e1, double e2, double alpha) { double d = e1 - e2; return exp(-alpha * d * d); }
+/* kappa_e of two labels (dim attributes each); alpha = 1/(2 l^2) of the call for kind 0 */
+static double ke(const double* e1, const double* e2, double alpha) {
+    const okern* kn = &g_kern;
+    if (kn->kind == 0) { double d = e1[0] - e2[0]; return exp(-alpha * d * d); }
+    if (kn->kind == 1) {
+        double r = fabs(e1[0] - e2[0]) / kn->par[0];
+        if (!(r < 1.0)) return 0.0;
+        int nc = (int)kn->par[1];
+        double v = 0.0, rp = 1.0;
+        for (int i = 0; i < nc; ++i) { v += kn->par[2 + i] * rp; rp *= r; }
+        return v;
+    }
+    if (kn->kind == 2) {
+        double v = 1.0;
+        for (int a = 0; a < kn->dim; ++a) {
+            double d = e1[a] - e2[a], l = kn->par[a];
+            v *= exp(-d * d / (2.0 * l * l));
+        }
+        return v;
+    }
+    double v = 0.0, l = kn->par[0];
+    for (int a = 0; a < kn->dim; ++a)
+        for (int b = 0; b < kn->dim; ++b) {
+            double d = e1[a] - e2[b];
+            v += exp(-d * d / (2.0 * l * l));
+        }
+    return v / (double)(kn->dim * kn->dim);
+}
 static double pstart(const ograph* g, int i) { return g->start ? g->start[i] : 1.0 / (double)g->n; }
 
 /* ---- tier 0: dense assemble + Cholesky ---------------------------------- */
@@ -94,7 +145,7 @@ static int pair_dense(const ograph* g1, const ograph* g2, double q, double h, do
             for (int k = g1->rowptr[i]; k < g1->rowptr[i + 1]; ++k)
                 for (int kp = g2->rowptr[ip]; kp < g2->rowptr[ip + 1]; ++kp) {
                     size_t colx = (size_t)g1->col[k] * n2 + g2->col[kp];
-                    S[row * N + colx] = -g1->w[k] * g2->w[kp] * ke(g1->e[k], g2->e[kp], alpha);
+                    S[row * N + colx] = -g1->w[k] * g2->w[kp] * ke(g1->e + (size_t)k * g_kern.dim, g2->e + (size_t)kp * g_kern.dim, alpha);
                 }
             x[row] = g1->deg[i] * g2->deg[ip] * q * q;   /* b = D_x q_x */
         }
@@ -146,7 +197,7 @@ static void apply_S(const ograph* g1, const ograph* g2, double h, double alpha,
             for (int k = g1->rowptr[i]; k < g1->rowptr[i + 1]; ++k) {
                 const double* urow = u + (size_t)g1->col[k] * n2;
                 for (int kp = g2->rowptr[ip]; kp < g2->rowptr[ip + 1]; ++kp)
-                    s -= g1->w[k] * g2->w[kp] * ke(g1->e[k], g2->e[kp], alpha) * urow[g2->col[kp]];
+                    s -= g1->w[k] * g2->w[kp] * ke(g1->e + (size_t)k * g_kern.dim, g2->e + (size_t)kp * g_kern.dim, alpha) * urow[g2->col[kp]];
             }
             out[row] = s;
         }
@@ -197,7 +248,8 @@ static int pair_matrix_free(const ograph* g1, const ograph* g2, double q, double
 /* ---- exported ------------------------------------------------------------ */
 /* Kernel values for n_pairs pairs (pi[k], pj[k]) of a batch given in the flat
  * form: vtx_off[G+1], vtx_label, start_prob (NULL -> 1/n), edge_off[G+1],
- * src/dst (local ids, each undirected edge once), weight, edge_label.
+ * src/dst (local ids, each undirected edge once), weight, edge_label (dim floats
+ * per edge for the kernel in force; length_scale is used by kind 0 only).
  * tier 0 = dense Cholesky, 1 = matrix-free CG.  Returns 0, or the first
  * negative error (-1 memory, -2 bad edge, -3 not SPD, -4 CG not converged). */
 int mgk_oracle_pairs(int32_t n_graphs, const int64_t* vtx_off, const int32_t* vtx_label,
@@ -215,7 +267,7 @@ int mgk_oracle_pairs(int32_t n_graphs, const int64_t* vtx_off, const int32_t* vt
         int64_t v0 = vtx_off[g], e0 = edge_off[g];
         int rc = build_graph(&gs[g], (int)(vtx_off[g + 1] - v0), vtx_label + v0,
                              start_prob ? start_prob + v0 : NULL, (int)(edge_off[g + 1] - e0),
-                             src + e0, dst + e0, weight + e0, edge_label + e0, q);
+                             src + e0, dst + e0, weight + e0, edge_label + e0 * g_kern.dim, q);
         if (rc && !err) err = rc;
     }
     if (!err) {

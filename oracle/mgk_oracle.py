@@ -48,19 +48,73 @@ def vertex_kernel(a, b, h: float):
     return np.where(np.asarray(a) == np.asarray(b), 1.0, float(h))
 
 
-def edge_kernel(e1, e2, length_scale: float):
-    """kappa_e: square exponential exp(-alpha (e1 - e2)^2), alpha = 1/(2 l^2) (Appendix B)."""
-    alpha = 1.0 / (2.0 * float(length_scale) ** 2)
-    d = np.asarray(e1, dtype=np.float64) - np.asarray(e2, dtype=np.float64)
-    return np.exp(-alpha * d * d)
+class EdgeKernel:
+    """An edge base kernel other than the plain square exponential (the list of
+    examples in Appendix B).  Passed wherever the functions below take
+    ``length_scale``; a bare number there means the square-exponential kernel.
+
+    kind "poly":     compact polynomial radial basis kernel on scalar labels,
+                     sum_i coef[i] r^i for r = |e1 - e2| / rho < 1, and 0 from
+                     r = 1 on (compact support).
+    kind "kron_se":  Kronecker-product kernel over labels with D attributes,
+                     prod_a exp(-(e1_a - e2_a)^2 / (2 l_a^2)), one length
+                     scale per attribute.
+    kind "rconv_se": R-convolution kernel over labels made of D parts,
+                     (1 / D^2) sum_a sum_b exp(-(e1_a - e2_b)^2 / (2 l^2));
+                     the factor 1 / D^2 keeps the range inside [0, 1].
+    """
+
+    def __init__(self, kind: str, coef=(), rho: float = 1.0, length_scales=(), dim: int = 0):
+        if kind not in ("poly", "kron_se", "rconv_se"):
+            raise ValueError("unknown edge kernel " + kind)
+        self.kind = kind
+        self.coef = tuple(float(c) for c in coef)
+        self.rho = float(rho)
+        self.length_scales = tuple(float(l) for l in length_scales)
+        self.dim = int(dim) if dim else (len(self.length_scales) if kind == "kron_se" else 1)
+
+
+def edge_kernel(e1, e2, length_scale):
+    """kappa_e.  Square exponential exp(-alpha (e1 - e2)^2), alpha = 1/(2 l^2), when
+    ``length_scale`` is a number; otherwise the kernel an EdgeKernel describes
+    (Appendix B).  Labels with attributes carry them on the last axis."""
+    a = np.asarray(e1, dtype=np.float64)
+    b = np.asarray(e2, dtype=np.float64)
+    if not isinstance(length_scale, EdgeKernel):
+        alpha = 1.0 / (2.0 * float(length_scale) ** 2)
+        d = a - b
+        return np.exp(-alpha * d * d)
+    spec = length_scale
+    if spec.kind == "poly":
+        r = np.abs(a - b) / spec.rho
+        val = np.zeros_like(r)
+        for i, c in enumerate(spec.coef):
+            val = val + c * r ** i
+        return np.where(r < 1.0, val, 0.0)
+    if spec.kind == "kron_se":
+        out = 1.0
+        for k, l in enumerate(spec.length_scales):
+            d = a[..., k] - b[..., k]
+            out = out * np.exp(-d * d / (2.0 * l * l))
+        return out
+    # rconv_se
+    (l,) = spec.length_scales
+    D = a.shape[-1]
+    out = 0.0
+    for i in range(D):
+        for j in range(D):
+            d = a[..., i] - b[..., j]
+            out = out + np.exp(-d * d / (2.0 * l * l))
+    return out / float(D * D)
 
 
 # ---------------------------------------------------------------- per-graph matrices
 def dense_graph(g: Graph):
     """Symmetric adjacency matrix A and edge-label matrix E (Definitions 4, 5)."""
     n, _lab, src, dst, w, e = g
+    e = np.asarray(e, dtype=np.float64)
     A = np.zeros((n, n), dtype=np.float64)
-    E = np.zeros((n, n), dtype=np.float64)
+    E = np.zeros((n, n) + e.shape[1:], dtype=np.float64)   # attributes, if any, on the last axis
     for s, d, ww, ee in zip(src, dst, w, e):
         s = int(s); d = int(d)
         if s == d:
@@ -68,7 +122,7 @@ def dense_graph(g: Graph):
         if A[s, d] != 0.0:
             raise ValueError("duplicate edge")
         A[s, d] = A[d, s] = float(ww)
-        E[s, d] = E[d, s] = float(ee)
+        E[s, d] = E[d, s] = ee
     return A, E
 
 
@@ -244,7 +298,7 @@ def _directed_edges(g: Graph):
     s = np.concatenate([src, dst]).astype(np.int64)
     d = np.concatenate([dst, src]).astype(np.int64)
     ww = np.concatenate([w, w]).astype(np.float64)
-    ee = np.concatenate([e, e]).astype(np.float64)
+    ee = np.concatenate([e, e], axis=0).astype(np.float64)
     return s, d, ww, ee
 
 
@@ -297,10 +351,21 @@ def kernel_value_matrix_free(g1: Graph, g2: Graph, q: float, h: float, length_sc
 # ---------------------------------------------------------------- batches
 def gram_values(batch, pairs_i: Sequence[int], pairs_j: Sequence[int]) -> np.ndarray:
     """Kernel values for the listed pairs of a GraphBatch-like object exposing
-    ``graph(g)`` and ``params`` (q, h, length_scale)."""
+    ``graph(g)`` and ``params`` (q, h, and the edge kernel: length_scale, or
+    edge_kernel / poly_coef / poly_rho / length_scales)."""
     prm = batch.params
+    spec = edge_kernel_of(prm)
     out = np.zeros(len(pairs_i))
     for k, (i, j) in enumerate(zip(pairs_i, pairs_j)):
-        out[k] = kernel_value(batch.graph(int(i)), batch.graph(int(j)),
-                              prm.q, prm.h, prm.length_scale)
+        out[k] = kernel_value(batch.graph(int(i)), batch.graph(int(j)), prm.q, prm.h, spec)
     return out
+
+
+def edge_kernel_of(prm):
+    """The ``length_scale`` argument of the functions above for a parameter record."""
+    kind = getattr(prm, "edge_kernel", "se")
+    if kind == "se":
+        return prm.length_scale
+    if kind == "poly":
+        return EdgeKernel("poly", coef=prm.poly_coef, rho=prm.poly_rho)
+    return EdgeKernel(kind, length_scales=prm.length_scales, dim=getattr(prm, "label_dim", 0))

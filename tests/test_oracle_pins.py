@@ -304,3 +304,89 @@ def test_c_oracle_nodal_solution_matches_numpy():
     # x of (G', G) is the transpose
     _, xt = O.kernel_value(g2, g1, Q, 0.5, 0.8, return_nodal=True)
     np.testing.assert_allclose(xt.T, x0, rtol=1e-10)
+
+
+# ---- P12: the other edge base kernels of Appendix B --------------------------
+# Each closed form below takes the value of kappa_e from the kernel's textbook
+# expression (never from the oracle's own evaluation of it).
+WENDLAND_C2 = (1.0, 0.0, -10.0, 20.0, -15.0, 4.0)   # (1 - r)^4 (4 r + 1), expanded
+
+
+def _wendland(r):
+    return (1.0 - r) ** 4 * (4.0 * r + 1.0) if r < 1.0 else 0.0
+
+
+def test_compact_polynomial_values_and_support():
+    spec = O.EdgeKernel("poly", coef=WENDLAND_C2, rho=0.8)
+    for d in (0.0, 0.1, 0.37, 0.79, 0.8, 0.81, 5.0):
+        assert float(O.edge_kernel(1.0 + d, 1.0, spec)) == pytest.approx(_wendland(d / 0.8), abs=1e-14)
+        assert float(O.edge_kernel(1.0, 1.0 + d, spec)) == pytest.approx(_wendland(d / 0.8), abs=1e-14)
+
+
+@pytest.mark.parametrize("n1,k1,n2,k2", [(5, 2, 4, 3), (3, 2, 6, 2)])
+def test_regular_graphs_with_each_edge_kernel(n1, k1, n2, k2):
+    """Regular graphs, one label value per graph: kappa_e is one number g and
+    K = d d' q^2 / (d d' / h - k k' g), whatever kernel produced g."""
+    h, e0, e1 = 0.4, 1.0, 1.5
+    d1, d2 = k1 + Q, k2 + Q
+    closed = lambda g: d1 * d2 * Q * Q / (d1 * d2 / h - k1 * k2 * g)
+    mk = lambda n, k, lab, e: _cycle(n, lab, e) if k == 2 else _complete(n, lab, e)
+    # compact polynomial, inside and outside its support
+    spec = O.EdgeKernel("poly", coef=WENDLAND_C2, rho=0.8)
+    assert both(mk(n1, k1, 0, e0), mk(n2, k2, 1, e1), Q, h, spec) == pytest.approx(closed(_wendland(0.5 / 0.8)), rel=1e-12)
+    spec = O.EdgeKernel("poly", coef=WENDLAND_C2, rho=0.4)
+    assert both(mk(n1, k1, 0, e0), mk(n2, k2, 1, e1), Q, h, spec) == pytest.approx(closed(0.0), rel=1e-12)
+    # Kronecker product of square exponentials over two attributes
+    def attr(g, vals):
+        n, lab, s, d, w, e = g
+        return (n, lab, s, d, w, np.tile(f32(vals), (len(s), 1)))
+    a, b = (1.0, 0.25), (1.5, -0.5)
+    spec = O.EdgeKernel("kron_se", length_scales=(0.7, 1.3))
+    gk = math.exp(-(a[0] - b[0]) ** 2 / (2 * 0.7 ** 2)) * math.exp(-(a[1] - b[1]) ** 2 / (2 * 1.3 ** 2))
+    assert both(attr(mk(n1, k1, 0, 0.0), a), attr(mk(n2, k2, 1, 0.0), b), Q, h, spec) == pytest.approx(closed(gk), rel=1e-12)
+    # R-convolution over two parts
+    spec = O.EdgeKernel("rconv_se", length_scales=(0.9,), dim=2)
+    gr = sum(math.exp(-(x - y) ** 2 / (2 * 0.9 ** 2)) for x in a for y in b) / 4.0
+    assert both(attr(mk(n1, k1, 0, 0.0), a), attr(mk(n2, k2, 1, 0.0), b), Q, h, spec) == pytest.approx(closed(gr), rel=1e-12)
+
+
+def test_edge_kernels_reduce_to_each_other():
+    """Special cases: a one-attribute Kronecker product and a one-part R-convolution are
+    the square exponential; two equal parts give the same R-convolution value as one;
+    a polynomial of degree 0 is the constant kernel (the unlabeled limit with c = 1)."""
+    rng = np.random.default_rng(12)
+    g1, g2 = random_graph(rng, 5), random_graph(rng, 6)
+    col = lambda g, reps: g[:5] + (np.repeat(np.asarray(g[5])[:, None], reps, axis=1),)
+    ref = both(g1, g2, Q, 0.5, 0.8)
+    assert both(col(g1, 1), col(g2, 1), Q, 0.5, O.EdgeKernel("kron_se", length_scales=(0.8,))) == pytest.approx(ref, rel=1e-12)
+    assert both(col(g1, 1), col(g2, 1), Q, 0.5, O.EdgeKernel("rconv_se", length_scales=(0.8,), dim=1)) == pytest.approx(ref, rel=1e-12)
+    assert both(col(g1, 2), col(g2, 2), Q, 0.5, O.EdgeKernel("rconv_se", length_scales=(0.8,), dim=2)) == pytest.approx(ref, rel=1e-12)
+    # a second attribute that is the same on every edge does not change a Kronecker product
+    two = lambda g: g[:5] + (np.stack([np.asarray(g[5]), np.full(len(g[5]), 0.3)], axis=1),)
+    assert both(two(g1), two(g2), Q, 0.5, O.EdgeKernel("kron_se", length_scales=(0.8, 0.2))) == pytest.approx(ref, rel=1e-12)
+    flat = both(g1, g2, Q, 0.5, 1e9)                      # kappa_e == 1
+    assert both(g1, g2, Q, 0.5, O.EdgeKernel("poly", coef=(1.0,), rho=1e9)) == pytest.approx(flat, rel=1e-9)
+
+
+@pytest.mark.parametrize("kind", ["poly", "kron_se", "rconv_se"])
+def test_walk_sum_and_series_with_each_edge_kernel(kind):
+    """Appendix A: the explicit sum over walk pairs and the matrix series give the
+    value of Eq. 1 for any edge kernel; symmetric in its arguments."""
+    rng = np.random.default_rng(5)
+    g1, g2 = random_graph(rng, 4, 0.6), random_graph(rng, 3, 0.7)
+    if kind == "poly":
+        spec = O.EdgeKernel("poly", coef=WENDLAND_C2, rho=1.5)
+    else:
+        D = 2
+        ext = lambda g: g[:5] + (f32(rng.uniform(0.0, 2.0, (len(g[2]), D))),)
+        g1, g2 = ext(g1), ext(g2)
+        spec = (O.EdgeKernel("kron_se", length_scales=(0.6, 1.1)) if kind == "kron_se"
+                else O.EdgeKernel("rconv_se", length_scales=(0.7,), dim=D))
+    q = 0.4
+    K = both(g1, g2, q, 0.5, spec)
+    assert O.kernel_series(g1, g2, q, 0.5, spec) == pytest.approx(K, rel=1e-12)
+    walks = O.kernel_walks(g1, g2, q, 0.5, spec, 4)
+    terms = O.series_terms(g1, g2, q, 0.5, spec, 4)
+    np.testing.assert_allclose(walks, terms, rtol=1e-12)
+    assert both(g2, g1, q, 0.5, spec) == pytest.approx(K, rel=1e-12)
+    assert O.kernel_value_matrix_free(g1, g2, q, 0.5, spec) == pytest.approx(K, rel=1e-10)
