@@ -36,7 +36,7 @@ def hbm_traffic(workload, args):
     copy of known size).  Only for the exact workload it was measured on."""
     path = os.path.join(ROOT, "profiles", "mgk_pcg_regs_config4_hbm.json")
     if (workload != "config4" or args.graphs != 2000 or not args.product_cache or args.waves
-            or not os.path.exists(path)):
+            or args.edge_kernel != "se" or not os.path.exists(path)):
         return None
     with open(path) as fh:
         return json.load(fh)["bytes_per_step"]
@@ -137,6 +137,10 @@ def main() -> int:
     ap.add_argument("--tile-path", type=int, default=0, help="global-memory solver: 0 auto, 1 sparse, 2 dense")
     ap.add_argument("--product-cache", type=int, default=1,
                     help="on-chip solver: 1 keep the matrix entries of small pairs in registers, 0 regenerate them")
+    ap.add_argument("--edge-kernel", default="se",
+                    help="se (default, the benchmark line), poly (Wendland (1-r)^4(4r+1), radius 0.25), "
+                         "kron_se (3 attributes), rconv_se (3 parts): the other edge base kernels, on the "
+                         "Gram workloads")
     ap.add_argument("--ablation", action="store_true",
                     help="instead of the benchmark line: time the optimisation levels of the paper's "
                          "incremental study and a workgroup-size sweep, one JSON line each")
@@ -184,6 +188,25 @@ def main() -> int:
     else:
         print("unknown workload " + wl, file=sys.stderr)
         return 2
+    flops_per_element_pair = FLOPS_PER_ELEMENT_PAIR
+    if args.edge_kernel != "se":
+        import dataclasses
+        ek = args.edge_kernel
+        if ek == "poly":
+            wb.params = dataclasses.replace(wb.params, edge_kernel="poly", poly_rho=0.25,
+                                            poly_coef=(1.0, 0.0, -10.0, 20.0, -15.0, 4.0))
+            flops_per_element_pair = 3 + 1 + 2 * 5       # difference, Horner of degree 5
+        elif ek in ("kron_se", "rconv_se"):
+            dim = 3
+            prm = dataclasses.replace(wb.params, edge_kernel=ek, label_dim=dim,
+                                      length_scales=(0.15, 0.4, 0.25) if ek == "kron_se" else (0.3,))
+            wb = W.with_label_attributes(wb, np.random.default_rng(7), dim, 0.3, prm)
+            # per attribute (pair of parts): difference, square, accumulate; one (dim^2) exponentials
+            flops_per_element_pair = 3 + (3 * dim + 2 if ek == "kron_se" else 5 * dim * dim)
+        else:
+            print("unknown edge kernel " + ek, file=sys.stderr)
+            return 2
+        wl_name += ", edge kernel " + ek
     G = wb.n_graphs
     solver = M.Solver(0)
     solver.configure(wb.params)
@@ -257,7 +280,7 @@ def main() -> int:
     pair_iterations = float(it.sum())
     not_converged = int((fl_all[pi, pj] if pair_list is None else fl_all).sum())
     kernel_s = float(np.mean(kernel_ms)) * 1e-3
-    alg_flops = FLOPS_PER_ELEMENT_PAIR * element_pairs
+    alg_flops = flops_per_element_pair * element_pairs
     achieved_tflops = alg_flops / kernel_s / 1e12
 
     out = {
@@ -296,7 +319,7 @@ def main() -> int:
             "unit": "TFLOP/s",
             "frac": achieved_tflops / FP32_VECTOR_PEAK_TFLOPS,
             "traffic": hbm_traffic(wl, args),
-            "flops_per_element_pair": FLOPS_PER_ELEMENT_PAIR,
+            "flops_per_element_pair": flops_per_element_pair,
             "element_pairs_per_step": element_pairs,
             "kernel_ms_per_step": kernel_s * 1e3,
         },

@@ -79,6 +79,27 @@ const char* mgk_last_error(const mgk_ctx* ctx);
 mgk_status mgk_set_vertex_kernel_delta(mgk_ctx* ctx, float h);
 mgk_status mgk_set_edge_kernel_se(mgk_ctx* ctx, float length_scale);
 mgk_status mgk_set_edge_kernel_const(mgk_ctx* ctx, float c);
+/* More edge base kernels (the examples of Appendix B).  Values must stay in
+ * [0, 1] and the kernel positive definite for Eq. 1 to be SPD (Section II-B).
+ *
+ * poly: compact polynomial radial basis kernel on scalar labels,
+ *   kappa_e(e, e') = sum_{i < n_coef} coef[i] r^i  for r = |e - e'| / rho < 1,
+ *   and 0 for r >= 1 (compact support of radius rho > 0).  n_coef in 1..9
+ *   (coef is copied).  Rejected with MGK_EINVAL if the polynomial leaves
+ *   [0, 1] anywhere on 0 <= r <= 1 (checked on a grid of 4097 points).
+ *   Example: Wendland's (1-r)^4 (4r+1) = {1, 0, -10, 20, -15, 4}.
+ * kron_se: Kronecker-product kernel over labels with `dim` real attributes,
+ *   kappa_e = prod_a exp(-(e_a - e'_a)^2 / (2 length_scale[a]^2)), dim in 1..4.
+ * rconv_se: R-convolution kernel over labels made of `dim` parts,
+ *   kappa_e = (1 / dim^2) sum_a sum_b exp(-(e_a - e'_b)^2 / (2 length_scale^2));
+ *   the factor 1 / dim^2 keeps the range inside [0, 1].  dim in 1..4.
+ * The last two need batches loaded with the same number of attributes per
+ * edge (mgk_load_graphs_attr); a solve with another batch fails with
+ * MGK_ESTATE.  Pairs too large for the register-resident on-chip solver are
+ * solved with vectors in global memory (poly: all solvers). */
+mgk_status mgk_set_edge_kernel_poly(mgk_ctx* ctx, int32_t n_coef, const float* coef, float rho);
+mgk_status mgk_set_edge_kernel_kron_se(mgk_ctx* ctx, int32_t dim, const float* length_scale);
+mgk_status mgk_set_edge_kernel_rconv_se(mgk_ctx* ctx, int32_t dim, float length_scale);
 mgk_status mgk_set_stop_prob(mgk_ctx* ctx, float q);
 mgk_status mgk_set_solver(mgk_ctx* ctx, float rtol, int32_t max_iter);
 /* Tile-pair primitive of the global-memory solver: sparse (only the nnz * nnz'
@@ -133,6 +154,16 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs,
                            const int64_t* edge_off, const int32_t* src, const int32_t* dst,
                            const float* weight, const float* edge_label,
                            int32_t reorder, mgk_batch** out);
+/* The same with label_dim (1..4) attributes per edge label:
+ * edge_label[(sum m) * label_dim], the attributes of an edge adjacent.
+ * mgk_load_graphs is label_dim = 1.  The octiles (mgk_batch_get_tiles) hold
+ * attribute 0. */
+mgk_status mgk_load_graphs_attr(mgk_ctx* ctx, int32_t n_graphs,
+                                const int64_t* vtx_off, const int32_t* vtx_label,
+                                const float* start_prob,
+                                const int64_t* edge_off, const int32_t* src, const int32_t* dst,
+                                const float* weight, int32_t label_dim, const float* edge_label,
+                                int32_t reorder, mgk_batch** out);
 void mgk_free_batch(mgk_ctx* ctx, mgk_batch* batch);
 
 /* Totals over the batch (any pointer may be NULL): graphs, vertices, stored

@@ -20,6 +20,7 @@ from .generators import (  # noqa: F401
     barabasi_albert_batch,
     concat_batches,
     permute_vertices,
+    with_label_attributes,
     gram_pairs,
     paper_synthetic,
 )

@@ -32,6 +32,15 @@ class KernelParams:
     q: float = 0.05            # stopping probability, same on every vertex
     h: float = 0.5             # vertex delta kernel: 1 if labels equal else h
     length_scale: float = 1.0  # square-exponential edge kernel length scale
+    # edge base kernel: "se" (square exponential, length_scale), "poly" (compact polynomial:
+    # poly_coef, support radius poly_rho), "kron_se" (product of square exponentials over
+    # label_dim attributes, one of length_scales each), "rconv_se" (R-convolution over
+    # label_dim parts, length_scales[0])
+    edge_kernel: str = "se"
+    poly_coef: Tuple[float, ...] = ()
+    poly_rho: float = 1.0
+    length_scales: Tuple[float, ...] = ()
+    label_dim: int = 1
 
 
 @dataclass
@@ -121,6 +130,18 @@ def permute_vertices(batch: GraphBatch, rng: np.random.Generator) -> GraphBatch:
         order = rng.permutation(len(lo))
         graphs.append((n, new_lab, lo[order], hi[order], w[order], e[order]))
     return _assemble(graphs, batch.params, batch.name + "+perm")
+
+
+def with_label_attributes(batch: GraphBatch, rng: np.random.Generator, dim: int, spread: float = 0.3,
+                          params: Optional[KernelParams] = None) -> GraphBatch:
+    """The same graphs with ``dim`` attributes per edge label: attribute 0 is the
+    existing label, the others are drawn around it (normal, standard deviation
+    ``spread``), as for a bond described by several correlated measurements."""
+    base = np.asarray(batch.edge_label, dtype=np.float32).reshape(-1, 1)
+    extra = base + rng.normal(0.0, spread, (len(base), dim - 1)).astype(np.float32)
+    lab = np.concatenate([base, extra], axis=1).astype(np.float32)
+    return GraphBatch(batch.vtx_off, batch.vtx_label, batch.edge_off, batch.src, batch.dst,
+                      batch.weight, lab, params or batch.params, batch.name + "+attr%d" % dim)
 
 
 def gram_pairs(n_graphs: int) -> Tuple[np.ndarray, np.ndarray]:

@@ -23,6 +23,8 @@ TILE_AUTO, TILE_SPARSE, TILE_DENSE = 0, 1, 2
 EXPORTS = [
     "mgk_create", "mgk_destroy", "mgk_last_error",
     "mgk_set_vertex_kernel_delta", "mgk_set_edge_kernel_se", "mgk_set_edge_kernel_const",
+    "mgk_set_edge_kernel_poly", "mgk_set_edge_kernel_kron_se", "mgk_set_edge_kernel_rconv_se",
+    "mgk_load_graphs_attr",
     "mgk_set_stop_prob", "mgk_set_solver", "mgk_set_tile_path", "mgk_set_launch",
     "mgk_set_onchip_limit", "mgk_set_product_cache", "mgk_set_schedule",
     "mgk_load_graphs", "mgk_free_batch", "mgk_batch_stats", "mgk_batch_permutation",
@@ -58,6 +60,10 @@ def load_library(path: Optional[str] = None):
     lib.mgk_set_vertex_kernel_delta.argtypes = [vp, f32]
     lib.mgk_set_edge_kernel_se.argtypes = [vp, f32]
     lib.mgk_set_edge_kernel_const.argtypes = [vp, f32]
+    lib.mgk_set_edge_kernel_poly.argtypes = [vp, i32, vp, f32]
+    lib.mgk_set_edge_kernel_kron_se.argtypes = [vp, i32, vp]
+    lib.mgk_set_edge_kernel_rconv_se.argtypes = [vp, i32, f32]
+    lib.mgk_load_graphs_attr.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, i32, vp, i32, c.POINTER(vp)]
     lib.mgk_set_stop_prob.argtypes = [vp, f32]
     lib.mgk_set_solver.argtypes = [vp, f32, i32]
     lib.mgk_set_tile_path.argtypes = [vp, i32]
@@ -185,6 +191,17 @@ class Solver:
     def set_edge_kernel_const(self, c: float):
         self._check(load_library().mgk_set_edge_kernel_const(self._h, c))
 
+    def set_edge_kernel_poly(self, coef, rho: float):
+        cf, pcf = _host(coef, np.float32)
+        self._check(load_library().mgk_set_edge_kernel_poly(self._h, len(cf), pcf, rho))
+
+    def set_edge_kernel_kron_se(self, length_scales):
+        ls, pls = _host(length_scales, np.float32)
+        self._check(load_library().mgk_set_edge_kernel_kron_se(self._h, len(ls), pls))
+
+    def set_edge_kernel_rconv_se(self, dim: int, length_scale: float):
+        self._check(load_library().mgk_set_edge_kernel_rconv_se(self._h, dim, length_scale))
+
     def set_stop_prob(self, q: float):
         self._check(load_library().mgk_set_stop_prob(self._h, q))
 
@@ -216,10 +233,13 @@ class Solver:
         s, ps = _host(src, np.int32)
         d, pd = _host(dst, np.int32)
         w, pw = _host(weight, np.float32)
-        e, pe = _host(edge_label, np.float32)
+        dim = 1
+        if edge_label is not None and np.ndim(edge_label) == 2:   # [edges, attributes]
+            dim = int(np.shape(edge_label)[1])
+        e, pe = _host(None if edge_label is None else np.reshape(edge_label, -1), np.float32)
         h = ctypes.c_void_p()
-        self._check(lib.mgk_load_graphs(self._h, len(vo) - 1, pvo, pvl, psp, peo, ps, pd, pw, pe,
-                                        reorder, ctypes.byref(h)))
+        self._check(lib.mgk_load_graphs_attr(self._h, len(vo) - 1, pvo, pvl, psp, peo, ps, pd, pw, dim, pe,
+                                             reorder, ctypes.byref(h)))
         return Batch(self, h, vo.copy())
 
     def load_batch(self, batch, reorder: int = REORDER_PBR, start_prob=None) -> Batch:
@@ -266,10 +286,20 @@ class Solver:
                                                       _stream_ptr(stream)))
 
     def configure(self, params):
-        """Apply q, h and the square-exponential length scale of a workload."""
+        """Apply q, h and the edge kernel of a workload's parameter record."""
         self.set_stop_prob(params.q)
         self.set_vertex_kernel_delta(params.h)
-        self.set_edge_kernel_se(params.length_scale)
+        kind = getattr(params, "edge_kernel", "se")
+        if kind == "se":
+            self.set_edge_kernel_se(params.length_scale)
+        elif kind == "poly":
+            self.set_edge_kernel_poly(params.poly_coef, params.poly_rho)
+        elif kind == "kron_se":
+            self.set_edge_kernel_kron_se(params.length_scales)
+        elif kind == "rconv_se":
+            self.set_edge_kernel_rconv_se(params.label_dim, params.length_scales[0])
+        else:
+            raise ValueError("unknown edge kernel " + str(kind))
 
     def __del__(self):
         try:

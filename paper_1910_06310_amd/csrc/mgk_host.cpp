@@ -52,6 +52,7 @@ struct mgk_batch {
     int32_t n_graphs = 0;
     int64_t n_vertices = 0, nnz = 0, n_tiles = 0, n_offdiag = 0;
     bool weighted = false;
+    int label_dim = 1;
     double label_mean = 0.0;
     // host copies
     std::vector<MgkGraphDesc> graphs;
@@ -69,6 +70,7 @@ struct mgk_batch {
     int gram_jobs_tile_path = 0;   // tile path setting the list was built for
     int gram_jobs_cache = 0;       // product-cache setting the list was built for
     int gram_jobs_sorted = 0;      // schedule setting the list was built for
+    int gram_jobs_streaming = 1;   // whether the edge kernel it was built for runs in every solver
 };
 
 struct mgk_ctx {
@@ -76,6 +78,10 @@ struct mgk_ctx {
     std::string err;
     float q = 0.05f, h = 1.0f, length_scale = 1.0f, ke_const = 1.0f, rtol = 1e-6f;
     int edge_kernel = MGK_EK_CONST;
+    int label_dim = 1;                          // attributes the edge kernel reads
+    float attr_ls[MGK_MAX_LABEL_DIM] = {1.f, 1.f, 1.f, 1.f};  // length scales of kron_se / rconv_se
+    float poly_c[MGK_POLY_MAX_COEF] = {};
+    float poly_rho = 1.f;
     int max_iter = 0;
     int tile_path = MGK_TILE_AUTO;
     int waves = 0;
@@ -122,13 +128,36 @@ size_t append_bytes(std::vector<char>& blob, const std::vector<T>& v) {
     return off;
 }
 
+// kernels over label attributes are built into the register-resident and the
+// global-memory solver, not into the streaming on-chip one
+bool streaming_ok(const mgk_ctx* ctx) {
+    return ctx->edge_kernel != MGK_EK_KRON_SE && ctx->edge_kernel != MGK_EK_RCONV_SE;
+}
+
+// the batches must carry the number of label attributes the edge kernel reads
+mgk_status check_label_dim(mgk_ctx* ctx, const mgk_batch* X, const mgk_batch* Y) {
+    if (streaming_ok(ctx)) return MGK_OK;
+    if (X->label_dim != ctx->label_dim || Y->label_dim != ctx->label_dim)
+        return fail(ctx, MGK_ESTATE, "edge kernel reads %d label attributes, the batches hold %d and %d",
+                    ctx->label_dim, X->label_dim, Y->label_dim);
+    return MGK_OK;
+}
+
 MgkParams make_params(const mgk_ctx* ctx, const mgk_batch* X) {
     MgkParams p{};
     p.q = ctx->q;
     p.h = ctx->h;
+    const double log2e = 1.4426950408889634;
     const double alpha = 1.0 / (2.0 * (double)ctx->length_scale * (double)ctx->length_scale);
-    p.e_scale = (float)std::sqrt(alpha * 1.4426950408889634);  // exp(-a d^2) = exp2(-(d sqrt(a log2 e))^2)
+    p.e_scale = (float)std::sqrt(alpha * log2e);  // exp(-a d^2) = exp2(-(d sqrt(a log2 e))^2)
     p.e_shift = (float)X->label_mean;
+    if (ctx->edge_kernel == MGK_EK_POLY) p.e_scale = 1.0f / ctx->poly_rho;
+    p.label_dim = ctx->edge_kernel == MGK_EK_KRON_SE || ctx->edge_kernel == MGK_EK_RCONV_SE ? ctx->label_dim : 1;
+    for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a) {
+        const double l = ctx->attr_ls[ctx->edge_kernel == MGK_EK_RCONV_SE ? 0 : a];
+        p.attr_scale[a] = (float)std::sqrt(log2e / (2.0 * l * l));
+    }
+    for (int i = 0; i < MGK_POLY_MAX_COEF; ++i) p.poly_c[i] = ctx->poly_c[i];
     p.ke_const = ctx->ke_const;
     p.rtol2 = ctx->rtol * ctx->rtol;
     p.max_iter = ctx->max_iter;
@@ -174,7 +203,7 @@ int64_t regs_cost(const MgkGraphDesc& o, const MgkGraphDesc& i, int waves) {
 }
 
 PairPlan plan_pair(const MgkGraphDesc& a, const MgkGraphDesc& b, bool may_swap, int forced_waves,
-                   int onchip_limit, bool product_cache) {
+                   int onchip_limit, bool product_cache, bool streaming_ok) {
     // wave iterations of one XMV: outer nonzeros x 64-lane chunks of the inner layout
     auto passes = [](const MgkGraphDesc& o, const MgkGraphDesc& i) {
         return (int64_t)o.nnz * (i.lane_len / 64) + 2 * (int64_t)o.n * (i.lane_len / 64);
@@ -205,6 +234,7 @@ PairPlan plan_pair(const MgkGraphDesc& a, const MgkGraphDesc& b, bool may_swap, 
             return pl;
         }
     }
+    if (!streaming_ok) return pl;   // this edge kernel runs on chip in the register-resident solver only
     if (forced_waves > 0) {  // requested workgroup size, doubled until the pair fits
         for (int w = forced_waves; w <= 16 && pl.waves == 0; w *= 2)
             for (int e : kEpts)
@@ -355,6 +385,7 @@ mgk_status ensure(mgk_ctx* ctx, DevBuf& b, size_t bytes) {
 constexpr int kDenseMinNnzPerTile = 24;
 
 bool use_dense_tiles(const mgk_ctx* ctx, const MgkGraphDesc& a, const MgkGraphDesc& b) {
+    if (ctx->edge_kernel == MGK_EK_KRON_SE || ctx->edge_kernel == MGK_EK_RCONV_SE) return false;
     if (ctx->tile_path == MGK_TILE_DENSE) return true;
     if (ctx->tile_path == MGK_TILE_SPARSE) return false;
     return a.n_tiles > 0 && b.n_tiles > 0 &&
@@ -551,6 +582,7 @@ mgk_status mgk_set_edge_kernel_se(mgk_ctx* ctx, float length_scale) {
         return fail(ctx, MGK_EINVAL, "length scale must be positive and finite, got %g", length_scale);
     ctx->length_scale = length_scale;
     ctx->edge_kernel = MGK_EK_SE;
+    ctx->label_dim = 1;
     return MGK_OK;
 }
 
@@ -559,7 +591,50 @@ mgk_status mgk_set_edge_kernel_const(mgk_ctx* ctx, float c) {
     if (!(c >= 0.f && c <= 1.f)) return fail(ctx, MGK_EINVAL, "constant edge kernel must be in [0, 1], got %g", c);
     ctx->ke_const = c;
     ctx->edge_kernel = MGK_EK_CONST;
+    ctx->label_dim = 1;
     return MGK_OK;
+}
+
+mgk_status mgk_set_edge_kernel_poly(mgk_ctx* ctx, int32_t n_coef, const float* coef, float rho) {
+    if (!ctx) return MGK_EINVAL;
+    if (n_coef < 1 || n_coef > MGK_POLY_MAX_COEF || !coef)
+        return fail(ctx, MGK_EINVAL, "polynomial needs 1 to %d coefficients", MGK_POLY_MAX_COEF);
+    if (!(rho > 0.f) || !std::isfinite(rho)) return fail(ctx, MGK_EINVAL, "support radius must be positive and finite, got %g", rho);
+    for (int i = 0; i < n_coef; ++i)
+        if (!std::isfinite(coef[i])) return fail(ctx, MGK_EINVAL, "coefficient %d is not finite", i);
+    for (int k = 0; k <= 4096; ++k) {  // range of a base kernel (Section II-B)
+        const double r = k / 4096.0;
+        double v = 0.0;
+        for (int i = n_coef - 1; i >= 0; --i) v = v * r + coef[i];
+        if (v < -1e-6 || v > 1.0 + 1e-6)
+            return fail(ctx, MGK_EINVAL, "polynomial is %g at r = %g, outside [0, 1]", v, r);
+    }
+    for (int i = 0; i < MGK_POLY_MAX_COEF; ++i) ctx->poly_c[i] = i < n_coef ? coef[i] : 0.f;
+    ctx->poly_rho = rho;
+    ctx->edge_kernel = MGK_EK_POLY;
+    ctx->label_dim = 1;
+    return MGK_OK;
+}
+
+static mgk_status set_attr_kernel(mgk_ctx* ctx, int kind, int32_t dim, const float* ls, int n_ls) {
+    if (!ctx) return MGK_EINVAL;
+    if (dim < 1 || dim > MGK_MAX_LABEL_DIM) return fail(ctx, MGK_EINVAL, "label attributes must be 1 to %d, got %d", MGK_MAX_LABEL_DIM, dim);
+    if (!ls) return fail(ctx, MGK_EINVAL, "null length scales");
+    for (int a = 0; a < n_ls; ++a)
+        if (!(ls[a] > 0.f) || !std::isfinite(ls[a]))
+            return fail(ctx, MGK_EINVAL, "length scale %d must be positive and finite, got %g", a, ls[a]);
+    for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a) ctx->attr_ls[a] = a < n_ls ? ls[a] : 1.f;
+    ctx->edge_kernel = kind;
+    ctx->label_dim = dim;
+    return MGK_OK;
+}
+
+mgk_status mgk_set_edge_kernel_kron_se(mgk_ctx* ctx, int32_t dim, const float* length_scale) {
+    return set_attr_kernel(ctx, MGK_EK_KRON_SE, dim, length_scale, dim);
+}
+
+mgk_status mgk_set_edge_kernel_rconv_se(mgk_ctx* ctx, int32_t dim, float length_scale) {
+    return set_attr_kernel(ctx, MGK_EK_RCONV_SE, dim, &length_scale, 1);
 }
 
 mgk_status mgk_set_stop_prob(mgk_ctx* ctx, float q) {
@@ -620,8 +695,20 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
                            const int64_t* edge_off, const int32_t* src, const int32_t* dst,
                            const float* weight, const float* edge_label, int32_t reorder,
                            mgk_batch** out) {
+    return mgk_load_graphs_attr(ctx, n_graphs, vtx_off, vtx_label, start_prob, edge_off, src, dst, weight,
+                                1, edge_label, reorder, out);
+}
+
+mgk_status mgk_load_graphs_attr(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_off,
+                                const int32_t* vtx_label, const float* start_prob,
+                                const int64_t* edge_off, const int32_t* src, const int32_t* dst,
+                                const float* weight, int32_t label_dim, const float* edge_label,
+                                int32_t reorder, mgk_batch** out) {
     if (!ctx || !out) return MGK_EINVAL;
     *out = nullptr;
+    if (label_dim < 1 || label_dim > MGK_MAX_LABEL_DIM)
+        return fail(ctx, MGK_EINVAL, "label attributes must be 1 to %d, got %d", MGK_MAX_LABEL_DIM, label_dim);
+    const int D = label_dim;
     if (n_graphs < 0 || !vtx_off || !edge_off) return fail(ctx, MGK_EINVAL, "null offsets or negative graph count");
     if (reorder < MGK_REORDER_NONE || reorder > MGK_REORDER_RCM)
         return fail(ctx, MGK_EINVAL, "unknown reorder mode %d", reorder);
@@ -647,13 +734,17 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
     std::vector<int32_t> vlabel((size_t)tot_v), rowptr((size_t)tot_v), lanepos((size_t)tot_v), iperm((size_t)tot_v), trow_ptr, tile_graph;
     std::vector<MgkEntry> list_outer, list_inner;   // nonzero lists for the register-resident solver
     list_outer.reserve((size_t)(2 * tot_e));
+    // label attributes in the order of the two lists, attribute-major; filled after the loop
+    // (the plane stride is the batch total): (position, edge) pairs collected meanwhile
+    std::vector<std::pair<int64_t, int64_t>> attr_pos_outer, attr_pos_inner;
+    B->label_dim = D;
     int64_t lanes_total = 0;
     std::vector<float> rowsum((size_t)tot_v), start((size_t)tot_v);
     B->w.reserve((size_t)(2 * tot_e));
     B->e.reserve((size_t)(2 * tot_e));
     double label_sum = 0.0;
 
-    struct Nz { uint64_t key; float w, e; };
+    struct Nz { uint64_t key; float w, e; int64_t edge; };
     std::vector<Nz> nz;
     MgkAdj adj;
     std::vector<int32_t> cursor;
@@ -677,8 +768,9 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
             const float wv = weight ? weight[k] : 1.f;
             if (!(wv > 0.f) || !std::isfinite(wv))
                 return fail(ctx, MGK_EINVAL, "graph %d edge %lld: weight must be finite and > 0", g, (long long)(k - e0));
-            if (edge_label && !std::isfinite(edge_label[k]))
-                return fail(ctx, MGK_EINVAL, "graph %d edge %lld: label is not finite", g, (long long)(k - e0));
+            for (int a = 0; edge_label && a < D; ++a)
+                if (!std::isfinite(edge_label[k * D + a]))
+                    return fail(ctx, MGK_EINVAL, "graph %d edge %lld: label is not finite", g, (long long)(k - e0));
             adj.ptr[s + 1]++;
             adj.ptr[d + 1]++;
         }
@@ -728,14 +820,14 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
         nz.reserve((size_t)(2 * m));
         for (int64_t k = e0; k < e1; ++k) {
             const float wv = weight ? weight[k] : 1.f;
-            const float ev = edge_label ? edge_label[k] : 0.f;
+            const float ev = edge_label ? edge_label[k * D] : 0.f;
             if (wv != 1.f) B->weighted = true;
             label_sum += 2.0 * ev;
             const int a = perm[src[k]], b = perm[dst[k]];
             for (int dir = 0; dir < 2; ++dir) {
                 const int i = dir ? b : a, j = dir ? a : b;
                 const uint64_t tile_id = (uint64_t)(i / kTile) * ntr + (uint64_t)(j / kTile);
-                nz.push_back({tile_id * 64 + (uint64_t)((i % kTile) * 8 + (j % kTile)), wv, ev});
+                nz.push_back({tile_id * 64 + (uint64_t)((i % kTile) * 8 + (j % kTile)), wv, ev, k});
             }
         }
         std::sort(nz.begin(), nz.end(), [](const Nz& x, const Nz& y) { return x.key < y.key; });
@@ -812,6 +904,10 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
             const uint32_t longrow = deg[i] > MGK_LANE_GROUP ? 1u : 0u;
             list_inner[(size_t)gd.loff + lanepos[v0 + i] + rank] =
                 MgkEntry{i | (run_rank << 20) | (longrow << 30) | (last << 31), j, ebits, wbits};
+            {
+                attr_pos_outer.push_back({(int64_t)gd.zoff + rowptr[v0 + i] + rank, nz[k].edge});
+                attr_pos_inner.push_back({(int64_t)gd.loff + lanepos[v0 + i] + rank, nz[k].edge});
+            }
         }
         tile_graph.resize(B->tiles.size(), g);
     }
@@ -836,6 +932,20 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
     const size_t o_ip = append_bytes(blob, iperm);
     const size_t o_lo = append_bytes(blob, list_outer);
     const size_t o_li = append_bytes(blob, list_inner);
+    std::vector<float> attr_outer, attr_inner;
+    {
+        attr_outer.assign((size_t)D * B->w.size(), 0.f);
+        attr_inner.assign((size_t)D * (size_t)lanes_total, 0.f);
+        for (const auto& pe : attr_pos_outer)
+            for (int a = 0; a < D; ++a)
+                attr_outer[(size_t)a * B->w.size() + (size_t)pe.first] = edge_label ? edge_label[pe.second * D + a] : 0.f;
+        for (const auto& pe : attr_pos_inner)
+            for (int a = 0; a < D; ++a)
+                attr_inner[(size_t)a * (size_t)lanes_total + (size_t)pe.first] = edge_label ? edge_label[pe.second * D + a] : 0.f;
+    }
+    const size_t o_ao = append_bytes(blob, attr_outer);
+    const size_t o_ai = append_bytes(blob, attr_inner);
+    B->dev.label_dim = D;
     B->dev.n_graphs = n_graphs;
     B->dev.n_tiles_total = (int32_t)B->tiles.size();
     B->dev.nnz_total = (int32_t)B->w.size();
@@ -863,6 +973,8 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
     B->dev.iperm = reinterpret_cast<const int32_t*>(base + o_ip);
     B->dev.list_outer = reinterpret_cast<const MgkEntry*>(base + o_lo);
     B->dev.list_inner = reinterpret_cast<const MgkEntry*>(base + o_li);
+    B->dev.attr_outer = reinterpret_cast<const float*>(base + o_ao);
+    B->dev.attr_inner = reinterpret_cast<const float*>(base + o_ai);
 
     guard.b = nullptr;
     *out = B;
@@ -920,13 +1032,15 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
     if (batch->owner != ctx) return fail(ctx, MGK_ESTATE, "batch belongs to another context");
     if (ctx->device < 0) return fail(ctx, MGK_ESTATE, "host-only context cannot solve");
     hipStream_t stream = static_cast<hipStream_t>(stream_);
+    if (mgk_status st = check_label_dim(ctx, batch, batch)) return st;
     MGK_HIP(ctx, hipSetDevice(ctx->device));
     const int64_t G = batch->n_graphs;
     if (G * G >= (int64_t)1 << 31) return fail(ctx, MGK_ELIMIT, "Gram matrix too large for 32-bit output indices");
     if (batch->gram_jobs.dev != nullptr &&
         (batch->gram_jobs_waves != ctx->waves || batch->gram_jobs_max_iter != ctx->max_iter ||
          batch->gram_jobs_limit != ctx->onchip_limit || batch->gram_jobs_tile_path != ctx->tile_path ||
-         batch->gram_jobs_cache != ctx->product_cache || batch->gram_jobs_sorted != ctx->cost_sorted)) {
+         batch->gram_jobs_cache != ctx->product_cache || batch->gram_jobs_sorted != ctx->cost_sorted ||
+         batch->gram_jobs_streaming != (streaming_ok(ctx) ? 1 : 0))) {
         MGK_HIP(ctx, hipStreamSynchronize(stream));  // launch shape changed: rebuild the job list
         MGK_HIP(ctx, hipFree(batch->gram_jobs.dev));
         batch->gram_jobs.dev = nullptr;
@@ -938,7 +1052,7 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
         for (auto& a : batch->gram_jobs.large) for (auto& v : a) v.clear();
         for (int64_t i = 0; i < G; ++i)
             for (int64_t j = i; j < G; ++j) {
-                const PairPlan pl = plan_pair(batch->graphs[i], batch->graphs[j], true, ctx->waves, ctx->onchip_limit, ctx->product_cache != 0);
+                const PairPlan pl = plan_pair(batch->graphs[i], batch->graphs[j], true, ctx->waves, ctx->onchip_limit, ctx->product_cache != 0, streaming_ok(ctx));
                 HostJob hj;
                 hj.job.g1 = (int32_t)(pl.swap ? j : i);
                 hj.job.g2 = (int32_t)(pl.swap ? i : j);
@@ -970,6 +1084,7 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
         batch->gram_jobs_tile_path = ctx->tile_path;
         batch->gram_jobs_cache = ctx->product_cache;
         batch->gram_jobs_sorted = ctx->cost_sorted;
+        batch->gram_jobs_streaming = streaming_ok(ctx) ? 1 : 0;
         if (st != MGK_OK) return st;
     }
     const MgkOutputs out{K_dev, iters_dev, flag_dev, nullptr, nullptr};
@@ -986,6 +1101,7 @@ static mgk_status pairs_impl(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n
     if (n_pairs < 0 || n_pairs >= (int64_t)1 << 31) return fail(ctx, MGK_EINVAL, "bad pair count");
     if (n_pairs == 0) return MGK_OK;
     if (!i_host || !j_host || !K_dev) return fail(ctx, MGK_EINVAL, "null argument");
+    if (mgk_status st = check_label_dim(ctx, X, Y)) return st;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     MGK_HIP(ctx, hipSetDevice(ctx->device));
     // Either graph of a pair may be the outer operand; jobs whose outer graph
@@ -996,7 +1112,7 @@ static mgk_status pairs_impl(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n
         const int32_t i = i_host[k], j = j_host[k];
         if (i < 0 || i >= X->n_graphs || j < 0 || j >= Y->n_graphs)
             return fail(ctx, MGK_EINVAL, "pair %lld: graph index out of range", (long long)k);
-        const PairPlan pl = plan_pair(X->graphs[i], Y->graphs[j], true, ctx->waves, ctx->onchip_limit, ctx->product_cache != 0);
+        const PairPlan pl = plan_pair(X->graphs[i], Y->graphs[j], true, ctx->waves, ctx->onchip_limit, ctx->product_cache != 0, streaming_ok(ctx));
         HostJob& hj = jobs[(size_t)k];
         hj.job.g1 = pl.swap ? j : i;
         hj.job.g2 = pl.swap ? i : j;

@@ -59,7 +59,10 @@ struct MgkBatchDev {
     const int32_t* iperm;    // per vertex: original id of the stored vertex
     const struct MgkEntry* list_outer;  // per nonzero (CSR order, index zoff + k), see MgkEntry
     const struct MgkEntry* list_inner;  // per lane slot (index loff + slot)
+    const float* attr_outer;  // label attribute a of nonzero k (CSR order): attr_outer[a * nnz_total + zoff + k]
+    const float* attr_inner;  // the same in lane order: attr_inner[a * lanes_total + loff + slot], 0 on idle slots
     int32_t n_graphs, n_tiles_total, nnz_total, lanes_total;
+    int32_t label_dim;        // attributes per edge label (1 for plain scalar labels)
 };
 
 // One unit of work: solve the pair (outer graph g1 of batch X, inner graph g2
@@ -84,18 +87,39 @@ struct MgkOutputs {
     const int64_t* nodal_off;
 };
 
-enum { MGK_EK_CONST = 0, MGK_EK_SE = 1 };
+// Edge base kernels (Appendix B).  SE, POLY and CONST take one label per edge;
+// KRON_SE and RCONV_SE take label_dim attributes (parts) per edge.
+enum { MGK_EK_CONST = 0, MGK_EK_SE = 1, MGK_EK_POLY = 2, MGK_EK_KRON_SE = 3, MGK_EK_RCONV_SE = 4 };
+#define MGK_MAX_LABEL_DIM 4
+#define MGK_POLY_MAX_COEF 9
 
 struct MgkParams {
     float q;          // stopping probability
     float h;          // vertex kernel off-diagonal value
-    float e_scale;    // sqrt(alpha * log2(e)): kappa_e = exp2(-((e-e')*e_scale)^2)
+    float e_scale;    // SE: sqrt(alpha * log2(e)), kappa_e = exp2(-((e-e')*e_scale)^2); POLY: 1 / rho
     float e_shift;    // common shift applied to labels before scaling
     float ke_const;   // constant edge kernel value
     float rtol2;      // rtol^2
     int32_t max_iter; // <= 0: automatic
     int32_t edge_kernel;
+    int32_t label_dim;                     // attributes per edge label the kernel reads
+    float attr_scale[MGK_MAX_LABEL_DIM];   // KRON_SE: sqrt(alpha_a log2(e)) per attribute; RCONV_SE: [0] for all parts
+    float poly_c[MGK_POLY_MAX_COEF];       // POLY: sum_i poly_c[i] r^i on r = |e-e'| / rho < 1, zero-padded
 };
+
+#if defined(__HIPCC__)
+// Compact polynomial radial basis kernel on the prescaled difference d = (e - e') / rho:
+// Horner over all MGK_POLY_MAX_COEF coefficients (the unused high ones are 0), and
+// 0 from |d| = 1 on.
+__device__ __forceinline__ float mgk_poly_kernel(float d, const float* c) {
+    const float r = __builtin_fabsf(d);
+    const float rc = __builtin_fminf(r, 1.0f);
+    float v = c[MGK_POLY_MAX_COEF - 1];
+#pragma unroll
+    for (int i = MGK_POLY_MAX_COEF - 2; i >= 0; --i) v = __builtin_fmaf(v, rc, c[i]);
+    return r < 1.0f ? v : 0.0f;
+}
+#endif
 
 // ---- LDS plan of the on-chip solver (one workgroup per pair) ---------------
 // All offsets in 4-byte words from the start of dynamic LDS.  Computed the same

@@ -55,10 +55,11 @@ __device__ __forceinline__ float row_shr(float v) {
 }
 
 // ---- expansion of the octiles of a whole batch --------------------------------
-// idle lane slots of the inner lists: weight 0 (log2 = -inf), never the end of a run
-__global__ void mgk_fill_idle_kernel(uint4* inner, int n) {
+// idle lane slots of the inner lists: weight 0 (`aux` = its log2, -inf, or the weight
+// itself for the kernels that multiply by it), never the end of a run
+__global__ void mgk_fill_idle_kernel(uint4* inner, int n, uint32_t aux) {
     const int k = blockIdx.x * blockDim.x + threadIdx.x;
-    if (k < n) inner[k] = make_uint4(0u, 0u, 0u, 0xff800000u);
+    if (k < n) inner[k] = make_uint4(0u, 0u, 0u, aux);
 }
 
 // one wave per octile, lane <-> bit of the bitmap
@@ -83,8 +84,9 @@ __global__ __launch_bounds__(256) void mgk_expand_kernel(MgkBatchDev B, MgkParam
     const int rp1 = (row + 1 < g.n) ? B.rowptr[g.voff + row + 1] : g.nnz;
     const uint32_t rowbyte = (uint32_t)(tile.bitmap >> (8 * r)) & 0xffu;
     const int rank = prior + __popc(rowbyte & ((1u << c) - 1u));
-    const float lw = __log2f(w);
-    const float lab = EK == MGK_EK_SE ? el : w;
+    // fourth word: log2 weight where the weight is folded into an exponent, else the weight
+    const float lw = (EK == MGK_EK_POLY || EK == MGK_EK_RCONV_SE) ? w : __log2f(w);
+    const float lab = EK == MGK_EK_CONST ? w : el;
     outer[g.zoff + rp0 + rank] = make_uint4((uint32_t)col, __float_as_uint(lab), __float_as_uint(lw), (uint32_t)row);
     const uint32_t run_rank = (uint32_t)rank % MGK_LANE_GROUP;
     const uint32_t last = (rank + 1 == rp1 - rp0 || run_rank == MGK_LANE_GROUP - 1) ? 1u : 0u;
@@ -133,8 +135,11 @@ __global__ __launch_bounds__(256) void mgk_large_init_kernel(MgkBatchDev X, MgkB
 template <bool WEIGHTED, int EK>
 __global__ __launch_bounds__(kThreads) void mgk_large_xmv_kernel(
     MgkBatchDev X, MgkBatchDev Y, MgkExpanded EX, MgkExpanded EY, const MgkLargePair* pairs,
-    const MgkPairState* state, float* vec, float ke_c) {
+    const MgkPairState* state, float* vec, MgkParams prm) {
     if (state[blockIdx.y].done) return;
+    const float ke_c = prm.ke_const;
+    constexpr bool ATTR = EK == MGK_EK_KRON_SE || EK == MGK_EK_RCONV_SE;   // labels with D attributes
+    const int D = prm.label_dim;
     const MgkLargePair P = pairs[blockIdx.y];
     const MgkGraphDesc g1 = X.graphs[P.g1], g2 = Y.graphs[P.g2];
     const int chunks = g2.lane_len / 64;
@@ -165,6 +170,15 @@ __global__ __launch_bounds__(kThreads) void mgk_large_xmv_kernel(
         const float lw2 = __uint_as_float(e2.w);
         const float m1 = rank >= 1 ? 1.f : 0.f, m2 = rank >= 2 ? 1.f : 0.f;
         const float m4 = rank >= 4 ? 1.f : 0.f, m8 = rank >= 8 ? 1.f : 0.f;
+        float e2a[MGK_MAX_LABEL_DIM] = {0.f, 0.f, 0.f, 0.f};   // this lane's attributes, prescaled
+        if (ATTR) {
+#pragma unroll
+            for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a)
+                if (a < D)
+                    e2a[a] = Y.attr_inner[(int64_t)a * Y.lanes_total + g2.loff + c * 64 + lane] * prm.attr_scale[a];
+        }
+        const float* ao = X.attr_outer + g1.zoff;   // outer attributes, raw: plane a at a * nnz_total
+        const float w2s = lw2 / (float)(D * D);     // R-convolution: A'_i'j' / D^2 (0 on idle lanes)
         for (int i = row0; i < row1; ++i) {
             const int kb = rowptr1[i];
             const int ke = (i + 1 < P.n1) ? rowptr1[i + 1] : g1.nnz;
@@ -179,11 +193,42 @@ __global__ __launch_bounds__(kThreads) void mgk_large_xmv_kernel(
                     if (WEIGHTED) t = __builtin_fmaf(-d, d, lw2 + __uint_as_float(e1.z));
                     else t = __builtin_fmaf(-d, d, lw2);
                     acc = __builtin_fmaf(__builtin_amdgcn_exp2f(t), pv, acc);
+                } else if (EK == MGK_EK_POLY) {
+                    float cu = mgk_poly_kernel(el2 - __uint_as_float(e1.y), prm.poly_c);
+                    if (WEIGHTED) cu *= __uint_as_float(e1.z);
+                    acc = __builtin_fmaf(cu, pv, acc);
+                } else if (EK == MGK_EK_KRON_SE) {
+                    // exp2(log2 A + log2 A' - sum_a (s_a (e_a - e'_a))^2); k is wave-uniform
+                    float t = WEIGHTED ? lw2 + __uint_as_float(e1.z) : lw2;
+#pragma unroll
+                    for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a)
+                        if (a < D) {
+                            const float d = __builtin_fmaf(ao[(int64_t)a * X.nnz_total + k], -prm.attr_scale[a], e2a[a]);
+                            t = __builtin_fmaf(-d, d, t);
+                        }
+                    acc = __builtin_fmaf(__builtin_amdgcn_exp2f(t), pv, acc);
+                } else if (EK == MGK_EK_RCONV_SE) {
+                    float sum = 0.f;
+#pragma unroll
+                    for (int b = 0; b < MGK_MAX_LABEL_DIM; ++b)
+                        if (b < D) {
+                            const float e1b = ao[(int64_t)b * X.nnz_total + k] * prm.attr_scale[0];
+#pragma unroll
+                            for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a)
+                                if (a < D) {
+                                    const float d = e2a[a] - e1b;
+                                    sum += __builtin_amdgcn_exp2f(-d * d);
+                                }
+                        }
+                    if (WEIGHTED) sum *= __uint_as_float(e1.z);
+                    acc = __builtin_fmaf(sum, pv, acc);
                 } else {
                     acc = __builtin_fmaf(WEIGHTED ? __uint_as_float(e1.y) : 1.f, pv, acc);
                 }
             }
             if (EK == MGK_EK_CONST) acc *= ke_c * el2;
+            if (EK == MGK_EK_POLY) acc *= lw2;          // A'_i'j' (0 on idle lanes)
+            if (EK == MGK_EK_RCONV_SE) acc *= w2s;
             if (P.nsteps > 0) acc = __builtin_fmaf(m1, row_shr<1>(acc), acc);
             if (P.nsteps > 1) acc = __builtin_fmaf(m2, row_shr<2>(acc), acc);
             if (P.nsteps > 2) acc = __builtin_fmaf(m4, row_shr<4>(acc), acc);
@@ -230,9 +275,10 @@ __global__ __launch_bounds__(256) void mgk_expand_dense_kernel(MgkBatchDev B, Mg
 template <int EK>
 __global__ __launch_bounds__(256) void mgk_large_xmv_dense_kernel(
     MgkBatchDev X, MgkBatchDev Y, MgkDenseTiles DX, MgkDenseTiles DY, const MgkLargePair* pairs,
-    const MgkPairState* state, float* vec, float ke_c) {
+    const MgkPairState* state, float* vec, MgkParams prm) {
     __shared__ __align__(16) float ptile[4][64];
     if (state[blockIdx.y].done) return;
+    const float ke_c = prm.ke_const;
     const MgkLargePair P = pairs[blockIdx.y];
     const MgkGraphDesc g1 = X.graphs[P.g1], g2 = Y.graphs[P.g2];
     const int ntr1 = g1.n_tile_rows, ntr2 = g2.n_tile_rows;
@@ -296,6 +342,8 @@ __global__ __launch_bounds__(256) void mgk_large_xmv_dense_kernel(
                     if (EK == MGK_EK_SE) {
                         const float d = e2[jp] - er[j];
                         s = __builtin_fmaf(__builtin_amdgcn_exp2f(__builtin_fmaf(-d, d, f2[jp])), pj[jp], s);
+                    } else if (EK == MGK_EK_POLY) {
+                        s = __builtin_fmaf(mgk_poly_kernel(e2[jp] - er[j], prm.poly_c) * f2[jp], pj[jp], s);
                     } else {
                         s = __builtin_fmaf(f2[jp], pj[jp], s);
                     }
@@ -459,13 +507,18 @@ hipError_t mgk_launch_expand(const MgkBatchDev& B, const MgkParams& prm, MgkEntr
     uint4* inner = reinterpret_cast<uint4*>(inner_);
     if (B.lanes_total > 0)
         hipLaunchKernelGGL(mgk_fill_idle_kernel, dim3((B.lanes_total + 255) / 256), dim3(256), 0, stream,
-                           inner, B.lanes_total);
+                           inner, B.lanes_total,
+                           (prm.edge_kernel == MGK_EK_POLY || prm.edge_kernel == MGK_EK_RCONV_SE) ? 0u : 0xff800000u);
     if (B.n_tiles_total > 0) {
         const dim3 grid((B.n_tiles_total + 3) / 4);
-        if (prm.edge_kernel == MGK_EK_SE)
-            hipLaunchKernelGGL(mgk_expand_kernel<MGK_EK_SE>, grid, dim3(256), 0, stream, B, prm, outer, inner);
-        else
-            hipLaunchKernelGGL(mgk_expand_kernel<MGK_EK_CONST>, grid, dim3(256), 0, stream, B, prm, outer, inner);
+        switch (prm.edge_kernel) {
+#define MGK_EXPAND(EKV) \
+    case EKV: hipLaunchKernelGGL(mgk_expand_kernel<EKV>, grid, dim3(256), 0, stream, B, prm, outer, inner); break;
+            MGK_EXPAND(MGK_EK_SE) MGK_EXPAND(MGK_EK_CONST) MGK_EXPAND(MGK_EK_POLY)
+            MGK_EXPAND(MGK_EK_KRON_SE) MGK_EXPAND(MGK_EK_RCONV_SE)
+#undef MGK_EXPAND
+            default: return hipErrorInvalidValue;
+        }
     }
     return hipGetLastError();
 }
@@ -499,14 +552,23 @@ hipError_t mgk_launch_large_iteration(const MgkBatchDev& X, const MgkBatchDev& Y
     const dim3 gx(xmv_blocks, n_pairs), gv(vec_blocks, n_pairs), gs((n_pairs + 63) / 64);
     if (DX != nullptr) {
         if (prm.edge_kernel == MGK_EK_SE)
-            hipLaunchKernelGGL(mgk_large_xmv_dense_kernel<MGK_EK_SE>, gx, dim3(256), 0, stream, X, Y, *DX, *DY, pairs, state, vec, prm.ke_const);
+            hipLaunchKernelGGL(mgk_large_xmv_dense_kernel<MGK_EK_SE>, gx, dim3(256), 0, stream, X, Y, *DX, *DY, pairs, state, vec, prm);
+        else if (prm.edge_kernel == MGK_EK_POLY)
+            hipLaunchKernelGGL(mgk_large_xmv_dense_kernel<MGK_EK_POLY>, gx, dim3(256), 0, stream, X, Y, *DX, *DY, pairs, state, vec, prm);
+        else if (prm.edge_kernel == MGK_EK_CONST)
+            hipLaunchKernelGGL(mgk_large_xmv_dense_kernel<MGK_EK_CONST>, gx, dim3(256), 0, stream, X, Y, *DX, *DY, pairs, state, vec, prm);
         else
-            hipLaunchKernelGGL(mgk_large_xmv_dense_kernel<MGK_EK_CONST>, gx, dim3(256), 0, stream, X, Y, *DX, *DY, pairs, state, vec, prm.ke_const);
+            return hipErrorInvalidValue;   // kernels over label attributes use the sparse product
     } else {
-#define MGK_XMV(WT, EKV) \
-    hipLaunchKernelGGL((mgk_large_xmv_kernel<WT, EKV>), gx, dim3(kThreads), 0, stream, X, Y, EX, EY, pairs, state, vec, prm.ke_const)
-    if (prm.edge_kernel == MGK_EK_SE) { if (weighted) MGK_XMV(true, MGK_EK_SE); else MGK_XMV(false, MGK_EK_SE); }
-    else { if (weighted) MGK_XMV(true, MGK_EK_CONST); else MGK_XMV(false, MGK_EK_CONST); }
+#define MGK_XMV(EKV) \
+    case EKV: \
+        if (weighted) hipLaunchKernelGGL((mgk_large_xmv_kernel<true, EKV>), gx, dim3(kThreads), 0, stream, X, Y, EX, EY, pairs, state, vec, prm); \
+        else hipLaunchKernelGGL((mgk_large_xmv_kernel<false, EKV>), gx, dim3(kThreads), 0, stream, X, Y, EX, EY, pairs, state, vec, prm); \
+        break;
+        switch (prm.edge_kernel) {
+            MGK_XMV(MGK_EK_SE) MGK_XMV(MGK_EK_CONST) MGK_XMV(MGK_EK_POLY) MGK_XMV(MGK_EK_KRON_SE) MGK_XMV(MGK_EK_RCONV_SE)
+            default: return hipErrorInvalidValue;
+        }
 #undef MGK_XMV
     }
     hipLaunchKernelGGL(mgk_large_dot_kernel, gv, dim3(256), 0, stream, pairs, state, vec);

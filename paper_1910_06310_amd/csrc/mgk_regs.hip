@@ -87,6 +87,83 @@ __device__ __forceinline__ void fill_const(float (&kap)[C][SMAX], int S, const f
     }
 }
 
+// compact polynomial kernel on labels prescaled by 1 / rho; wprod = A_ij A'_i'j' per lane
+// pair (0 on idle slots and past the run)
+template <int K0, int SMAX, int C>
+__device__ __forceinline__ void fill_poly(float (&kap)[C][SMAX], int S, const float (&e2s)[C],
+                                          const float (&w2)[C], float e1s, float w1, const float* pc) {
+    if constexpr (K0 < SMAX) {
+        if (K0 < S) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float e1 = lane_value(e1s, K0 + u);
+                const float wa = lane_value(w1, K0 + u);
+#pragma unroll
+                for (int c = 0; c < C; ++c)
+                    kap[c][K0 + u] = mgk_poly_kernel(e2s[c] - e1, pc) * (w2[c] * wa);
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int c = 0; c < C; ++c) kap[c][K0 + u] = 0.f;
+        }
+        fill_poly<K0 + 4, SMAX, C>(kap, S, e2s, w2, e1s, w1, pc);
+    }
+}
+
+// Kernels over labels with D attributes, each prescaled by sqrt(log2(e) / (2 l_a^2)).
+// RCONV false: Kronecker product of square exponentials, exp2(log2 A + log2 A' -
+// sum_a (e_a - e'_a)^2), with l1 / l2 the log2 weights (-inf on idle slots; lanes past
+// the run carry a huge attribute 0).  RCONV true: (A A' / D^2) sum_a sum_b
+// exp2(-(e_a - e'_b)^2), with l1 / l2 the weights themselves (0 where there is no entry).
+template <int K0, int SMAX, int C, bool RCONV>
+__device__ __forceinline__ void fill_attr(float (&kap)[C][SMAX], int S, int D,
+                                          const float (&e2a)[C][MGK_MAX_LABEL_DIM], const float (&l2)[C],
+                                          const float (&e1a)[MGK_MAX_LABEL_DIM], float l1) {
+    if constexpr (K0 < SMAX) {
+        if (K0 < S) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float e1[MGK_MAX_LABEL_DIM];
+#pragma unroll
+                for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a) e1[a] = a < D ? lane_value(e1a[a], K0 + u) : 0.f;
+                const float la = lane_value(l1, K0 + u);
+#pragma unroll
+                for (int c = 0; c < C; ++c) {
+                    if (RCONV) {
+                        float sum = 0.f;
+#pragma unroll
+                        for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a)
+#pragma unroll
+                            for (int b = 0; b < MGK_MAX_LABEL_DIM; ++b)
+                                if (a < D && b < D) {
+                                    const float d = e2a[c][a] - e1[b];
+                                    sum += __builtin_amdgcn_exp2f(-d * d);
+                                }
+                        kap[c][K0 + u] = sum * (l2[c] * la);
+                    } else {
+                        float t = l2[c] + la;
+#pragma unroll
+                        for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a)
+                            if (a < D) {
+                                const float d = e2a[c][a] - e1[a];
+                                t = __builtin_fmaf(-d, d, t);
+                            }
+                        kap[c][K0 + u] = __builtin_amdgcn_exp2f(t);
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int c = 0; c < C; ++c) kap[c][K0 + u] = 0.f;
+        }
+        fill_attr<K0 + 4, SMAX, C, RCONV>(kap, S, D, e2a, l2, e1a, l1);
+    }
+}
+
 // per-lane constants of the inner nonzeros, one set per chunk
 template <int C>
 struct InnerLanes {
@@ -257,7 +334,7 @@ __global__ __launch_bounds__(W * 64) void mgk_pcg_regs(MgkBatchDev X, MgkBatchDe
     InnerLanes<C> in;
     float kap[C][SMAX];
     {
-        float e2s[C], l2[C], w2c[C];
+        float e2s[C], l2[C], w2c[C], w2r[C];
 #pragma unroll
         for (int c = 0; c < C; ++c) {
             const int slot = c * 64 + lane;
@@ -271,12 +348,42 @@ __global__ __launch_bounds__(W * 64) void mgk_pcg_regs(MgkBatchDev X, MgkBatchDe
             e2s[c] = (__uint_as_float(e.z) - prm.e_shift) * prm.e_scale;
             l2[c] = w2 > 0.f ? (weighted ? __log2f(w2) : 0.f) : -__builtin_inff();
             w2c[c] = w2 * prm.ke_const;
+            w2r[c] = w2;
         }
         if (prm.edge_kernel == MGK_EK_SE) {
             if (weighted) fill_se<0, SMAX, C, true>(kap, S, e2s, l2, e1s, l1);
             else fill_se<0, SMAX, C, false>(kap, S, e2s, l2, e1s, l1);
-        } else {
+        } else if (prm.edge_kernel == MGK_EK_CONST) {
             fill_const<0, SMAX, C>(kap, S, w2c, w1);
+        } else if (prm.edge_kernel == MGK_EK_POLY) {
+            fill_poly<0, SMAX, C>(kap, S, e2s, w2r, e1s, w1, prm.poly_c);
+        } else {
+            // labels with D attributes, from the attribute planes of the two lists
+            const int D = prm.label_dim;
+            const bool rconv = prm.edge_kernel == MGK_EK_RCONV_SE;
+            float e1a[MGK_MAX_LABEL_DIM], e2a[C][MGK_MAX_LABEL_DIM], f2[C];
+#pragma unroll
+            for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a) {
+                const bool on = a < D;
+                const float raw1 = on && live1 ? X.attr_outer[(int64_t)a * X.nnz_total + g1.zoff + kbeg + lane] : 0.f;
+                e1a[a] = raw1 * prm.attr_scale[a];
+#pragma unroll
+                for (int c = 0; c < C; ++c) {
+                    const int slot = c * 64 + lane;
+                    const float raw2 = on && slot < len2 ? Y.attr_inner[(int64_t)a * Y.lanes_total + g2.loff + slot] : 0.f;
+                    e2a[c][a] = raw2 * prm.attr_scale[a];
+                }
+            }
+            if (rconv) {
+                const float inv = 1.0f / (float)(D * D);
+#pragma unroll
+                for (int c = 0; c < C; ++c) f2[c] = w2r[c] * inv;   // 0 on idle slots
+                fill_attr<0, SMAX, C, true>(kap, S, D, e2a, f2, e1a, w1);   // w1 is 0 past the run
+            } else {
+                if (!live1) e1a[0] = 1e18f;   // past the run: kappa_e underflows to exactly 0
+                const float la = weighted ? __log2f(live1 ? w1 : 1.f) : 0.f;
+                fill_attr<0, SMAX, C, false>(kap, S, D, e2a, l2, e1a, la);
+            }
         }
     }
     __syncthreads();   // per-vertex data staged

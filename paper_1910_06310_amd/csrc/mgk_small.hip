@@ -30,7 +30,8 @@ namespace {
 // row.  (Octiles of these graphs hold only a few nonzeros, so a thread per
 // nonzero wastes far fewer lanes than a lane per bit of every bitmap.)
 // Outer graph: CSR order, entry = {byte offset of p row j, scaled label (or
-// weight for the constant kernel), log2 weight, byte offset of y row i};
+// weight for the constant kernel), log2 weight (the weight itself for the
+// polynomial kernel), byte offset of y row i};
 // `rowend` gets bit k set when entry k is the last of its row.
 // Inner graph: lane layout (rows in adjacent lanes inside groups of 16), entry
 // = {i'*4 | rank in run << 20 | row-longer-than-16 << 30 | last-of-run << 31,
@@ -69,8 +70,8 @@ __device__ __forceinline__ void expand_nonzero(const MgkBatchDev& B, const MgkGr
     if (OUTER) {
         const int pos = rp0 + rank;
         v.x = (uint32_t)(col * n_inner * 4);
-        v.y = __float_as_uint(EK == MGK_EK_SE ? el : w);
-        v.z = __float_as_uint(WEIGHTED ? __log2f(w) : 0.f);
+        v.y = __float_as_uint(EK == MGK_EK_CONST ? w : el);
+        v.z = __float_as_uint(EK == MGK_EK_POLY ? w : WEIGHTED ? __log2f(w) : 0.f);
         v.w = (uint32_t)(row * n_inner * 4);
         ent[pos] = v;
         if (pos + 1 == rp1) atomicOr(&rowend[pos >> 5], 1u << (pos & 31));
@@ -82,8 +83,8 @@ __device__ __forceinline__ void expand_nonzero(const MgkBatchDev& B, const MgkGr
         const uint32_t longrow = deg > MGK_LANE_GROUP ? 1u : 0u;   // row cut into several runs
         v.x = (uint32_t)(row * 4) | (run_rank << 20) | (longrow << 30) | (last << 31);
         v.y = (uint32_t)(col * 4);
-        v.z = __float_as_uint(EK == MGK_EK_SE ? el : w);
-        v.w = __float_as_uint(WEIGHTED ? __log2f(w) : 0.f);
+        v.z = __float_as_uint(EK == MGK_EK_CONST ? w : el);
+        v.w = __float_as_uint(EK == MGK_EK_POLY ? w : WEIGHTED ? __log2f(w) : 0.f);
         ent[lp + rank] = v;
     }
 }
@@ -107,7 +108,7 @@ __device__ __forceinline__ int next_set_bit(const uint32_t* bits, int words, int
 template <int NSTEPS, bool WEIGHTED, int EK, bool ATOMIC>
 __device__ __forceinline__ void xmv_pass(const uint4* ent1, const uint4* ent2, const uint32_t* rowend,
                                          const char* pbytes, char* ybytes, int len2, int kbeg,
-                                         int kend, float ke_c, int lane) {
+                                         int kend, float ke_c, const float* pc, int lane) {
     for (int c = 0; c < len2; c += 64) {
         const uint4 e2 = ent2[c + lane];
         const uint32_t ip4 = e2.x & 0xfffffu, jp4 = e2.y;
@@ -142,6 +143,9 @@ __device__ __forceinline__ void xmv_pass(const uint4* ent1, const uint4* ent2, c
                         if (WEIGHTED) t = __builtin_fmaf(-d, d, lw2 + __uint_as_float(e1[u].z));
                         else t = __builtin_fmaf(-d, d, lw2);  // lw2: 0, or -inf on idle lanes
                         cu[u] = __builtin_amdgcn_exp2f(t);
+                    } else if (EK == MGK_EK_POLY) {
+                        cu[u] = mgk_poly_kernel(el2 - __uint_as_float(e1[u].y), pc);
+                        if (WEIGHTED) cu[u] *= __uint_as_float(e1[u].z);     // A_ij
                     } else {
                         cu[u] = WEIGHTED ? __uint_as_float(e1[u].y) : 1.f;  // A_ij
                     }
@@ -151,6 +155,7 @@ __device__ __forceinline__ void xmv_pass(const uint4* ent1, const uint4* ent2, c
                     acc = __builtin_fmaf(cu[u], pv[u], acc);
                     if ((window >> u) & 1u) {   // end of outer row i: sum over each inner row
                         if (EK == MGK_EK_CONST) acc *= ke_c * el2;  // el2 = A'_i'j' (0 on idle lanes)
+                        if (EK == MGK_EK_POLY) acc *= lw2;           // lw2 = A'_i'j' (0 on idle lanes)
                         if (NSTEPS > 0) acc = shr_fmac<1>(acc, m1);
                         if (NSTEPS > 1) acc = shr_fmac<2>(acc, m2);
                         if (NSTEPS > 2) acc = shr_fmac<4>(acc, m4);
@@ -218,7 +223,8 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
     // spare outer entries past z1 (read by the 4-wide loop, never used) and idle
     // lane slots of the inner layout: weight 0, address 0, never the end of a run
     for (int k = z1 + tid; k < L.z1pad; k += NT) ent1[k] = make_uint4(0u, 0u, 0u, 0u);
-    for (int k = tid; k < len2; k += NT) ent2[k] = make_uint4(0u, 0u, 0u, 0xff800000u);  // log2 w = -inf
+    // idle slots: log2 w = -inf, or w = 0 where the entry carries the weight itself
+    for (int k = tid; k < len2; k += NT) ent2[k] = make_uint4(0u, 0u, 0u, EK == MGK_EK_POLY ? 0u : 0xff800000u);
 #pragma unroll
     for (int m = 0; m < EPT; ++m) y[tid + m * NT] = 0.f;  // entries no row pair reaches stay 0
     __syncthreads();
@@ -284,11 +290,11 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
     while (it < max_iter) {
         // ---- XMV (Alg. 2): y_ii' = sum_{j,j'} A_ij A'_i'j' kappa_e(E_ij,E'_i'j') p_jj'
         switch (nsteps) {
-            case 0: xmv_pass<0, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, ke_c, lane); break;
-            case 1: xmv_pass<1, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, ke_c, lane); break;
-            case 2: xmv_pass<2, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, ke_c, lane); break;
-            case 3: xmv_pass<3, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, ke_c, lane); break;
-            default: xmv_pass<4, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, ke_c, lane); break;
+            case 0: xmv_pass<0, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, ke_c, prm.poly_c, lane); break;
+            case 1: xmv_pass<1, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, ke_c, prm.poly_c, lane); break;
+            case 2: xmv_pass<2, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, ke_c, prm.poly_c, lane); break;
+            case 3: xmv_pass<3, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, ke_c, prm.poly_c, lane); break;
+            default: xmv_pass<4, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, ke_c, prm.poly_c, lane); break;
         }
         __syncthreads();
 
@@ -400,6 +406,12 @@ hipError_t launch_we(bool weighted, bool atomic_rows, int ek, const MgkBatchDev&
         if (atomic_rows) MGK_GO(false, MGK_EK_SE, true);
         MGK_GO(false, MGK_EK_SE, false);
     }
+    if (ek == MGK_EK_POLY) {
+        if (weighted) { if (atomic_rows) MGK_GO(true, MGK_EK_POLY, true); MGK_GO(true, MGK_EK_POLY, false); }
+        if (atomic_rows) MGK_GO(false, MGK_EK_POLY, true);
+        MGK_GO(false, MGK_EK_POLY, false);
+    }
+    if (ek != MGK_EK_CONST) return hipErrorInvalidValue;   // kernels over label attributes do not run here
     if (weighted) { if (atomic_rows) MGK_GO(true, MGK_EK_CONST, true); MGK_GO(true, MGK_EK_CONST, false); }
     if (atomic_rows) MGK_GO(false, MGK_EK_CONST, true);
     MGK_GO(false, MGK_EK_CONST, false);
