@@ -15,6 +15,7 @@ from .generators import (  # noqa: F401
     config4,
     erdos_renyi_batch,
     molecule_like_batch,
+    morton_rank,
     geometric_batch,
     newman_watts_strogatz_batch,
     barabasi_albert_batch,

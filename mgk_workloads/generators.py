@@ -230,11 +230,28 @@ def _geometric_edges(pts, rc):
     return lo, hi, dist
 
 
-def geometric_batch(rng, n_graphs, n, mean_degree, n_vlabels, params, name="geo") -> GraphBatch:
+def morton_rank(pts: np.ndarray, bits: int = 10) -> np.ndarray:
+    """Position of each point of the unit cube along the Morton (Z-order) curve:
+    the coordinates are quantised to ``bits`` bits and their bits interleaved."""
+    q = np.minimum((np.asarray(pts) * (1 << bits)).astype(np.int64), (1 << bits) - 1)
+    key = np.zeros(len(q), dtype=np.int64)
+    for b in range(bits):
+        for axis in range(q.shape[1]):
+            key |= ((q[:, axis] >> b) & 1) << (q.shape[1] * b + axis)
+    rank = np.empty(len(q), dtype=np.int64)
+    rank[np.argsort(key, kind="stable")] = np.arange(len(q))
+    return rank
+
+
+def geometric_batch(rng, n_graphs, n, mean_degree, n_vlabels, params, name="geo",
+                    order: str = "random") -> GraphBatch:
     """Points uniform in the unit cube, edge iff distance < r_c.  r_c is
     calibrated once on the first point set so the mean degree is within 0.3 of
     the request, then used for every graph.  weight = exp(-dist), label = dist.
-    The point order is the random draw order (no spatial locality)."""
+    ``order``: "random" numbers the points in the draw order (no spatial
+    locality); "morton" numbers them along the Morton curve through the cube,
+    the space-filling-curve ordering for graphs that come with an embedding.
+    Both give the same graphs up to the numbering."""
     graphs = []
     rc = (3.0 * mean_degree / (4.0 * np.pi * n)) ** (1.0 / 3.0)
     calibrated = False
@@ -250,6 +267,14 @@ def geometric_batch(rng, n_graphs, n, mean_degree, n_vlabels, params, name="geo"
             calibrated = True
         lo, hi, dist = _geometric_edges(pts, rc)
         lab = rng.integers(0, n_vlabels, size=n)
+        if order == "morton":
+            rank = morton_rank(pts)
+            new_lab = np.empty_like(lab)
+            new_lab[rank] = lab
+            a, b = rank[lo], rank[hi]
+            lab, lo, hi = new_lab, np.minimum(a, b), np.maximum(a, b)
+        elif order != "random":
+            raise ValueError("order must be random or morton")
         graphs.append((n, lab, lo, hi, np.exp(-dist), dist))
     b = _assemble(graphs, params, name)
     b.cutoff = rc  # type: ignore[attr-defined]
@@ -335,12 +360,13 @@ def config2(density: float, n_graphs: int = 128, n: int = 256) -> GraphBatch:
                              "config2[rho=%g]" % density, w_min=1e-3)
 
 
-def config3(n_graphs: int = 32, n: int = 2048) -> GraphBatch:
+def config3(n_graphs: int = 32, n: int = 2048, order: str = "random") -> GraphBatch:
     """3-D random geometric graphs, mean degree ~12, w=exp(-d), label=d,
-    8 vertex labels, h=0.5, length scale 0.05; pair k is graphs (2k, 2k+1)."""
+    8 vertex labels, h=0.5, length scale 0.05; pair k is graphs (2k, 2k+1).
+    ``order`` as in ``geometric_batch`` (the configuration itself uses "random")."""
     rng = np.random.default_rng(SEED_BASE + 3)
     return geometric_batch(rng, n_graphs, n, 12.0, 8,
-                           KernelParams(q=0.05, h=0.5, length_scale=0.05), "config3")
+                           KernelParams(q=0.05, h=0.5, length_scale=0.05), "config3", order)
 
 
 def config4(n_graphs: int = 2000) -> GraphBatch:

@@ -139,3 +139,20 @@ def test_single_vertex_and_edgeless_graphs_pack(solver):
     B = solver.load_graphs([0, 1, 4], np.zeros(4, np.int32), [0, 0, 0], [], [])
     st = B.stats()
     assert st["n_tiles"] == 0 and st["nnz"] == 0 and st["n_vertices"] == 4
+
+
+def test_morton_numbering_of_geometric_graphs():
+    """The space-filling-curve ordering (Section IV-A) is a property of the input
+    numbering: the same graphs, far fewer non-empty octiles than the random
+    numbering, more than PBR finds."""
+    import mgk_workloads as W
+    from oracle import mgk_oracle as O
+    rnd = W.geometric_batch(np.random.default_rng(5), 2, 40, 5.0, 3, W.KernelParams(0.05, 0.5, 0.3), order="random")
+    mor = W.geometric_batch(np.random.default_rng(5), 2, 40, 5.0, 3, W.KernelParams(0.05, 0.5, 0.3), order="morton")
+    assert O.gram_values(mor, [0], [1])[0] == pytest.approx(O.gram_values(rnd, [0], [1])[0], rel=1e-12)
+    s = M.Solver(-1)
+    big_r, big_m = W.config3(2, 512, order="random"), W.config3(2, 512, order="morton")
+    t_rand = s.load_batch(big_r, reorder=M.REORDER_NONE).stats()["n_offdiag_tiles"]
+    t_mort = s.load_batch(big_m, reorder=M.REORDER_NONE).stats()["n_offdiag_tiles"]
+    t_pbr = s.load_batch(big_r, reorder=M.REORDER_PBR).stats()["n_offdiag_tiles"]
+    assert t_pbr < t_mort < 0.5 * t_rand
