@@ -1,5 +1,5 @@
-// Register-resident on-chip solver: one workgroup of four wavefronts runs the
-// whole preconditioned CG iteration (Alg. 1) for one graph pair whose
+// Register-resident on-chip solver: one workgroup of four or eight wavefronts
+// runs the whole preconditioned CG iteration (Alg. 1) for one graph pair whose
 // off-diagonal matrix fits in the register file.
 //
 // Alg. 2 regenerates the entries A_ij A'_i'j' kappa_e(E_ij, E'_i'j') in every
@@ -13,8 +13,11 @@
 // and the lane's inner nonzero of chunk c.  One XMV then costs, per entry, an
 // address add, a gathered LDS read of p_jj' and a multiply-add; the loop over k
 // is unrolled completely so that the register index is static.  The sum over
-// the lanes of an inner row at the end of an outer row, the single-writer store
-// of y_ii' and the vector part of the iteration are as in the streaming kernel.
+// the lanes of an inner row at the end of an outer row (DPP shift-and-add) and
+// the vector part of the iteration follow the streaming kernel; the edge base
+// kernel appears only in the one-off fill of the registers, so every base
+// kernel runs the same iteration.  x is kept in LDS beside p and y (it is
+// touched once per iteration), r, M, the owner's p and z in registers.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -24,14 +27,13 @@
 
 namespace {
 
-
+// value of v in lane k (k a compile-time constant after unrolling)
 __device__ __forceinline__ uint32_t lane_value(uint32_t v, int k) {
     return (uint32_t)__builtin_amdgcn_readlane((int)v, k);
 }
 __device__ __forceinline__ float lane_value(float v, int k) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), k));
 }
-
 
 // The loops over the wave's outer nonzeros are unrolled by template recursion,
 // four nonzeros per step, so that every index into the register array kap is a
