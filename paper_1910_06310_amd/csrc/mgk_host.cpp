@@ -946,6 +946,7 @@ mgk_status mgk_load_graphs_attr(mgk_ctx* ctx, int32_t n_graphs, const int64_t* v
     const size_t o_ao = append_bytes(blob, attr_outer);
     const size_t o_ai = append_bytes(blob, attr_inner);
     B->dev.label_dim = D;
+    B->dev.uniform_start = start_prob ? 0 : 1;
     B->dev.n_graphs = n_graphs;
     B->dev.n_tiles_total = (int32_t)B->tiles.size();
     B->dev.nnz_total = (int32_t)B->w.size();

@@ -63,6 +63,7 @@ struct MgkBatchDev {
     const float* attr_inner;  // the same in lane order: attr_inner[a * lanes_total + loff + slot], 0 on idle slots
     int32_t n_graphs, n_tiles_total, nnz_total, lanes_total;
     int32_t label_dim;        // attributes per edge label (1 for plain scalar labels)
+    int32_t uniform_start;    // 1: no starting probabilities were given, p_i = 1/n on every graph
 };
 
 // One unit of work: solve the pair (outer graph g1 of batch X, inner graph g2
