@@ -134,7 +134,7 @@ def main() -> int:
                     help="config4 (default, the benchmark line), config1, config2:<density>, config3, nws, ba")
     ap.add_argument("--waves", type=int, default=0, help="wavefronts per pair (0 = library default)")
     ap.add_argument("--reorder", type=int, default=1, help="0 none, 1 PBR, 2 RCM")
-    ap.add_argument("--tile-path", type=int, default=0, help="global-memory solver: 0 auto, 1 sparse, 2 dense")
+    ap.add_argument("--tile-path", type=int, default=0, help="global-memory solver: 0 auto, 1 sparse, 2 dense, 3 sparse with p gathered from global memory")
     ap.add_argument("--product-cache", type=int, default=1,
                     help="on-chip solver: 1 keep the matrix entries of small pairs in registers, 0 regenerate them")
     ap.add_argument("--edge-kernel", default="se",
@@ -301,7 +301,7 @@ def main() -> int:
             "q": wb.params.q, "h": wb.params.h, "length_scale": wb.params.length_scale,
             "rtol": 1e-6, "reorder": {0: "none", 1: "pbr", 2: "rcm"}[args.reorder],
             "waves_per_pair": args.waves or "auto",
-            "tile_path": {0: "auto", 1: "sparse", 2: "dense"}[args.tile_path],
+            "tile_path": {0: "auto", 1: "sparse", 2: "dense", 3: "sparse, global gathers"}[args.tile_path],
             "product_cache": bool(args.product_cache),
         },
         "matvec_element_pairs_per_s": element_pairs / kernel_s,
@@ -313,7 +313,7 @@ def main() -> int:
             "bound": "alu",
             "kernel": ("mgk_pcg_regs" if wl in ("config4", "config1") and args.product_cache and not args.waves
                        else "mgk_pcg_small" if wl in ("config4", "config1", "nws", "ba")
-                       else "mgk_large_xmv_dense_kernel / mgk_large_xmv_kernel (+ vector kernels)"),
+                       else "mgk_large_xmv_rows_kernel / mgk_large_xmv_dense_kernel (+ vector kernels)"),
             "achieved": achieved_tflops,
             "peak": FP32_VECTOR_PEAK_TFLOPS,
             "unit": "TFLOP/s",

@@ -57,7 +57,7 @@ typedef enum {
 /* vertex reordering applied when a batch is loaded (Section IV-A) */
 enum { MGK_REORDER_NONE = 0, MGK_REORDER_PBR = 1, MGK_REORDER_RCM = 2 };
 /* tile-pair primitive selection (Section IV-B, "hybrid dense-sparse") */
-enum { MGK_TILE_AUTO = 0, MGK_TILE_SPARSE = 1, MGK_TILE_DENSE = 2 };
+enum { MGK_TILE_AUTO = 0, MGK_TILE_SPARSE = 1, MGK_TILE_DENSE = 2, MGK_TILE_SPARSE_GATHER = 3 };
 
 /* Create a context on HIP device `device`.  *out is NULL on failure.
  * device = -1 creates a host-only context: graphs can be loaded, reordered,
@@ -105,8 +105,11 @@ mgk_status mgk_set_solver(mgk_ctx* ctx, float rtol, int32_t max_iter);
 /* Tile-pair primitive of the global-memory solver: sparse (only the nnz * nnz'
  * products of the nonzeros), dense (all 4096 products of every pair of
  * non-empty octiles, no gathers), or automatic per graph pair from the mean
- * fill of the two graphs' octiles.  The on-chip solver always uses the sparse
- * product. */
+ * fill of the two graphs' octiles.  The sparse product stages the rows of p
+ * that a row of the outer graph needs in LDS whenever a row of p (4 n' bytes)
+ * fits in 120 KB; MGK_TILE_SPARSE_GATHER forces the variant that gathers p from
+ * global memory instead (always used for larger n' and for the edge kernels
+ * over label attributes).  The on-chip solvers always use the sparse product. */
 mgk_status mgk_set_tile_path(mgk_ctx* ctx, int32_t mode);
 /* Tuning knobs, safe to leave alone.  waves_per_pair: wavefronts of the
  * workgroup that solves one on-chip pair (1, 2, 4, 8 or 16; 0 = automatic by

@@ -5,5 +5,5 @@ thin Python binding plus the in-tree build step.
 """
 from .binding import (  # noqa: F401
     Batch, MgkError, Solver, load_library, EXPORTS,
-    REORDER_NONE, REORDER_PBR, REORDER_RCM, TILE_AUTO, TILE_SPARSE, TILE_DENSE,
+    REORDER_NONE, REORDER_PBR, REORDER_RCM, TILE_AUTO, TILE_SPARSE, TILE_DENSE, TILE_SPARSE_GATHER,
 )

@@ -18,7 +18,7 @@ _lib = None
 
 OK, EINVAL, ENOMEM, EDEVICE, ESTATE, ELIMIT = range(6)
 REORDER_NONE, REORDER_PBR, REORDER_RCM = 0, 1, 2
-TILE_AUTO, TILE_SPARSE, TILE_DENSE = 0, 1, 2
+TILE_AUTO, TILE_SPARSE, TILE_DENSE, TILE_SPARSE_GATHER = 0, 1, 2, 3
 
 EXPORTS = [
     "mgk_create", "mgk_destroy", "mgk_last_error",

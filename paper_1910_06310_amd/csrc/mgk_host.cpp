@@ -88,6 +88,7 @@ struct mgk_ctx {
     int onchip_limit = MGK_SMALL_MAX_N;  // largest n n' given to the on-chip solver
     int product_cache = 1;      // small pairs keep their matrix entries in registers
     int cost_sorted = 1;        // expensive pairs first inside a launch
+    int row_staging = 1;        // global-memory sparse product stages rows of p in LDS
     JobList pair_jobs;          // reused by mgk_pairs
     int64_t pair_jobs_cap = 0;
     hipStream_t pair_jobs_stream = nullptr;
@@ -382,12 +383,12 @@ mgk_status ensure(mgk_ctx* ctx, DevBuf& b, size_t bytes) {
 // "hybrid dense-sparse"): the dense primitive evaluates all 4096 products of a
 // tile pair, the sparse one only nnz * nnz' of them but pays gathers and row
 // sums; the dense one wins when both graphs' tiles are well filled.
-constexpr int kDenseMinNnzPerTile = 24;
+constexpr int kDenseMinNnzPerTile = 46;
 
 bool use_dense_tiles(const mgk_ctx* ctx, const MgkGraphDesc& a, const MgkGraphDesc& b) {
     if (ctx->edge_kernel == MGK_EK_KRON_SE || ctx->edge_kernel == MGK_EK_RCONV_SE) return false;
     if (ctx->tile_path == MGK_TILE_DENSE) return true;
-    if (ctx->tile_path == MGK_TILE_SPARSE) return false;
+    if (ctx->tile_path == MGK_TILE_SPARSE || ctx->tile_path == MGK_TILE_SPARSE_GATHER) return false;
     return a.n_tiles > 0 && b.n_tiles > 0 &&
            (int64_t)a.nnz >= (int64_t)kDenseMinNnzPerTile * a.n_tiles &&
            (int64_t)b.nnz >= (int64_t)kDenseMinNnzPerTile * b.n_tiles;
@@ -426,8 +427,13 @@ mgk_status solve_large(mgk_ctx* ctx, const mgk_batch* A, const mgk_batch* Bb, in
     if (n_pairs == 0) return MGK_OK;
     int64_t total = 0;
     int max_npad = 0, max_iter = 0, xmv_blocks = 1;
+    int max_n1 = 1, max_n2 = 1, max_deg1 = 1, max_chunks = 1;
     constexpr int CPB = MGK_LARGE_WAVES * MGK_LARGE_CHUNKS_PER_WAVE;
     for (MgkLargePair& P : pairs) {
+        max_n1 = std::max(max_n1, P.n1);
+        max_n2 = std::max(max_n2, P.n2);
+        max_deg1 = std::max(max_deg1, A->graphs[P.g1].max_deg);
+        max_chunks = std::max(max_chunks, Bb->graphs[P.g2].lane_len / 64);
         P.vec = total;
         total += 5 * (int64_t)P.npad;
         max_npad = std::max(max_npad, P.npad);
@@ -438,6 +444,22 @@ mgk_status solve_large(mgk_ctx* ctx, const mgk_batch* A, const mgk_batch* Bb, in
             xmv_blocks = std::max(xmv_blocks, (A->graphs[P.g1].n_tile_rows * Bb->graphs[P.g2].n_tile_rows + 3) / 4);
         else
             xmv_blocks = std::max(xmv_blocks, rb * ((chunks + CPB - 1) / CPB));
+    }
+    // Sparse product: stage the rows of p a row of the outer graph needs in LDS when a row
+    // fits (one workgroup per outer row), else gather p from global memory.
+    // Up to 60 KB of LDS per workgroup of at most 8 wavefronts (two or more workgroups per
+    // CU); when the rows of p are so long that the neighbours of one outer row need more,
+    // one workgroup of 16 wavefronts per CU with up to 120 KB.
+    constexpr int kRowsLdsSmall = 60 * 1024, kRowsLdsLarge = 120 * 1024;
+    int rows_threads = 0, rows_lds_bytes = 0;
+    if (!dense && ctx->row_staging && streaming_ok(ctx) && (int64_t)max_n2 * 4 <= kRowsLdsLarge) {
+        const int64_t need = (int64_t)max_deg1 * max_n2 * 4;
+        const bool large = need > kRowsLdsSmall;
+        const int budget = large ? kRowsLdsLarge : kRowsLdsSmall;
+        const int rows = std::max(1, std::min(std::min(max_deg1, MGK_ROWS_MAX_BATCH), budget / (max_n2 * 4)));
+        rows_lds_bytes = rows * max_n2 * 4;   // + MGK_ROWS_MAX_BATCH outer entries, added by the launcher
+        rows_threads = 64 * std::max(1, std::min(large ? 16 : 8, (max_chunks + 1) / 2));
+        xmv_blocks = max_n1;
     }
     const int vec_blocks = std::max(1, std::min(2048, (max_npad + 1023) / 1024));
     mgk_status st;
@@ -492,7 +514,8 @@ mgk_status solve_large(mgk_ctx* ctx, const mgk_batch* A, const mgk_batch* Bb, in
     for (int it = 0; it < max_iter; ++it) {
         e = mgk_launch_large_iteration(A->dev, Bb->dev, ex[0], ex[1], dpairs, dstate, vec, prm, weighted,
                                        n_pairs, xmv_blocks, vec_blocks, dactive, it == 0,
-                                       dense ? &dt[0] : nullptr, dense ? &dt[1] : nullptr, stream);
+                                       dense ? &dt[0] : nullptr, dense ? &dt[1] : nullptr, rows_threads,
+                                       rows_lds_bytes, stream);
         if (e != hipSuccess) return fail(ctx, MGK_EDEVICE, "iteration launch failed: %s", hipGetErrorString(e));
         if ((it + 1) % check_every == 0 || it + 1 == max_iter) {
             MGK_HIP(ctx, hipMemcpyAsync(ctx->active_host, dactive, sizeof(int), hipMemcpyDeviceToHost, stream));
@@ -654,8 +677,9 @@ mgk_status mgk_set_solver(mgk_ctx* ctx, float rtol, int32_t max_iter) {
 
 mgk_status mgk_set_tile_path(mgk_ctx* ctx, int32_t mode) {
     if (!ctx) return MGK_EINVAL;
-    if (mode < MGK_TILE_AUTO || mode > MGK_TILE_DENSE) return fail(ctx, MGK_EINVAL, "unknown tile path %d", mode);
+    if (mode < MGK_TILE_AUTO || mode > MGK_TILE_SPARSE_GATHER) return fail(ctx, MGK_EINVAL, "unknown tile path %d", mode);
     ctx->tile_path = mode;
+    ctx->row_staging = mode == MGK_TILE_SPARSE_GATHER ? 0 : 1;
     return MGK_OK;
 }
 

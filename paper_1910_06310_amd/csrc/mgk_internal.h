@@ -206,7 +206,8 @@ static inline MGK_HD MgkRegsPlan mgk_regs_plan(int32_t n1, int32_t n2, int32_t w
 //   outer list (CSR order, index zoff + position): {col, scaled label or
 //     weight, log2 weight, row}
 //   inner list (lane layout, index loff + slot): {row, col | rank in run << 24
-//     | last of run << 31, scaled label or weight, log2 weight}
+//     | row longer than a lane group << 30 | last of run << 31, scaled label or
+//     weight, log2 weight (the weight itself for the kernels that multiply by it)}
 struct alignas(16) MgkEntry {
     uint32_t x, y, z, w;
 };
@@ -253,5 +254,6 @@ struct MgkPairState {
 #define MGK_LARGE_ROWS_PER_BLOCK 8    // outer rows per workgroup of the large XMV
 #define MGK_LARGE_CHUNKS_PER_WAVE 2   // 64-lane chunks of the inner layout per wave
 #define MGK_LARGE_WAVES 4
+#define MGK_ROWS_MAX_BATCH 64         // rows of p (= outer nonzeros) staged at a time by the row-staged XMV
 
 #endif

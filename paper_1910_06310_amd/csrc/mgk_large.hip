@@ -90,8 +90,9 @@ __global__ __launch_bounds__(256) void mgk_expand_kernel(MgkBatchDev B, MgkParam
     outer[g.zoff + rp0 + rank] = make_uint4((uint32_t)col, __float_as_uint(lab), __float_as_uint(lw), (uint32_t)row);
     const uint32_t run_rank = (uint32_t)rank % MGK_LANE_GROUP;
     const uint32_t last = (rank + 1 == rp1 - rp0 || run_rank == MGK_LANE_GROUP - 1) ? 1u : 0u;
+    const uint32_t longrow = rp1 - rp0 > MGK_LANE_GROUP ? 1u : 0u;   // row cut into several runs
     inner[g.loff + B.lanepos[g.voff + row] + rank] =
-        make_uint4((uint32_t)row, (uint32_t)col | (run_rank << 24) | (last << 31), __float_as_uint(lab),
+        make_uint4((uint32_t)row, (uint32_t)col | (run_rank << 24) | (longrow << 30) | (last << 31), __float_as_uint(lab),
                    __float_as_uint(lw));
 }
 
@@ -235,8 +236,122 @@ __global__ __launch_bounds__(kThreads) void mgk_large_xmv_kernel(
             if (P.nsteps > 3) acc = __builtin_fmaf(m8, row_shr<8>(acc), acc);
             if (last) {
                 float* dst = y + ((int64_t)i * n2 + ip);
+                // pairs with long inner rows add everywhere (y is cleared after every product):
+                // measured faster than atomics on the long-row lanes and plain stores on the rest
                 if (P.atomic_rows) atomicAdd(dst, acc);
                 else *dst = acc;
+            }
+        }
+    }
+}
+
+// ---- XMV with the needed rows of p staged in LDS -------------------------------------------
+// One workgroup per outer row i (grid.y = pair).  The rows p_j. of the neighbours j of i are
+// copied to LDS with coalesced loads, as many at a time as fit (`lds_floats` / n'), and every
+// (outer nonzero, inner nonzero) product then gathers p_jj' from LDS instead of from global
+// memory: a row is read from memory once and gathered from z' times (z' nonzeros of the
+// inner graph), so the 64-lane gathers no longer go through the L2.  Lane scheme, base kernel
+// evaluation and row sums as in mgk_large_xmv_kernel; the waves of the workgroup take the
+// 64-lane chunks of the inner graph in turn.  Edge kernels with one label per edge only.
+template <bool WEIGHTED, int EK>
+__global__ __launch_bounds__(1024) void mgk_large_xmv_rows_kernel(
+    MgkBatchDev X, MgkBatchDev Y, MgkExpanded EX, MgkExpanded EY, const MgkLargePair* pairs,
+    const MgkPairState* state, float* vec, MgkParams prm, int lds_floats) {
+    extern __shared__ __align__(16) float prow[];
+    static_assert(EK == MGK_EK_SE || EK == MGK_EK_CONST || EK == MGK_EK_POLY, "one label per edge");
+    if (state[blockIdx.y].done) return;
+    const MgkLargePair P = pairs[blockIdx.y];
+    const int i = blockIdx.x;
+    if (i >= P.n1) return;
+    const MgkGraphDesc g1 = X.graphs[P.g1], g2 = Y.graphs[P.g2];
+    const int32_t* rowptr1 = X.rowptr + g1.voff;
+    const int kb = rowptr1[i];
+    const int ke = (i + 1 < P.n1) ? rowptr1[i + 1] : g1.nnz;
+    if (kb == ke) return;   // whole workgroup: y_i. stays 0
+    const int n2 = P.n2;
+    const int chunks = g2.lane_len / 64;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nwaves = blockDim.x >> 6;
+    // the host sizes LDS for at least one row of p, plus MGK_ROWS_MAX_BATCH outer entries
+    const int bmax = min(max(lds_floats / n2, 1), MGK_ROWS_MAX_BATCH);
+    uint4* oent = reinterpret_cast<uint4*>(prow + lds_floats);   // the batch's outer entries
+    const float* p = vec + P.vec + 2 * (int64_t)P.npad;
+    float* y = vec + P.vec + 4 * (int64_t)P.npad;
+    const uint4* outer = reinterpret_cast<const uint4*>(EX.outer) + g1.zoff;
+    const uint4* inner = reinterpret_cast<const uint4*>(EY.inner) + g2.loff;
+    const float ke_c = prm.ke_const;
+
+    for (int b0 = kb; b0 < ke; b0 += bmax) {
+        const int nb = min(bmax, ke - b0);
+        if (b0 > kb) __syncthreads();   // every wave is done with the rows staged before
+        // the outer entries go to LDS too: in the product loop they are wave-uniform
+        // operands, and a global load of one address by 64 lanes costs a full memory access
+        if ((int)threadIdx.x < nb) oent[threadIdx.x] = outer[b0 + threadIdx.x];
+        for (int r = 0; r < nb; ++r) {
+            const int j = (int)outer[b0 + r].x;   // wave-uniform
+            const float* src = p + (int64_t)j * n2;
+            float* dst = prow + r * n2;
+            if ((n2 & 3) == 0) {   // rows start on 16-byte boundaries
+                const float4* s4 = reinterpret_cast<const float4*>(src);
+                float4* d4 = reinterpret_cast<float4*>(dst);
+                for (int t = threadIdx.x; t < (n2 >> 2); t += blockDim.x) d4[t] = s4[t];
+            } else {
+                for (int t = threadIdx.x; t < n2; t += blockDim.x) dst[t] = src[t];
+            }
+        }
+        __syncthreads();
+        uint4 e2_next = wave < chunks ? inner[wave * 64 + lane] : make_uint4(0u, 0u, 0u, 0u);
+        for (int c = wave; c < chunks; c += nwaves) {
+            const uint4 e2 = e2_next;
+            if (c + nwaves < chunks) e2_next = inner[(c + nwaves) * 64 + lane];   // in flight during this chunk
+            const int ip = (int)e2.x;
+            const uint32_t jp4 = (e2.y & 0xffffffu) * 4u;
+            const uint32_t rank = (e2.y >> 24) & 0xfu;
+            const bool last = (e2.y >> 31) != 0u;
+            const float el2 = __uint_as_float(e2.z);
+            const float lw2 = __uint_as_float(e2.w);
+            const char* pb = reinterpret_cast<const char*>(prow) + jp4;
+            float acc = 0.f;
+            for (int r0 = 0; r0 < nb; r0 += 4) {
+                uint4 e1[4];
+                float pv[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {   // past the batch: repeat its last entry with weight 0
+                    const int r = min(r0 + u, nb - 1);
+                    e1[u] = oent[r];            // wave-uniform LDS broadcast
+                    pv[u] = *reinterpret_cast<const float*>(pb + (size_t)r * n2 * 4);
+                    if (r0 + u >= nb) pv[u] = 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    float cu;
+                    if (EK == MGK_EK_SE) {
+                        const float d = el2 - __uint_as_float(e1[u].y);
+                        cu = __builtin_amdgcn_exp2f(__builtin_fmaf(-d, d, WEIGHTED ? lw2 + __uint_as_float(e1[u].z) : lw2));
+                    } else if (EK == MGK_EK_POLY) {
+                        cu = mgk_poly_kernel(el2 - __uint_as_float(e1[u].y), prm.poly_c);
+                        if (WEIGHTED) cu *= __uint_as_float(e1[u].z);
+                    } else {
+                        cu = WEIGHTED ? __uint_as_float(e1[u].y) : 1.f;
+                    }
+                    acc = __builtin_fmaf(cu, pv[u], acc);
+                }
+            }
+            if (EK == MGK_EK_CONST) acc *= ke_c * el2;
+            if (EK == MGK_EK_POLY) acc *= lw2;
+            const float m1 = rank >= 1 ? 1.f : 0.f, m2 = rank >= 2 ? 1.f : 0.f;
+            const float m4 = rank >= 4 ? 1.f : 0.f, m8 = rank >= 8 ? 1.f : 0.f;
+            if (P.nsteps > 0) acc = __builtin_fmaf(m1, row_shr<1>(acc), acc);
+            if (P.nsteps > 1) acc = __builtin_fmaf(m2, row_shr<2>(acc), acc);
+            if (P.nsteps > 2) acc = __builtin_fmaf(m4, row_shr<4>(acc), acc);
+            if (P.nsteps > 3) acc = __builtin_fmaf(m8, row_shr<8>(acc), acc);
+            if (last) {
+                float* dst = y + ((int64_t)i * n2 + ip);
+                // pairs with long inner rows add everywhere (y is cleared after every product)
+                if (P.atomic_rows) atomicAdd(dst, acc);
+                else if (b0 == kb) *dst = acc;
+                else *dst += acc;                   // same lane, later batch of this row
             }
         }
     }
@@ -548,9 +663,29 @@ hipError_t mgk_launch_large_iteration(const MgkBatchDev& X, const MgkBatchDev& Y
                                       MgkPairState* state, float* vec, const MgkParams& prm,
                                       bool weighted, int n_pairs, int xmv_blocks, int vec_blocks,
                                       int* n_active, bool first, const MgkDenseTiles* DX,
-                                      const MgkDenseTiles* DY, hipStream_t stream) {
+                                      const MgkDenseTiles* DY, int rows_threads, int rows_lds_bytes,
+                                      hipStream_t stream) {
     const dim3 gx(xmv_blocks, n_pairs), gv(vec_blocks, n_pairs), gs((n_pairs + 63) / 64);
-    if (DX != nullptr) {
+    if (DX == nullptr && rows_threads > 0) {
+        // xmv_blocks = largest number of outer rows of a pair
+#define MGK_ROWS(EKV) \
+    case EKV: { \
+        auto kern = weighted ? mgk_large_xmv_rows_kernel<true, EKV> : mgk_large_xmv_rows_kernel<false, EKV>; \
+        static bool configured[2] = {false, false}; \
+        if (!configured[weighted ? 1 : 0]) { \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, MGK_LDS_LIMIT_BYTES); \
+            if (e != hipSuccess) return e; \
+            configured[weighted ? 1 : 0] = true; \
+        } \
+        hipLaunchKernelGGL(kern, gx, dim3(rows_threads), rows_lds_bytes + MGK_ROWS_MAX_BATCH * sizeof(uint4), stream, X, Y, EX, EY, pairs, state, vec, prm, rows_lds_bytes / 4); \
+        break; }
+        switch (prm.edge_kernel) {
+            MGK_ROWS(MGK_EK_SE) MGK_ROWS(MGK_EK_CONST) MGK_ROWS(MGK_EK_POLY)
+            default: return hipErrorInvalidValue;
+        }
+#undef MGK_ROWS
+    } else if (DX != nullptr) {
         if (prm.edge_kernel == MGK_EK_SE)
             hipLaunchKernelGGL(mgk_large_xmv_dense_kernel<MGK_EK_SE>, gx, dim3(256), 0, stream, X, Y, *DX, *DY, pairs, state, vec, prm);
         else if (prm.edge_kernel == MGK_EK_POLY)

@@ -81,13 +81,18 @@ hipError_t mgk_launch_large_init(const MgkBatchDev& X, const MgkBatchDev& Y, con
                                  int vec_blocks, hipStream_t stream);
 // One iteration of Alg. 1 for all pairs that have not stopped; *n_active is
 // decremented for every pair that stops.  DX/DY non-null: dense tile-pair XMV
-// (xmv_blocks = workgroups of 4 output blocks), else the expanded sparse XMV.
+// (xmv_blocks = workgroups of 4 output blocks); else the sparse XMV on the
+// expanded lists: with rows_threads > 0 the one that stages rows of p in
+// rows_lds_bytes of LDS (xmv_blocks = outer rows, one workgroup of rows_threads
+// each; every row of p must fit), with rows_threads == 0 the one that gathers p
+// from global memory.
 hipError_t mgk_launch_large_iteration(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkExpanded& EX,
                                       const MgkExpanded& EY, const MgkLargePair* pairs,
                                       MgkPairState* state, float* vec, const MgkParams& prm,
                                       bool weighted, int n_pairs, int xmv_blocks, int vec_blocks,
                                       int* n_active, bool first, const MgkDenseTiles* DX,
-                                      const MgkDenseTiles* DY, hipStream_t stream);
+                                      const MgkDenseTiles* DY, int rows_threads, int rows_lds_bytes,
+                                      hipStream_t stream);
 // K = p_x^T x and the per-pair outputs.
 hipError_t mgk_launch_large_final(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkLargePair* pairs,
                                   MgkPairState* state, const float* vec, int n_pairs, int vec_blocks,

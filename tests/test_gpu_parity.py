@@ -306,13 +306,14 @@ def test_dense_and_sparse_tile_paths_agree(torch, solver, weighted):
         pi = np.repeat(np.arange(3), 2).astype(np.int32); pj = np.tile(np.arange(2), 3).astype(np.int32)
         ref = C.pairs(both, pi, pj + 3, tier=0)
         out = {}
-        for mode in (M.TILE_SPARSE, M.TILE_DENSE, M.TILE_AUTO):
+        for mode in (M.TILE_SPARSE, M.TILE_SPARSE_GATHER, M.TILE_DENSE, M.TILE_AUTO):
             solver.set_tile_path(mode)
             K, it, fl = run_pairs(torch, solver, BX, BY, pi, pj)
             np.testing.assert_allclose(K, ref, rtol=RTOL)
             assert (fl == 0).all()
             out[mode] = (K, it)
         np.testing.assert_allclose(out[M.TILE_DENSE][0], out[M.TILE_SPARSE][0], rtol=2e-5)
+        np.testing.assert_allclose(out[M.TILE_SPARSE_GATHER][0], out[M.TILE_SPARSE][0], rtol=2e-5)
         assert np.abs(out[M.TILE_DENSE][1] - out[M.TILE_SPARSE][1]).max() <= 1
         # constant edge kernel through the dense primitive
         solver.set_edge_kernel_const(0.5)
