@@ -7,8 +7,10 @@
  *
  * by running the Jacobi-preconditioned conjugate-gradient iteration of
  * Alg. 1 on the tensor-product system of each requested pair, with the
- * off-diagonal product (A (x) A') (.) (E (x)k E') p regenerated on the fly from
- * the two graphs (Alg. 2, Section III) instead of being stored.  Graphs are
+ * off-diagonal product (A (x) A') (.) (E (x)k E') p formed from the two graphs
+ * (Alg. 2, Section III) instead of from a stored N x N matrix: regenerated in
+ * every iteration, or, for pairs of small graphs, generated once per solve
+ * into registers (mgk_set_product_cache).  Graphs are
  * held on the device as coordinate lists of non-empty 8x8 tiles ("octiles",
  * Section III-D) with a 64-bit occupancy bitmap and packed nonzeros per tile
  * (Section IV-A/B), after an optional partition-based vertex reordering
