@@ -110,8 +110,7 @@ mgk_status mgk_set_solver(mgk_ctx* ctx, float rtol, int32_t max_iter);
  * fill of the two graphs' octiles.  The sparse product stages the rows of p
  * that a row of the outer graph needs in LDS whenever a row of p (4 n' bytes)
  * fits in 120 KB; MGK_TILE_SPARSE_GATHER forces the variant that gathers p from
- * global memory instead (always used for larger n' and for the edge kernels
- * over label attributes).  The on-chip solvers always use the sparse product. */
+ * global memory instead (always used for larger n').  The on-chip solvers always use the sparse product. */
 mgk_status mgk_set_tile_path(mgk_ctx* ctx, int32_t mode);
 /* Tuning knobs, safe to leave alone.  waves_per_pair: wavefronts of the
  * workgroup that solves one on-chip pair (1, 2, 4, 8 or 16; 0 = automatic by

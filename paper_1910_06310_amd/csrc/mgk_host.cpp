@@ -452,12 +452,12 @@ mgk_status solve_large(mgk_ctx* ctx, const mgk_batch* A, const mgk_batch* Bb, in
     // one workgroup of 16 wavefronts per CU with up to 120 KB.
     constexpr int kRowsLdsSmall = 60 * 1024, kRowsLdsLarge = 120 * 1024;
     int rows_threads = 0, rows_lds_bytes = 0;
-    if (!dense && ctx->row_staging && streaming_ok(ctx) && (int64_t)max_n2 * 4 <= kRowsLdsLarge) {
+    if (!dense && ctx->row_staging && (int64_t)max_n2 * 4 <= kRowsLdsLarge) {
         const int64_t need = (int64_t)max_deg1 * max_n2 * 4;
         const bool large = need > kRowsLdsSmall;
         const int budget = large ? kRowsLdsLarge : kRowsLdsSmall;
         const int rows = std::max(1, std::min(std::min(max_deg1, MGK_ROWS_MAX_BATCH), budget / (max_n2 * 4)));
-        rows_lds_bytes = rows * max_n2 * 4;   // + MGK_ROWS_MAX_BATCH outer entries, added by the launcher
+        rows_lds_bytes = rows * max_n2 * 4;   // + the batch's outer entries and attributes, added by the launcher
         rows_threads = 64 * std::max(1, std::min(large ? 16 : 8, (max_chunks + 1) / 2));
         xmv_blocks = max_n1;
     }

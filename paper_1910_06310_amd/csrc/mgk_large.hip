@@ -252,14 +252,16 @@ __global__ __launch_bounds__(kThreads) void mgk_large_xmv_kernel(
 // memory: a row is read from memory once and gathered from z' times (z' nonzeros of the
 // inner graph), so the 64-lane gathers no longer go through the L2.  Lane scheme, base kernel
 // evaluation and row sums as in mgk_large_xmv_kernel; the waves of the workgroup take the
-// 64-lane chunks of the inner graph in turn.  Edge kernels with one label per edge only.
+// 64-lane chunks of the inner graph in turn.  For the edge kernels over label attributes
+// the batch's outer attributes are staged (prescaled) next to the outer entries.
 template <bool WEIGHTED, int EK>
 __global__ __launch_bounds__(1024) void mgk_large_xmv_rows_kernel(
     MgkBatchDev X, MgkBatchDev Y, MgkExpanded EX, MgkExpanded EY, const MgkLargePair* pairs,
     const MgkPairState* state, float* vec, MgkParams prm, int lds_floats) {
     extern __shared__ __align__(16) float prow[];
-    static_assert(EK == MGK_EK_SE || EK == MGK_EK_CONST || EK == MGK_EK_POLY, "one label per edge");
+    constexpr bool ATTR = EK == MGK_EK_KRON_SE || EK == MGK_EK_RCONV_SE;   // labels with D attributes
     if (state[blockIdx.y].done) return;
+    const int D = prm.label_dim;
     const MgkLargePair P = pairs[blockIdx.y];
     const int i = blockIdx.x;
     if (i >= P.n1) return;
@@ -276,6 +278,9 @@ __global__ __launch_bounds__(1024) void mgk_large_xmv_rows_kernel(
     // the host sizes LDS for at least one row of p, plus MGK_ROWS_MAX_BATCH outer entries
     const int bmax = min(max(lds_floats / n2, 1), MGK_ROWS_MAX_BATCH);
     uint4* oent = reinterpret_cast<uint4*>(prow + lds_floats);   // the batch's outer entries
+    // their label attributes, prescaled: oattr[a * MGK_ROWS_MAX_BATCH + r]
+    float* oattr = reinterpret_cast<float*>(oent + MGK_ROWS_MAX_BATCH);
+    const float w2div = 1.0f / (float)(D * D);
     const float* p = vec + P.vec + 2 * (int64_t)P.npad;
     float* y = vec + P.vec + 4 * (int64_t)P.npad;
     const uint4* outer = reinterpret_cast<const uint4*>(EX.outer) + g1.zoff;
@@ -287,7 +292,17 @@ __global__ __launch_bounds__(1024) void mgk_large_xmv_rows_kernel(
         if (b0 > kb) __syncthreads();   // every wave is done with the rows staged before
         // the outer entries go to LDS too: in the product loop they are wave-uniform
         // operands, and a global load of one address by 64 lanes costs a full memory access
-        if ((int)threadIdx.x < nb) oent[threadIdx.x] = outer[b0 + threadIdx.x];
+        if ((int)threadIdx.x < nb) {
+            oent[threadIdx.x] = outer[b0 + threadIdx.x];
+            if (ATTR) {
+#pragma unroll
+                for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a)
+                    if (a < D)
+                        oattr[a * MGK_ROWS_MAX_BATCH + threadIdx.x] =
+                            X.attr_outer[(int64_t)a * X.nnz_total + g1.zoff + b0 + threadIdx.x] *
+                            prm.attr_scale[EK == MGK_EK_RCONV_SE ? 0 : a];
+            }
+        }
         for (int r = 0; r < nb; ++r) {
             const int j = (int)outer[b0 + r].x;   // wave-uniform
             const float* src = p + (int64_t)j * n2;
@@ -312,6 +327,14 @@ __global__ __launch_bounds__(1024) void mgk_large_xmv_rows_kernel(
             const float el2 = __uint_as_float(e2.z);
             const float lw2 = __uint_as_float(e2.w);
             const char* pb = reinterpret_cast<const char*>(prow) + jp4;
+            float e2a[MGK_MAX_LABEL_DIM] = {0.f, 0.f, 0.f, 0.f};   // this lane's attributes, prescaled
+            if (ATTR) {
+#pragma unroll
+                for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a)
+                    if (a < D)
+                        e2a[a] = Y.attr_inner[(int64_t)a * Y.lanes_total + g2.loff + c * 64 + lane] *
+                                 prm.attr_scale[EK == MGK_EK_RCONV_SE ? 0 : a];
+            }
             float acc = 0.f;
             for (int r0 = 0; r0 < nb; r0 += 4) {
                 uint4 e1[4];
@@ -332,6 +355,31 @@ __global__ __launch_bounds__(1024) void mgk_large_xmv_rows_kernel(
                     } else if (EK == MGK_EK_POLY) {
                         cu = mgk_poly_kernel(el2 - __uint_as_float(e1[u].y), prm.poly_c);
                         if (WEIGHTED) cu *= __uint_as_float(e1[u].z);
+                    } else if (EK == MGK_EK_KRON_SE) {
+                        const int r = min(r0 + u, nb - 1);
+                        float t = WEIGHTED ? lw2 + __uint_as_float(e1[u].z) : lw2;
+#pragma unroll
+                        for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a)
+                            if (a < D) {
+                                const float d = e2a[a] - oattr[a * MGK_ROWS_MAX_BATCH + r];
+                                t = __builtin_fmaf(-d, d, t);
+                            }
+                        cu = __builtin_amdgcn_exp2f(t);
+                    } else if (EK == MGK_EK_RCONV_SE) {
+                        const int r = min(r0 + u, nb - 1);
+                        cu = 0.f;
+#pragma unroll
+                        for (int b = 0; b < MGK_MAX_LABEL_DIM; ++b)
+                            if (b < D) {
+                                const float e1b = oattr[b * MGK_ROWS_MAX_BATCH + r];
+#pragma unroll
+                                for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a)
+                                    if (a < D) {
+                                        const float d = e2a[a] - e1b;
+                                        cu += __builtin_amdgcn_exp2f(-d * d);
+                                    }
+                            }
+                        if (WEIGHTED) cu *= __uint_as_float(e1[u].z);
                     } else {
                         cu = WEIGHTED ? __uint_as_float(e1[u].y) : 1.f;
                     }
@@ -340,6 +388,7 @@ __global__ __launch_bounds__(1024) void mgk_large_xmv_rows_kernel(
             }
             if (EK == MGK_EK_CONST) acc *= ke_c * el2;
             if (EK == MGK_EK_POLY) acc *= lw2;
+            if (EK == MGK_EK_RCONV_SE) acc *= lw2 * w2div;   // A'_i'j' / D^2 (0 on idle lanes)
             const float m1 = rank >= 1 ? 1.f : 0.f, m2 = rank >= 2 ? 1.f : 0.f;
             const float m4 = rank >= 4 ? 1.f : 0.f, m8 = rank >= 8 ? 1.f : 0.f;
             if (P.nsteps > 0) acc = __builtin_fmaf(m1, row_shr<1>(acc), acc);
@@ -678,10 +727,11 @@ hipError_t mgk_launch_large_iteration(const MgkBatchDev& X, const MgkBatchDev& Y
             if (e != hipSuccess) return e; \
             configured[weighted ? 1 : 0] = true; \
         } \
-        hipLaunchKernelGGL(kern, gx, dim3(rows_threads), rows_lds_bytes + MGK_ROWS_MAX_BATCH * sizeof(uint4), stream, X, Y, EX, EY, pairs, state, vec, prm, rows_lds_bytes / 4); \
+        hipLaunchKernelGGL(kern, gx, dim3(rows_threads), rows_lds_bytes + MGK_ROWS_MAX_BATCH * (sizeof(uint4) + MGK_MAX_LABEL_DIM * sizeof(float)), stream, X, Y, EX, EY, pairs, state, vec, prm, rows_lds_bytes / 4); \
         break; }
         switch (prm.edge_kernel) {
             MGK_ROWS(MGK_EK_SE) MGK_ROWS(MGK_EK_CONST) MGK_ROWS(MGK_EK_POLY)
+            MGK_ROWS(MGK_EK_KRON_SE) MGK_ROWS(MGK_EK_RCONV_SE)
             default: return hipErrorInvalidValue;
         }
 #undef MGK_ROWS

@@ -64,7 +64,7 @@ def test_compact_polynomial_all_solvers(torch, solver, weighted):
     pi, pj = W.gram_pairs(8)
     ref = C.pairs(wb, pi, pj, tier=0)
     for kw in (dict(), dict(cache=False), dict(onchip=0, tile_path=M.TILE_SPARSE),
-               dict(onchip=0, tile_path=M.TILE_DENSE)):
+               dict(onchip=0, tile_path=M.TILE_SPARSE_GATHER), dict(onchip=0, tile_path=M.TILE_DENSE)):
         got = pairs_on(torch, solver, wb, pi, pj, **kw)
         np.testing.assert_allclose(got, ref, rtol=RTOL, err_msg=str(kw))
     # graphs with long rows (streaming kernel with atomics, dense tiles)
@@ -97,7 +97,7 @@ def test_attribute_kernels_on_chip_and_in_global_memory(torch, solver, kind, wei
     wa = W.with_label_attributes(wb, rng, dim, 0.3, prm)
     pi, pj = W.gram_pairs(8)
     ref = C.pairs(wa, pi, pj, tier=0)
-    for kw in (dict(), dict(onchip=0), dict(reorder=M.REORDER_NONE)):
+    for kw in (dict(), dict(onchip=0), dict(onchip=0, tile_path=M.TILE_SPARSE_GATHER), dict(reorder=M.REORDER_NONE)):
         got = pairs_on(torch, solver, wa, pi, pj, **kw)
         np.testing.assert_allclose(got, ref, rtol=RTOL, err_msg=str(kw))
     # larger, denser graphs: on chip nothing fits, the sparse product in global memory runs
@@ -106,8 +106,9 @@ def test_attribute_kernels_on_chip_and_in_global_memory(torch, solver, kind, wei
     ea = W.with_label_attributes(er, np.random.default_rng(6), dim, 0.5, prm)
     pi, pj = W.gram_pairs(4)
     ref = C.pairs(ea, pi, pj, tier=1)
-    got = pairs_on(torch, solver, ea, pi, pj)
-    np.testing.assert_allclose(got, ref, rtol=RTOL)
+    for kw in (dict(), dict(tile_path=M.TILE_SPARSE_GATHER)):
+        got = pairs_on(torch, solver, ea, pi, pj, **kw)
+        np.testing.assert_allclose(got, ref, rtol=RTOL, err_msg=str(kw))
 
 
 def test_attribute_kernel_needs_matching_batch(torch, solver):
