@@ -30,7 +30,8 @@
  *  - Calls that include pairs too large for the on-chip solver synchronise the
  *    stream before returning (the host watches how many of them still iterate)
  *    and allocate device scratch owned by the ctx (5 vectors of n n' floats per
- *    such pair, plus expanded nonzero lists of the batches).
+ *    such pair, plus expanded nonzero lists of the batches).  Such pairs are
+ *    solved in groups of at most 4096 pairs and 8 GiB of vectors.
  *  - Non-convergence is data, not an error: the pair's flag is set to 1 and the
  *    value of the last iterate is still written.
  *  - Precision: fp32 on the device.  Product index of (i,i') is i*n'+i'.

@@ -548,12 +548,30 @@ mgk_status launch_jobs(mgk_ctx* ctx, const mgk_batch* X, const mgk_batch* Y, con
             done += chunk;
         }
     }
-    for (int dense = 0; dense < 2; ++dense) {
-        mgk_status st = solve_large(ctx, X, Y, 0, 1, jl.large[0][dense], dense != 0, out, stream, prm, weighted);
-        if (st != MGK_OK) return st;
-        st = solve_large(ctx, Y, X, 1, 0, jl.large[1][dense], dense != 0, out, stream, prm, weighted);
-        if (st != MGK_OK) return st;
-    }
+    // Pairs with vectors in global memory go in groups: the pair index is a grid dimension
+    // (at most 65535) and every pair of a group holds 5 vectors of scratch at the same time.
+    constexpr size_t kMaxPairsPerGroup = 4096;
+    constexpr int64_t kMaxScratchFloats = (int64_t)1 << 31;   // 8 GiB
+    for (int dense = 0; dense < 2; ++dense)
+        for (int swapped = 0; swapped < 2; ++swapped) {
+            const std::vector<MgkLargePair>& all = jl.large[swapped][dense];
+            size_t first = 0;
+            while (first < all.size()) {
+                size_t last = first;
+                int64_t floats = 0;
+                while (last < all.size() && last - first < kMaxPairsPerGroup &&
+                       (last == first || floats + 5 * (int64_t)all[last].npad <= kMaxScratchFloats)) {
+                    floats += 5 * (int64_t)all[last].npad;
+                    ++last;
+                }
+                std::vector<MgkLargePair> group(all.begin() + (std::ptrdiff_t)first, all.begin() + (std::ptrdiff_t)last);
+                const mgk_status st = swapped
+                    ? solve_large(ctx, Y, X, 1, 0, std::move(group), dense != 0, out, stream, prm, weighted)
+                    : solve_large(ctx, X, Y, 0, 1, std::move(group), dense != 0, out, stream, prm, weighted);
+                if (st != MGK_OK) return st;
+                first = last;
+            }
+        }
     return MGK_OK;
 }
 

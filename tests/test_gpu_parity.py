@@ -274,6 +274,23 @@ def test_global_memory_solver_weighted_long_rows_two_batches(torch, solver):
         solver.set_solver(1e-6, 0)
 
 
+def test_many_pairs_in_global_memory_are_solved_in_groups(torch, solver):
+    """More pairs than one group of the global-memory solver takes (4096): the whole
+    config 1 Gram with the on-chip solvers switched off."""
+    wb = W.config1()
+    solver.set_solver(1e-6, 0)
+    solver.set_launch(0)
+    solver.set_onchip_limit(0)
+    try:
+        K, it, fl = run_gram(torch, solver, wb)
+    finally:
+        solver.set_onchip_limit(16384)
+    pi, pj = W.gram_pairs(100)
+    ref = C.pairs(wb, pi, pj, tier=1)
+    np.testing.assert_allclose(K[pi, pj], ref, rtol=RTOL)
+    assert (K == K.T).all() and (fl == 0).all() and (it > 0).all()
+
+
 def test_mixed_sizes_in_one_call(torch, solver):
     # one Gram whose pairs are split between the on-chip and the global-memory solver
     rng = np.random.default_rng(33)
