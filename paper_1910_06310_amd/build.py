@@ -27,7 +27,7 @@ HOST_SOURCES = ["mgk_host.cpp", "mgk_reorder.cpp"]
 HIP_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
              "-munsafe-fp-atomics", "-Wall", "-Wno-unused-function"]
-HOST_FLAGS = ["-O2", "-std=c++17", "-fPIC", "-Wall", "-D__HIP_PLATFORM_AMD__=1"]
+HOST_FLAGS = ["-O2", "-std=c++17", "-fPIC", "-pthread", "-Wall", "-D__HIP_PLATFORM_AMD__=1"]
 
 
 def _hipcc() -> str:
@@ -64,7 +64,7 @@ def build(verbose: bool = False) -> str:
         objs.append(obj)
     with ThreadPoolExecutor(max_workers=min(8, len(cmds))) as pool:
         list(pool.map(_run, cmds))
-    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-pthread", "-o", LIB] + objs)
     if verbose:
         print("built", LIB)
     return LIB

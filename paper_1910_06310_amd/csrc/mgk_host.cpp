@@ -10,6 +10,7 @@
 #include <new>
 #include <numeric>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "../../include/mgk.h"
@@ -791,6 +792,47 @@ mgk_status mgk_load_graphs_attr(mgk_ctx* ctx, int32_t n_graphs, const int64_t* v
     MgkAdj adj;
     std::vector<int32_t> cursor;
 
+    // The vertex orders are by far the most expensive part of loading and independent per
+    // graph: they are computed first, on several threads, for every graph whose edge list is
+    // sound.  The loop below validates each graph in full (so errors are reported as before,
+    // for the first bad graph) and only then takes the order computed here.
+    std::vector<std::vector<int32_t>> pre_perm((size_t)n_graphs);
+    if (reorder != MGK_REORDER_NONE && n_graphs >= 8) {
+        const int T = (int)std::max(1u, std::min({std::thread::hardware_concurrency(), 16u, (unsigned)n_graphs / 4u}));
+        auto order_worker = [&](int t) {
+            MgkAdj a;
+            std::vector<int32_t> cur;
+            for (int32_t g = t; g < n_graphs; g += T) {
+                const int64_t v0 = vtx_off[g], v1 = vtx_off[g + 1], e0 = edge_off[g], e1 = edge_off[g + 1];
+                if (v1 <= v0 || e1 < e0 || v1 - v0 > 65535 * (int64_t)kTile) continue;
+                const int n = (int)(v1 - v0);
+                bool sound = true;
+                a.n = n;
+                a.ptr.assign(n + 1, 0);
+                for (int64_t k = e0; k < e1 && sound; ++k) {
+                    const int32_t sv = src[k], dv = dst[k];
+                    if (sv < 0 || sv >= n || dv < 0 || dv >= n || sv == dv) { sound = false; break; }
+                    a.ptr[sv + 1]++;
+                    a.ptr[dv + 1]++;
+                }
+                if (!sound) continue;
+                for (int i = 0; i < n; ++i) a.ptr[i + 1] += a.ptr[i];
+                a.idx.assign((size_t)(2 * (e1 - e0)), 0);
+                cur.assign(a.ptr.begin(), a.ptr.end() - 1);
+                for (int64_t k = e0; k < e1; ++k) {
+                    a.idx[cur[src[k]]++] = dst[k];
+                    a.idx[cur[dst[k]]++] = src[k];
+                }
+                for (int i = 0; i < n; ++i) std::sort(a.idx.begin() + a.ptr[i], a.idx.begin() + a.ptr[i + 1]);
+                pre_perm[(size_t)g] = reorder == MGK_REORDER_PBR ? mgk_order_pbr(a, kTile) : mgk_order_rcm(a);
+            }
+        };
+        std::vector<std::thread> pool;
+        for (int t = 1; t < T; ++t) pool.emplace_back(order_worker, t);
+        order_worker(0);
+        for (std::thread& th : pool) th.join();
+    }
+
     for (int32_t g = 0; g < n_graphs; ++g) {
         const int64_t v0 = vtx_off[g], v1 = vtx_off[g + 1], e0 = edge_off[g], e1 = edge_off[g + 1];
         if (v1 <= v0) return fail(ctx, MGK_EINVAL, "graph %d has no vertices", g);
@@ -836,7 +878,8 @@ mgk_status mgk_load_graphs_attr(mgk_ctx* ctx, int32_t n_graphs, const int64_t* v
 
         // ---- a2: vertex order
         std::vector<int32_t> perm;
-        if (reorder == MGK_REORDER_PBR) perm = mgk_order_pbr(adj, kTile);
+        if (!pre_perm[(size_t)g].empty()) perm = std::move(pre_perm[(size_t)g]);
+        else if (reorder == MGK_REORDER_PBR) perm = mgk_order_pbr(adj, kTile);
         else if (reorder == MGK_REORDER_RCM) perm = mgk_order_rcm(adj);
         else perm = mgk_order_identity(n);
         std::copy(perm.begin(), perm.end(), B->perm.begin() + v0);
@@ -1093,9 +1136,29 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
         std::vector<HostJob> jobs;
         jobs.reserve((size_t)(G * (G + 1) / 2));
         for (auto& a : batch->gram_jobs.large) for (auto& v : a) v.clear();
+        // the plans of the G (G + 1) / 2 pairs are independent: rows of the triangle in turn on
+        // several threads, row i starting at pair i G - i (i - 1) / 2
+        std::vector<PairPlan> plans((size_t)(G * (G + 1) / 2));
+        {
+            const bool cache = ctx->product_cache != 0, stream_ok = streaming_ok(ctx);
+            const int forced = ctx->waves, limit = ctx->onchip_limit;
+            const int T = (int)std::max<int64_t>(1, std::min<int64_t>({(int64_t)std::thread::hardware_concurrency(), 16, G / 64}));
+            auto plan_worker = [&](int t) {
+                for (int64_t i = t; i < G; i += T) {
+                    PairPlan* row = plans.data() + (i * G - i * (i - 1) / 2);
+                    for (int64_t j = i; j < G; ++j)
+                        row[j - i] = plan_pair(batch->graphs[i], batch->graphs[j], true, forced, limit, cache, stream_ok);
+                }
+            };
+            std::vector<std::thread> pool;
+            for (int t = 1; t < T; ++t) pool.emplace_back(plan_worker, t);
+            plan_worker(0);
+            for (std::thread& th : pool) th.join();
+        }
+        size_t next_plan = 0;
         for (int64_t i = 0; i < G; ++i)
             for (int64_t j = i; j < G; ++j) {
-                const PairPlan pl = plan_pair(batch->graphs[i], batch->graphs[j], true, ctx->waves, ctx->onchip_limit, ctx->product_cache != 0, streaming_ok(ctx));
+                const PairPlan pl = plans[next_plan++];
                 HostJob hj;
                 hj.job.g1 = (int32_t)(pl.swap ? j : i);
                 hj.job.g2 = (int32_t)(pl.swap ? i : j);
