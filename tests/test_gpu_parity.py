@@ -182,6 +182,29 @@ def test_unlabeled_random_walk_kernel(torch, solver):
     np.testing.assert_allclose(K2, C.pairs(wb2, pi, pj, tier=0), rtol=RTOL)  # all labels 0 -> kappa_e = 1
 
 
+@pytest.mark.parametrize("q", [0.005, 0.0005])
+def test_small_stopping_probabilities(torch, solver, q):
+    """The paper reports solves down to q = 0.0005 on labeled graphs (Section VI): long
+    walks dominate, the system stays well conditioned through the vertex and edge kernels."""
+    import dataclasses
+    wb = W.config1(30)
+    wb.params = dataclasses.replace(wb.params, q=q)
+    solver.configure(wb.params)
+    solver.set_solver(1e-6, 0)
+    solver.set_launch(0)
+    B = solver.load_batch(wb)
+    pi, pj = W.gram_pairs(30)
+    ref = C.pairs(wb, pi, pj, tier=0)
+    try:
+        for cache in (True, False):
+            solver.set_product_cache(cache)
+            K, it, fl = run_pairs(torch, solver, B, B, pi, pj)
+            np.testing.assert_allclose(K, ref, rtol=RTOL)
+            assert (fl == 0).all()
+    finally:
+        solver.set_product_cache(True)
+
+
 def test_iteration_cap_sets_flag(torch, solver):
     wb = W.config1(8)
     solver.configure(wb.params)
