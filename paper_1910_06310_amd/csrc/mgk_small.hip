@@ -101,79 +101,150 @@ __device__ __forceinline__ int next_set_bit(const uint32_t* bits, int words, int
     }
 }
 
-// One XMV (Alg. 2) over this wave's share [kbeg, kend) of the outer nonzeros:
+// One XMV (Alg. 2) over this wave's share [kbeg, kend) of the outer nonzeros and CB
+// chunks of 64 inner lane slots starting at ent2c[0] (this lane's slot of the first):
 // y_ii' = sum_{j,j'} A_ij A'_i'j' kappa_e(E_ij, E'_i'j') p_jj'.  NSTEPS DPP
 // shift-and-add steps sum the lanes of each inner row (rows of up to 2^NSTEPS
-// nonzeros).
-template <int NSTEPS, bool WEIGHTED, int EK, bool ATOMIC>
-__device__ __forceinline__ void xmv_pass(const uint4* ent1, const uint4* ent2, const uint32_t* rowend,
-                                         const char* pbytes, char* ybytes, int len2, int kbeg,
-                                         int kend, float ke_c, const float* pc, int lane) {
-    for (int c = 0; c < len2; c += 64) {
-        const uint4 e2 = ent2[c + lane];
-        const uint32_t ip4 = e2.x & 0xfffffu, jp4 = e2.y;
-        const uint32_t rank = (e2.x >> 20) & 0xffu;
-        const bool last = (e2.x >> 31) != 0u;
-        const bool longrow = ((e2.x >> 30) & 1u) != 0u;
-        const float el2 = __uint_as_float(e2.z);
-        const float lw2 = __uint_as_float(e2.w);
-        const float m1 = rank >= 1 ? 1.f : 0.f, m2 = rank >= 2 ? 1.f : 0.f;
-        const float m4 = rank >= 4 ? 1.f : 0.f, m8 = rank >= 8 ? 1.f : 0.f;
-        float acc = 0.f;
-        for (int k0 = kbeg; k0 < kend; k0 += 32) {
-            // row-end bits of entries k0 .. k0+31
-            const uint32_t lo = __builtin_amdgcn_readfirstlane(rowend[k0 >> 5]);
-            const uint32_t hi = __builtin_amdgcn_readfirstlane(rowend[(k0 >> 5) + 1]);
-            uint32_t window = (uint32_t)((((uint64_t)hi << 32) | lo) >> (k0 & 31));
-            const int kstop = min(k0 + 32, kend);
-            if (kstop - k0 < 32) window &= (1u << (kstop - k0)) - 1u;
-            for (int k = k0; k < kstop; k += 4, window >>= 4) {
-                uint4 e1[4];
-                float pv[4], cu[4];
+// nonzeros).  Every outer entry is a 16-byte broadcast read, which costs the LDS
+// four times what a conflict-free gather of p does: with CB chunks per pass it is
+// read 1/CB as often.
+// ATOMIC: the wave's share may begin and end inside an outer row.  kfirst is the
+// first row end of the share if that row began in the previous wave's share (-1
+// otherwise), force_end says that the share ends inside a row; the sums of both
+// rows are added to y atomically, like those of inner rows cut into several runs.
+template <int CB, int NSTEPS, bool WEIGHTED, int EK, bool ATOMIC>
+__device__ __forceinline__ void xmv_chunks(const uint4* ent1, const uint4* ent2c, const uint32_t* rowend,
+                                           const char* pbytes, char* ybytes, int kbeg, int kend,
+                                           int kfirst, bool force_end, float ke_c, const float* pc) {
+    static_assert(CB == 1 || CB == 2 || CB == 4, "one, two or four chunks per pass");
+    uint32_t ip4[CB], jp4[CB], rank[CB];
+    bool last[CB], longrow[CB];
+    float el2[CB], lw2[CB], acc[CB];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) e1[u] = ent1[k + u];
+    for (int b = 0; b < CB; ++b) {
+        const uint4 e2 = ent2c[64 * b];
+        ip4[b] = e2.x & 0xfffffu;
+        jp4[b] = e2.y;
+        rank[b] = (e2.x >> 20) & 0xffu;
+        last[b] = (e2.x >> 31) != 0u;
+        longrow[b] = ((e2.x >> 30) & 1u) != 0u;
+        el2[b] = __uint_as_float(e2.z);
+        lw2[b] = __uint_as_float(e2.w);
+        acc[b] = 0.f;
+    }
+    // multipliers of the shift-and-add steps: 1 where the lane DIST places lower belongs
+    // to the same run.  Short rows end every few entries: kept in registers; with long
+    // rows (NSTEPS > 2) the ends are rare and the masks are made when needed.
+    float m1[CB], m2[CB];
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    pv[u] = *reinterpret_cast<const float*>(pbytes + (e1[u].x + jp4));
+    for (int b = 0; b < CB; ++b) {
+        m1[b] = rank[b] >= 1 ? 1.f : 0.f;
+        m2[b] = rank[b] >= 2 ? 1.f : 0.f;
+    }
+    for (int k0 = kbeg; k0 < kend; k0 += 32) {
+        // row-end bits of entries k0 .. k0+31
+        const uint32_t lo = __builtin_amdgcn_readfirstlane(rowend[k0 >> 5]);
+        const uint32_t hi = __builtin_amdgcn_readfirstlane(rowend[(k0 >> 5) + 1]);
+        uint32_t window = (uint32_t)((((uint64_t)hi << 32) | lo) >> (k0 & 31));
+        const int kstop = min(k0 + 32, kend);
+        if (kstop - k0 < 32) window &= (1u << (kstop - k0)) - 1u;
+        if (ATOMIC && force_end && kstop == kend) window |= 1u << (kend - 1 - k0);
+        for (int k = k0; k < kstop; k += 4, window >>= 4) {
+            uint4 e1[4];
+            float pv[4][CB], cu[4][CB];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < 4; ++u) e1[u] = ent1[k + u];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int b = 0; b < CB; ++b)
+                    pv[u][b] = *reinterpret_cast<const float*>(pbytes + (e1[u].x + jp4[b]));
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+#pragma unroll
+                for (int b = 0; b < CB; ++b) {
                     if (EK == MGK_EK_SE) {
-                        const float d = el2 - __uint_as_float(e1[u].y);
+                        const float d = el2[b] - __uint_as_float(e1[u].y);
                         float t;
-                        if (WEIGHTED) t = __builtin_fmaf(-d, d, lw2 + __uint_as_float(e1[u].z));
-                        else t = __builtin_fmaf(-d, d, lw2);  // lw2: 0, or -inf on idle lanes
-                        cu[u] = __builtin_amdgcn_exp2f(t);
+                        if (WEIGHTED) t = __builtin_fmaf(-d, d, lw2[b] + __uint_as_float(e1[u].z));
+                        else t = __builtin_fmaf(-d, d, lw2[b]);  // lw2: 0, or -inf on idle lanes
+                        cu[u][b] = __builtin_amdgcn_exp2f(t);
                     } else if (EK == MGK_EK_POLY) {
-                        cu[u] = mgk_poly_kernel(el2 - __uint_as_float(e1[u].y), pc);
-                        if (WEIGHTED) cu[u] *= __uint_as_float(e1[u].z);     // A_ij
+                        cu[u][b] = mgk_poly_kernel(el2[b] - __uint_as_float(e1[u].y), pc);
+                        if (WEIGHTED) cu[u][b] *= __uint_as_float(e1[u].z);     // A_ij
                     } else {
-                        cu[u] = WEIGHTED ? __uint_as_float(e1[u].y) : 1.f;  // A_ij
+                        cu[u][b] = WEIGHTED ? __uint_as_float(e1[u].y) : 1.f;  // A_ij
                     }
                 }
+            }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    acc = __builtin_fmaf(cu[u], pv[u], acc);
-                    if ((window >> u) & 1u) {   // end of outer row i: sum over each inner row
-                        if (EK == MGK_EK_CONST) acc *= ke_c * el2;  // el2 = A'_i'j' (0 on idle lanes)
-                        if (EK == MGK_EK_POLY) acc *= lw2;           // lw2 = A'_i'j' (0 on idle lanes)
-                        if (NSTEPS > 0) acc = shr_fmac<1>(acc, m1);
-                        if (NSTEPS > 1) acc = shr_fmac<2>(acc, m2);
-                        if (NSTEPS > 2) acc = shr_fmac<4>(acc, m4);
-                        if (NSTEPS > 3) acc = shr_fmac<8>(acc, m8);
-                        if (last) {
-                            float* dst = reinterpret_cast<float*>(ybytes + (e1[u].w + ip4));
-                            if (ATOMIC && longrow)   // several runs add up to one y_ii'
-                                __hip_atomic_fetch_add(dst, acc, __ATOMIC_RELAXED,
+            for (int u = 0; u < 4; ++u) {
+#pragma unroll
+                for (int b = 0; b < CB; ++b) acc[b] = __builtin_fmaf(cu[u][b], pv[u][b], acc[b]);
+                if ((window >> u) & 1u) {   // end of outer row i: sum over each inner row
+                    // wave-uniform: this wave holds only a part of outer row i
+                    const bool part = ATOMIC && (k + u == kfirst || (force_end && k + u == kend - 1));
+#pragma unroll
+                    for (int b = 0; b < CB; ++b) {
+                        if (EK == MGK_EK_CONST) acc[b] *= ke_c * el2[b];  // el2 = A'_i'j' (0 on idle lanes)
+                        if (EK == MGK_EK_POLY) acc[b] *= lw2[b];           // lw2 = A'_i'j' (0 on idle lanes)
+                    }
+                    if constexpr (CB == 1) {
+                        if (NSTEPS > 0) acc[0] = shr_fmac<1>(acc[0], m1[0]);
+                        if (NSTEPS > 1) acc[0] = shr_fmac<2>(acc[0], m2[0]);
+                        if (NSTEPS > 2) acc[0] = shr_fmac<4>(acc[0], rank[0] >= 4 ? 1.f : 0.f);
+                        if (NSTEPS > 3) acc[0] = shr_fmac<8>(acc[0], rank[0] >= 8 ? 1.f : 0.f);
+                    } else {
+#pragma unroll
+                        for (int b = 0; b < CB; b += 2) {
+                            if (NSTEPS > 0) shr_fmac_pair<1>(acc[b], acc[b + 1], m1[b], m1[b + 1]);
+                            if (NSTEPS > 1) shr_fmac_pair<2>(acc[b], acc[b + 1], m2[b], m2[b + 1]);
+                            if (NSTEPS > 2) shr_fmac_pair<4>(acc[b], acc[b + 1], rank[b] >= 4 ? 1.f : 0.f,
+                                                             rank[b + 1] >= 4 ? 1.f : 0.f);
+                            if (NSTEPS > 3) shr_fmac_pair<8>(acc[b], acc[b + 1], rank[b] >= 8 ? 1.f : 0.f,
+                                                             rank[b + 1] >= 8 ? 1.f : 0.f);
+                        }
+                    }
+#pragma unroll
+                    for (int b = 0; b < CB; ++b) {
+                        if (last[b]) {
+                            float* dst = reinterpret_cast<float*>(ybytes + (e1[u].w + ip4[b]));
+                            if (ATOMIC && (longrow[b] || part))   // several sums add up to one y_ii'
+                                __hip_atomic_fetch_add(dst, acc[b], __ATOMIC_RELAXED,
                                                        __HIP_MEMORY_SCOPE_WORKGROUP);
                             else
-                                *dst = acc;
+                                *dst = acc[b];
                         }
-                        acc = 0.f;
+                        acc[b] = 0.f;
                     }
                 }
             }
         }
     }
+}
+
+// The whole inner lane layout (len2 slots, a multiple of 64): four chunks per pass,
+// then two, then one for what is left.
+template <int NSTEPS, bool WEIGHTED, int EK, bool ATOMIC>
+__device__ __forceinline__ void xmv_pass(const uint4* ent1, const uint4* ent2, const uint32_t* rowend,
+                                         const char* pbytes, char* ybytes, int len2, int kbeg,
+                                         int kend, int kfirst, bool force_end, float ke_c,
+                                         const float* pc, int lane) {
+    // A kernel's register count is that of its widest path: four chunks per pass only in
+    // the kernels for graphs with long rows, whose inner layouts have many chunks.
+    constexpr int CBMAX = ATOMIC ? 4 : 2;
+    int c = 0;
+    if constexpr (CBMAX >= 4)
+        for (; c + 256 <= len2; c += 256)
+            xmv_chunks<4, NSTEPS, WEIGHTED, EK, ATOMIC>(ent1, ent2 + c + lane, rowend, pbytes, ybytes,
+                                                        kbeg, kend, kfirst, force_end, ke_c, pc);
+    if constexpr (CBMAX >= 2)
+        for (; c + 128 <= len2; c += 128)
+            xmv_chunks<2, NSTEPS, WEIGHTED, EK, ATOMIC>(ent1, ent2 + c + lane, rowend, pbytes, ybytes,
+                                                        kbeg, kend, kfirst, force_end, ke_c, pc);
+    for (; c < len2; c += 64)
+        xmv_chunks<1, NSTEPS, WEIGHTED, EK, ATOMIC>(ent1, ent2 + c + lane, rowend, pbytes, ybytes,
+                                                    kbeg, kend, kfirst, force_end, ke_c, pc);
 }
 
 // ATOMIC: the inner graph has rows longer than 16 nonzeros; the runs of those rows are
@@ -271,10 +342,26 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
     __syncthreads();  // entries, row-end bits and p are complete
 
     // ---- this wave's share of the outer nonzeros: whole rows, about z1 / WAVES
-    int kbeg = 0, kend = z1;
+    //      (ATOMIC: exactly that many, rounded up to the groups of four the XMV reads;
+    //      the rows cut by a share boundary are completed with atomic adds)
+    int kbeg = 0, kend = z1, kfirst = -1;
+    bool force_end = false;
     if (WAVES > 1) {
-        if (wave > 0) kbeg = next_set_bit(rowend, L.rowend_words, wave * L.share - 1, z1 - 1) + 1;
-        if (wave < WAVES - 1) kend = next_set_bit(rowend, L.rowend_words, (wave + 1) * L.share - 1, z1 - 1) + 1;
+        if (ATOMIC) {
+            const int share4 = (L.share + 3) & ~3;
+            kbeg = min(wave * share4, z1);
+            kend = min(kbeg + share4, z1);
+            if (kbeg < kend) {
+                if (kbeg > 0 && !((rowend[(kbeg - 1) >> 5] >> ((kbeg - 1) & 31)) & 1u))
+                    kfirst = next_set_bit(rowend, L.rowend_words, kbeg, z1);
+                force_end = !((rowend[(kend - 1) >> 5] >> ((kend - 1) & 31)) & 1u);
+            }
+            kfirst = __builtin_amdgcn_readfirstlane(kfirst);
+            force_end = __builtin_amdgcn_readfirstlane((int)force_end) != 0;
+        } else {
+            if (wave > 0) kbeg = next_set_bit(rowend, L.rowend_words, wave * L.share - 1, z1 - 1) + 1;
+            if (wave < WAVES - 1) kend = next_set_bit(rowend, L.rowend_words, (wave + 1) * L.share - 1, z1 - 1) + 1;
+        }
         kbeg = __builtin_amdgcn_readfirstlane(min(kbeg, z1));
         kend = __builtin_amdgcn_readfirstlane(min(kend, z1));
     }
@@ -290,11 +377,11 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
     while (it < max_iter) {
         // ---- XMV (Alg. 2): y_ii' = sum_{j,j'} A_ij A'_i'j' kappa_e(E_ij,E'_i'j') p_jj'
         switch (nsteps) {
-            case 0: xmv_pass<0, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, ke_c, prm.poly_c, lane); break;
-            case 1: xmv_pass<1, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, ke_c, prm.poly_c, lane); break;
-            case 2: xmv_pass<2, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, ke_c, prm.poly_c, lane); break;
-            case 3: xmv_pass<3, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, ke_c, prm.poly_c, lane); break;
-            default: xmv_pass<4, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, ke_c, prm.poly_c, lane); break;
+            case 0: xmv_pass<0, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane); break;
+            case 1: xmv_pass<1, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane); break;
+            case 2: xmv_pass<2, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane); break;
+            case 3: xmv_pass<3, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane); break;
+            default: xmv_pass<4, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane); break;
         }
         __syncthreads();
 

@@ -97,6 +97,17 @@ __device__ __forceinline__ float shr_fmac(float acc, float m) {
     return acc;
 }
 
+// The same step on two accumulators at once: the second instruction fills one of the
+// wait states of the first one's successor.
+template <int DIST>
+__device__ __forceinline__ void shr_fmac_pair(float& acc0, float& acc1, float m0, float m1) {
+    asm volatile("s_nop 1\n\t"
+                 "v_fmac_f32_dpp %0, %0, %2 row_shr:%4 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                 "v_fmac_f32_dpp %1, %1, %3 row_shr:%4 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+                 : "+v"(acc0), "+v"(acc1)
+                 : "v"(m0), "v"(m1), "n"(DIST));
+}
+
 }  // namespace
 
 #endif
