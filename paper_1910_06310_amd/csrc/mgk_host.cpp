@@ -170,7 +170,7 @@ MgkParams make_params(const mgk_ctx* ctx, const mgk_batch* X) {
 // Launch shapes of the on-chip solver: `waves` wavefronts per pair, `ept`
 // vector elements per thread; a pair fits when n n' <= waves * 64 * ept.
 struct SmallConfig { int waves, ept; };
-const SmallConfig kAutoConfigs[] = {{1, 4}, {2, 4}, {4, 4}, {4, 6}, {4, 8}, {4, 10}, {4, 12}, {4, 14}, {4, 16}, {8, 12}, {8, 16}, {16, 12}, {16, 16}};
+const SmallConfig kAutoConfigs[] = {{1, 4}, {2, 4}, {4, 4}, {4, 6}, {4, 8}, {4, 10}, {4, 12}, {4, 14}, {4, 16}, {8, 12}, {8, 16}, {16, 10}, {16, 12}, {16, 16}};
 const int kEpts[] = {4, 8, 12, 16};
 
 // Orientation, launch shape and cost of one pair for the on-chip solver.  The
@@ -200,7 +200,7 @@ int64_t regs_cost(const MgkGraphDesc& o, const MgkGraphDesc& i, int waves) {
     const int64_t ept = std::max<int64_t>(1, (N + waves * 64 - 1) / (waves * 64));
     // register blocks that keep four wavefronts per SIMD resident
     if (ept > MGK_REGS_MAX_EPT) return -1;
-    return (int64_t)o.nnz * (1 + 2 * chunks) + (int64_t)o.n * (1 + 4 * chunks) +
+    return (int64_t)o.nnz * (2 * chunks) + (int64_t)o.n * (1 + 4 * chunks) +
            (int64_t)waves * (8 * ept + 45);
 }
 

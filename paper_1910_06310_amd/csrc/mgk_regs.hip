@@ -177,12 +177,12 @@ struct InnerLanes {
 
 // Gathered reads of p for outer nonzeros K0 .. K0+3 (lanes past the wave's run hold
 // offset 0, so the reads stay inside p).
-template <int K0, int C>
-__device__ __forceinline__ void gather4(float (&pv)[4][C], const InnerLanes<C>& in, uint32_t v_poff,
-                                        const char* pbytes) {
+template <int K0, int C, int SMAX>
+__device__ __forceinline__ void gather4(float (&pv)[4][C], const InnerLanes<C>& in,
+                                        const uint32_t (&s_poff)[SMAX], const char* pbytes) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-        const uint32_t po = lane_value(v_poff, K0 + u);
+        const uint32_t po = s_poff[K0 + u];
 #pragma unroll
         for (int c = 0; c < C; ++c)
             pv[u][c] = *reinterpret_cast<const float*>(pbytes + (po + in.jp[c]));
@@ -245,14 +245,14 @@ __device__ __forceinline__ void use4(const float (&kap)[C][SMAX], const InnerLan
 template <int K0, int SMAX, int C>
 __device__ __forceinline__ void xmv_steps(const float (&kap)[C][SMAX], const InnerLanes<C>& in,
                                           float (&acc)[C], const float (&pv)[4][C], int S,
-                                          uint64_t rowmask, uint32_t v_poff, uint32_t v_yoff,
-                                          const char* pbytes, char* ybytes) {
+                                          uint64_t rowmask, const uint32_t (&s_poff)[SMAX],
+                                          uint32_t v_yoff, const char* pbytes, char* ybytes) {
     if constexpr (K0 + 4 < SMAX) {
         if (K0 + 4 < S) {   // wave-uniform
             float nx[4][C];
-            gather4<K0 + 4, C>(nx, in, v_poff, pbytes);
+            gather4<K0 + 4, C, SMAX>(nx, in, s_poff, pbytes);
             use4<K0, SMAX, C>(kap, in, acc, pv, rowmask, v_yoff, ybytes);
-            xmv_steps<K0 + 4, SMAX, C>(kap, in, acc, nx, S, rowmask, v_poff, v_yoff, pbytes, ybytes);
+            xmv_steps<K0 + 4, SMAX, C>(kap, in, acc, nx, S, rowmask, s_poff, v_yoff, pbytes, ybytes);
             return;
         }
     }
@@ -425,6 +425,12 @@ __global__ __launch_bounds__(W * 64) void mgk_pcg_regs(MgkBatchDev X, MgkBatchDe
 
     const char* pbytes = reinterpret_cast<const char*>(p);
     char* ybytes = reinterpret_cast<char*>(y);
+    // byte offset of row j of p for each of the wave's outer nonzeros, in scalar
+    // registers for the whole solve (entries past the run read row 0); the offsets of the
+    // rows of y, needed at row ends only, stay in lanes: the scalar file does not hold both
+    uint32_t s_poff[SMAX];
+#pragma unroll
+    for (int k = 0; k < SMAX; ++k) s_poff[k] = lane_value(v_poff, k);
 
     int it = 0;
     int flag = 1;
@@ -434,8 +440,8 @@ __global__ __launch_bounds__(W * 64) void mgk_pcg_regs(MgkBatchDev X, MgkBatchDe
             float acc[C], pv[4][C];
 #pragma unroll
             for (int c = 0; c < C; ++c) acc[c] = 0.f;
-            gather4<0, C>(pv, in, v_poff, pbytes);
-            xmv_steps<0, SMAX, C>(kap, in, acc, pv, S, rowmask, v_poff, v_yoff, pbytes, ybytes);
+            gather4<0, C, SMAX>(pv, in, s_poff, pbytes);
+            xmv_steps<0, SMAX, C>(kap, in, acc, pv, S, rowmask, s_poff, v_yoff, pbytes, ybytes);
         }
         __syncthreads();
 

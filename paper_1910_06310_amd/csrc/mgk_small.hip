@@ -529,6 +529,10 @@ hipError_t MGK_CAT(mgk_launch_small_w, MGK_SMALL_WAVES)(
             default: break;
         }
     }
+    if constexpr (W == 16) {  // 16 x 64 x 10 elements hold a pair of 96-vertex graphs
+        if (ept == 10)
+            return launch_we<W, 10>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+    }
     switch (ept) {
         case 4: return launch_we<W, 4>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
         case 12: return launch_we<W, 12>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
