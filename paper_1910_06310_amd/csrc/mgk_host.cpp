@@ -130,6 +130,41 @@ size_t append_bytes(std::vector<char>& blob, const std::vector<T>& v) {
     return off;
 }
 
+// Contiguous division of the rows of a graph among `waves` wavefronts for the
+// register-resident solver: bounds[w] .. bounds[w+1] are wavefront w's rows.  A row of
+// deg nonzeros costs about 4 deg + 9 wave instructions of an XMV (two inner chunks: an
+// address add and a multiply-add per nonzero and chunk, the row sums and the store at its
+// end); the largest cost of a wavefront is made as small as whole rows allow (bisection
+// on the bound, rows filled in greedily).  Returns the most nonzeros a wavefront gets.
+int balanced_split(const std::vector<int32_t>& deg, int n, int waves, int32_t* bounds) {
+    auto row_cost = [&](int i) { return (int64_t)4 * deg[i] + 9; };
+    int64_t lo = 0, hi = 0;
+    for (int i = 0; i < n; ++i) { lo = std::max(lo, row_cost(i)); hi += row_cost(i); }
+    auto parts_needed = [&](int64_t bound) {
+        int parts = 1;
+        int64_t cur = 0;
+        for (int i = 0; i < n; ++i) {
+            if (cur + row_cost(i) > bound) { ++parts; cur = row_cost(i); } else cur += row_cost(i);
+        }
+        return parts;
+    };
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) / 2;
+        if (parts_needed(mid) <= waves) hi = mid; else lo = mid + 1;
+    }
+    int w = 0, longest = 0, run = 0;
+    int64_t cur = 0;
+    bounds[0] = 0;
+    for (int i = 0; i < n; ++i) {
+        if (cur + row_cost(i) > lo) { bounds[++w] = i; cur = 0; run = 0; }
+        cur += row_cost(i);
+        run += deg[i];
+        longest = std::max(longest, run);
+    }
+    while (w < waves) bounds[++w] = n;
+    return longest;
+}
+
 // kernels over label attributes are built into the register-resident and the
 // global-memory solver, not into the streaming on-chip one
 bool streaming_ok(const mgk_ctx* ctx) {
@@ -194,8 +229,8 @@ int64_t regs_cost(const MgkGraphDesc& o, const MgkGraphDesc& i, int waves) {
     const int chunks = std::max(1, i.lane_len / 64);
     if (chunks > MGK_REGS_MAX_CHUNKS || i.max_deg > MGK_REGS_MAX_DEG) return -1;
     const int smax = waves == 4 ? MGK_REGS_SMAX_W4 : MGK_REGS_SMAX_W8;
-    const int share = std::max((o.nnz + waves - 1) / waves, 1);
-    if (share + std::max(o.max_deg, 1) - 1 > smax) return -1;
+    const int run = waves == 4 ? (o.regs_runs & 0xffff) : (int)((uint32_t)o.regs_runs >> 16);
+    if (run > smax) return -1;
     const int64_t N = (int64_t)o.n * i.n;
     const int64_t ept = std::max<int64_t>(1, (N + waves * 64 - 1) / (waves * 64));
     // register blocks that keep four wavefronts per SIMD resident
@@ -776,6 +811,7 @@ mgk_status mgk_load_graphs_attr(mgk_ctx* ctx, int32_t n_graphs, const int64_t* v
     B->perm.resize((size_t)tot_v);
     std::vector<int32_t> vlabel((size_t)tot_v), rowptr((size_t)tot_v), lanepos((size_t)tot_v), iperm((size_t)tot_v), trow_ptr, tile_graph;
     std::vector<MgkEntry> list_outer, list_inner;   // nonzero lists for the register-resident solver
+    std::vector<int32_t> regs_split;                // its division of every graph's rows among wavefronts
     list_outer.reserve((size_t)(2 * tot_e));
     // label attributes in the order of the two lists, attribute-major; filled after the loop
     // (the plane stride is the batch total): (position, edge) pairs collected meanwhile
@@ -964,7 +1000,13 @@ mgk_status mgk_load_graphs_attr(mgk_ctx* ctx, int32_t n_graphs, const int64_t* v
         gd.max_deg = max_deg;
         gd.lane_len = (slot + 63) & ~63;
         gd.loff = (int32_t)lanes_total;
-        gd.reserved = 0;
+        {
+            int32_t bounds[MGK_REGS_SPLIT_STRIDE];
+            const int run4 = balanced_split(deg, n, 4, bounds);
+            const int run8 = balanced_split(deg, n, 8, bounds + MGK_REGS_SPLIT_W8);
+            regs_split.insert(regs_split.end(), bounds, bounds + MGK_REGS_SPLIT_STRIDE);
+            gd.regs_runs = std::min(run4, 0xffff) | (std::min(run8, 0xffff) << 16);
+        }
         lanes_total += gd.lane_len;
         if (lanes_total >= (int64_t)1 << 31) return fail(ctx, MGK_ELIMIT, "batch too large for 32-bit offsets");
         // the same nonzeros as plain lists: CSR order (columns ascending inside a row, which is
@@ -1017,6 +1059,7 @@ mgk_status mgk_load_graphs_attr(mgk_ctx* ctx, int32_t n_graphs, const int64_t* v
     const size_t o_ip = append_bytes(blob, iperm);
     const size_t o_lo = append_bytes(blob, list_outer);
     const size_t o_li = append_bytes(blob, list_inner);
+    const size_t o_sp = append_bytes(blob, regs_split);
     std::vector<float> attr_outer, attr_inner;
     {
         attr_outer.assign((size_t)D * B->w.size(), 0.f);
@@ -1059,6 +1102,7 @@ mgk_status mgk_load_graphs_attr(mgk_ctx* ctx, int32_t n_graphs, const int64_t* v
     B->dev.iperm = reinterpret_cast<const int32_t*>(base + o_ip);
     B->dev.list_outer = reinterpret_cast<const MgkEntry*>(base + o_lo);
     B->dev.list_inner = reinterpret_cast<const MgkEntry*>(base + o_li);
+    B->dev.regs_split = reinterpret_cast<const int32_t*>(base + o_sp);
     B->dev.attr_outer = reinterpret_cast<const float*>(base + o_ao);
     B->dev.attr_inner = reinterpret_cast<const float*>(base + o_ai);
 

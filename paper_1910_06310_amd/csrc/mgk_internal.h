@@ -25,7 +25,8 @@ struct MgkGraphDesc {
     int32_t max_deg;      // largest number of nonzeros in a row
     int32_t lane_len;     // lane slots of the graph as inner operand (multiple of 64)
     int32_t loff;         // first lane slot of the graph in batch-wide expanded inner lists
-    int32_t reserved;
+    int32_t regs_runs;    // longest run of outer nonzeros of one wavefront under regs_split:
+                          // 4 wavefronts in bits 0-15, 8 wavefronts in bits 16-31
 };
 
 // Lane layout of a graph used as the inner operand of the on-chip XMV: the
@@ -59,6 +60,7 @@ struct MgkBatchDev {
     const int32_t* iperm;    // per vertex: original id of the stored vertex
     const struct MgkEntry* list_outer;  // per nonzero (CSR order, index zoff + k), see MgkEntry
     const struct MgkEntry* list_inner;  // per lane slot (index loff + slot)
+    const int32_t* regs_split;  // per graph MGK_REGS_SPLIT_STRIDE row boundaries, see below
     const float* attr_outer;  // label attribute a of nonzero k (CSR order): attr_outer[a * nnz_total + zoff + k]
     const float* attr_inner;  // the same in lane order: attr_inner[a * lanes_total + loff + slot], 0 on idle slots
     int32_t n_graphs, n_tiles_total, nnz_total, lanes_total;
@@ -220,6 +222,13 @@ struct alignas(16) MgkEntry {
 //   list_inner[loff + slot], lane layout: {row | rank in run << 20 | row longer
 //     than a lane group << 30 | last of run << 31, col, label bits, weight bits
 //     (0.0f for an idle slot)}
+
+// Outer rows of a graph divided among the wavefronts of the register-resident solver
+// (whole rows, contiguous, the most loaded wavefront as light as possible; written at
+// load): regs_split[g * MGK_REGS_SPLIT_STRIDE + k], k = 0..4: wavefront w of 4 owns
+// rows [b[w], b[w+1]); k = 5..13: the same for 8 wavefronts.
+#define MGK_REGS_SPLIT_STRIDE 14
+#define MGK_REGS_SPLIT_W8 5
 
 struct MgkExpanded {
     const MgkEntry* outer;

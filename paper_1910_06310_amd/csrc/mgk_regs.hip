@@ -300,21 +300,10 @@ __global__ __launch_bounds__(W * 64) void mgk_pcg_regs(MgkBatchDev X, MgkBatchDe
 #pragma unroll
     for (int m = 0; m < EPT; ++m) y[tid + m * NT] = 0.f;
 
-    // ---- this wave's outer rows: whole rows, about z1 / W nonzeros ----------------
-    // first row whose first nonzero is at or after `target` (rowptr is non-decreasing)
-    const int share = max((z1 + W - 1) / W, 1);
-    int rbeg = 0, rend = n1;
-    {
-        int cb = 0, ce = 0;
-        for (int r0 = 0; r0 < n1; r0 += 64) {
-            const int r = r0 + lane;
-            const int rp = r < n1 ? X.rowptr[g1.voff + r] : 0x7fffffff;
-            cb += __popcll(__ballot(rp < wave * share));
-            ce += __popcll(__ballot(rp < (wave + 1) * share));
-        }
-        if (wave > 0) rbeg = cb;
-        if (wave < W - 1) rend = ce;
-    }
+    // ---- this wave's outer rows: whole rows, divided at load so that the most loaded
+    //      wavefront is as light as possible
+    const int32_t* split = X.regs_split + (int64_t)job.g1 * MGK_REGS_SPLIT_STRIDE + (W == 8 ? MGK_REGS_SPLIT_W8 : 0);
+    const int rbeg = split[wave], rend = split[wave + 1];
     int kbeg = rbeg < n1 ? X.rowptr[g1.voff + rbeg] : z1;
     int kend = rend < n1 ? X.rowptr[g1.voff + rend] : z1;
     kbeg = __builtin_amdgcn_readfirstlane(kbeg);
