@@ -318,6 +318,7 @@ def main() -> int:
             "bound": "alu",
             "kernel": ("mgk_pcg_regs" if wl in ("config4", "config1") and args.product_cache and not args.waves
                        else "mgk_pcg_small" if wl in ("config4", "config1", "nws", "ba")
+                       else "mgk_pcg_regs / mgk_pcg_small" if wl == "config0"
                        else "mgk_large_xmv_rows_kernel / mgk_large_xmv_dense_kernel (+ vector kernels)"),
             "achieved": achieved_tflops,
             "peak": FP32_VECTOR_PEAK_TFLOPS,
