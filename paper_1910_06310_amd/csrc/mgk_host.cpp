@@ -463,13 +463,14 @@ mgk_status solve_large(mgk_ctx* ctx, const mgk_batch* A, const mgk_batch* Bb, in
     if (n_pairs == 0) return MGK_OK;
     int64_t total = 0;
     int max_npad = 0, max_iter = 0, xmv_blocks = 1;
-    int max_n1 = 1, max_n2 = 1, max_deg1 = 1, max_chunks = 1;
+    int max_n1 = 1, max_n2 = 1, max_deg1 = 1, max_chunks = 1, min_chunks = 1 << 30;
     constexpr int CPB = MGK_LARGE_WAVES * MGK_LARGE_CHUNKS_PER_WAVE;
     for (MgkLargePair& P : pairs) {
         max_n1 = std::max(max_n1, P.n1);
         max_n2 = std::max(max_n2, P.n2);
         max_deg1 = std::max(max_deg1, A->graphs[P.g1].max_deg);
         max_chunks = std::max(max_chunks, Bb->graphs[P.g2].lane_len / 64);
+        min_chunks = std::min(min_chunks, Bb->graphs[P.g2].lane_len / 64);
         P.vec = total;
         total += 5 * (int64_t)P.npad;
         max_npad = std::max(max_npad, P.npad);
@@ -487,7 +488,7 @@ mgk_status solve_large(mgk_ctx* ctx, const mgk_batch* A, const mgk_batch* Bb, in
     // CU); when the rows of p are so long that the neighbours of one outer row need more,
     // one workgroup of 16 wavefronts per CU with up to 120 KB.
     constexpr int kRowsLdsSmall = 60 * 1024, kRowsLdsLarge = 120 * 1024;
-    int rows_threads = 0, rows_lds_bytes = 0;
+    int rows_threads = 0, rows_lds_bytes = 0, rows_chunks = 1;
     if (!dense && ctx->row_staging && (int64_t)max_n2 * 4 <= kRowsLdsLarge) {
         const int64_t need = (int64_t)max_deg1 * max_n2 * 4;
         const bool large = need > kRowsLdsSmall;
@@ -496,6 +497,12 @@ mgk_status solve_large(mgk_ctx* ctx, const mgk_batch* A, const mgk_batch* Bb, in
         rows_lds_bytes = rows * max_n2 * 4;   // + the batch's outer entries and attributes, added by the launcher
         rows_threads = 64 * std::max(1, std::min(large ? 16 : 8, (max_chunks + 1) / 2));
         xmv_blocks = max_n1;
+        // Chunks of the inner layout per pass of a wavefront: every outer entry read from LDS
+        // then serves that many gathers.  Four need about 110 registers per lane, which only
+        // the single large workgroup per CU affords; two where every wavefront still gets a
+        // pass on the smallest pair.
+        const int waves = rows_threads / 64;
+        rows_chunks = large && min_chunks >= 4 * waves ? 4 : min_chunks >= 2 * waves ? 2 : 1;
     }
     const int vec_blocks = std::max(1, std::min(2048, (max_npad + 1023) / 1024));
     mgk_status st;
@@ -551,7 +558,7 @@ mgk_status solve_large(mgk_ctx* ctx, const mgk_batch* A, const mgk_batch* Bb, in
         e = mgk_launch_large_iteration(A->dev, Bb->dev, ex[0], ex[1], dpairs, dstate, vec, prm, weighted,
                                        n_pairs, xmv_blocks, vec_blocks, dactive, it == 0,
                                        dense ? &dt[0] : nullptr, dense ? &dt[1] : nullptr, rows_threads,
-                                       rows_lds_bytes, stream);
+                                       rows_lds_bytes, rows_chunks, stream);
         if (e != hipSuccess) return fail(ctx, MGK_EDEVICE, "iteration launch failed: %s", hipGetErrorString(e));
         if ((it + 1) % check_every == 0 || it + 1 == max_iter) {
             MGK_HIP(ctx, hipMemcpyAsync(ctx->active_host, dactive, sizeof(int), hipMemcpyDeviceToHost, stream));

@@ -254,7 +254,151 @@ __global__ __launch_bounds__(kThreads) void mgk_large_xmv_kernel(
 // evaluation and row sums as in mgk_large_xmv_kernel; the waves of the workgroup take the
 // 64-lane chunks of the inner graph in turn.  For the edge kernels over label attributes
 // the batch's outer attributes are staged (prescaled) next to the outer entries.
-template <bool WEIGHTED, int EK>
+// This lane's inner entries of chunks c0 .. c0 + CB - 1 (idle entries past `chunks`).
+template <int CB>
+__device__ __forceinline__ void rows_load(uint4 (&e2v)[CB], const uint4* inner, int c0, int chunks, int lane) {
+#pragma unroll
+    for (int b = 0; b < CB; ++b)
+        e2v[b] = c0 + b < chunks ? inner[(c0 + b) * 64 + lane] : make_uint4(0u, 0u, 0u, 0u);
+}
+
+// All passes of one wave over a staged batch, CB chunks each; the inner entries of the
+// next pass are in flight during the products of this one.
+template <int CB, bool WEIGHTED, int EK, typename PASS>
+__device__ __forceinline__ void rows_sweep(const uint4* inner, int wave, int nwaves, int chunks, int lane,
+                                           const PASS& pass) {
+    uint4 nxt[CB];
+    rows_load<CB>(nxt, inner, wave * CB, chunks, lane);
+    for (int c0 = wave * CB; c0 < chunks; c0 += nwaves * CB) {
+        uint4 cur[CB];
+#pragma unroll
+        for (int b = 0; b < CB; ++b) cur[b] = nxt[b];
+        if (c0 + nwaves * CB < chunks) rows_load<CB>(nxt, inner, c0 + nwaves * CB, chunks, lane);
+        pass(cur, c0);
+    }
+}
+
+// The products of one pass: this wave's CB chunks of the inner lane layout (chunk c0 + b,
+// idle past `chunks`) against the nb outer entries of the staged batch.  The labels and
+// log-weights of the batch sit in LDS as plain arrays padded to a multiple of four with
+// entries whose kernel value is exactly 0, and are read four at a time: one 16-byte
+// broadcast read serves 4 * CB products, where a read of a whole 16-byte entry per product
+// occupied the LDS four times as long as the gather of p it accompanied.
+template <int CB, bool WEIGHTED, int EK>
+__device__ __forceinline__ void rows_pass(const MgkBatchDev& Y, const MgkGraphDesc& g2,
+                                          const MgkLargePair& P, const MgkParams& prm,
+                                          const uint4 (&e2v)[CB], int c0, int chunks, int lane,
+                                          const float* prow, const float* olab, const float* olw,
+                                          const float* oattr, int nb, int n2, float* yrow,
+                                          bool first_batch) {
+    constexpr bool ATTR = EK == MGK_EK_KRON_SE || EK == MGK_EK_RCONV_SE;
+    const int D = prm.label_dim;
+    int ip[CB];
+    uint32_t rank[CB];
+    bool last[CB];
+    float el2[CB], lw2[CB], acc[CB];
+    const char* pb[CB];
+    float e2a[CB][MGK_MAX_LABEL_DIM];   // this lane's attributes, prescaled
+#pragma unroll
+    for (int b = 0; b < CB; ++b) {
+        const bool on = c0 + b < chunks;
+        const uint4 e2 = e2v[b];
+        ip[b] = (int)e2.x;
+        pb[b] = reinterpret_cast<const char*>(prow) + (e2.y & 0xffffffu) * 4u;
+        rank[b] = (e2.y >> 24) & 0xfu;
+        last[b] = (e2.y >> 31) != 0u;
+        el2[b] = __uint_as_float(e2.z);
+        lw2[b] = __uint_as_float(e2.w);
+        acc[b] = 0.f;
+#pragma unroll
+        for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a) {
+            e2a[b][a] = 0.f;
+            if (ATTR && on && a < D)
+                e2a[b][a] = Y.attr_inner[(int64_t)a * Y.lanes_total + g2.loff + (c0 + b) * 64 + lane] *
+                            prm.attr_scale[EK == MGK_EK_RCONV_SE ? 0 : a];
+        }
+    }
+    const uint32_t n2x4 = (uint32_t)n2 * 4u;
+    for (int r0 = 0; r0 < nb; r0 += 4) {
+        const float4 l4 = *reinterpret_cast<const float4*>(olab + r0);   // wave-uniform broadcast
+        float4 w4 = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (WEIGHTED && EK != MGK_EK_CONST) w4 = *reinterpret_cast<const float4*>(olw + r0);
+        const float lab[4] = {l4.x, l4.y, l4.z, l4.w};
+        const float lw1[4] = {w4.x, w4.y, w4.z, w4.w};
+        float pv[4][CB];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t off = (uint32_t)min(r0 + u, nb - 1) * n2x4;   // past the batch: its last row
+#pragma unroll
+            for (int b = 0; b < CB; ++b) pv[u][b] = *reinterpret_cast<const float*>(pb[b] + off);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int r = r0 + u;   // < the padded batch length
+#pragma unroll
+            for (int b = 0; b < CB; ++b) {
+                float cu;
+                if (EK == MGK_EK_SE) {
+                    const float d = el2[b] - lab[u];
+                    cu = __builtin_amdgcn_exp2f(__builtin_fmaf(-d, d, WEIGHTED ? lw2[b] + lw1[u] : lw2[b]));
+                } else if (EK == MGK_EK_POLY) {
+                    cu = mgk_poly_kernel(el2[b] - lab[u], prm.poly_c);
+                    if (WEIGHTED) cu *= lw1[u];
+                } else if (EK == MGK_EK_KRON_SE) {
+                    float t = WEIGHTED ? lw2[b] + lw1[u] : lw2[b];
+#pragma unroll
+                    for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a)
+                        if (a < D) {
+                            const float d = e2a[b][a] - oattr[a * MGK_ROWS_MAX_BATCH + r];
+                            t = __builtin_fmaf(-d, d, t);
+                        }
+                    cu = __builtin_amdgcn_exp2f(t);
+                } else if (EK == MGK_EK_RCONV_SE) {
+                    cu = 0.f;
+#pragma unroll
+                    for (int q = 0; q < MGK_MAX_LABEL_DIM; ++q)
+                        if (q < D) {
+                            const float e1b = oattr[q * MGK_ROWS_MAX_BATCH + r];
+#pragma unroll
+                            for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a)
+                                if (a < D) {
+                                    const float d = e2a[b][a] - e1b;
+                                    cu += __builtin_amdgcn_exp2f(-d * d);
+                                }
+                        }
+                    if (WEIGHTED) cu *= lw1[u];
+                } else {
+                    cu = lab[u];   // A_ij, 1 without weights, 0 past the batch
+                }
+                acc[b] = __builtin_fmaf(cu, pv[u][b], acc[b]);
+            }
+        }
+    }
+    const float w2div = 1.0f / (float)(D * D);
+#pragma unroll
+    for (int b = 0; b < CB; ++b) {
+        float v = acc[b];
+        if (EK == MGK_EK_CONST) v *= prm.ke_const * el2[b];
+        if (EK == MGK_EK_POLY) v *= lw2[b];
+        if (EK == MGK_EK_RCONV_SE) v *= lw2[b] * w2div;   // A'_i'j' / D^2 (0 on idle lanes)
+        if (P.nsteps > 0) v = __builtin_fmaf(rank[b] >= 1 ? 1.f : 0.f, row_shr<1>(v), v);
+        if (P.nsteps > 1) v = __builtin_fmaf(rank[b] >= 2 ? 1.f : 0.f, row_shr<2>(v), v);
+        if (P.nsteps > 2) v = __builtin_fmaf(rank[b] >= 4 ? 1.f : 0.f, row_shr<4>(v), v);
+        if (P.nsteps > 3) v = __builtin_fmaf(rank[b] >= 8 ? 1.f : 0.f, row_shr<8>(v), v);
+        if (last[b]) {
+            float* dst = yrow + ip[b];
+            // pairs with long inner rows add everywhere (y is cleared after every product)
+            if (P.atomic_rows) atomicAdd(dst, v);
+            else if (first_batch) *dst = v;
+            else *dst += v;                   // same lane, later batch of this row
+        }
+    }
+}
+
+// CB: chunks of the inner layout per pass.  A kernel parameter, not a run-time choice: the
+// register count of a kernel is that of its widest path, and the workloads with short rows
+// of p (several workgroups per CU) need the small one.
+template <bool WEIGHTED, int EK, int CB>
 __global__ __launch_bounds__(1024) void mgk_large_xmv_rows_kernel(
     MgkBatchDev X, MgkBatchDev Y, MgkExpanded EX, MgkExpanded EY, const MgkLargePair* pairs,
     const MgkPairState* state, float* vec, MgkParams prm, int lds_floats) {
@@ -277,132 +421,104 @@ __global__ __launch_bounds__(1024) void mgk_large_xmv_rows_kernel(
     const int nwaves = blockDim.x >> 6;
     // the host sizes LDS for at least one row of p, plus MGK_ROWS_MAX_BATCH outer entries
     const int bmax = min(max(lds_floats / n2, 1), MGK_ROWS_MAX_BATCH);
-    uint4* oent = reinterpret_cast<uint4*>(prow + lds_floats);   // the batch's outer entries
-    // their label attributes, prescaled: oattr[a * MGK_ROWS_MAX_BATCH + r]
-    float* oattr = reinterpret_cast<float*>(oent + MGK_ROWS_MAX_BATCH);
-    const float w2div = 1.0f / (float)(D * D);
+    // labels (weights for the constant kernel) and log2 weights (weights for the polynomial
+    // and R-convolution kernels) of the batch's outer entries, then their label attributes,
+    // prescaled: oattr[a * MGK_ROWS_MAX_BATCH + r]
+    float* olab = prow + ((lds_floats + 3) & ~3);   // read four at a time: 16-byte aligned
+    float* olw = olab + MGK_ROWS_MAX_BATCH;
+    float* oattr = olab + MGK_ROWS_MAX_BATCH * 4;
     const float* p = vec + P.vec + 2 * (int64_t)P.npad;
     float* y = vec + P.vec + 4 * (int64_t)P.npad;
     const uint4* outer = reinterpret_cast<const uint4*>(EX.outer) + g1.zoff;
     const uint4* inner = reinterpret_cast<const uint4*>(EY.inner) + g2.loff;
-    const float ke_c = prm.ke_const;
-
+    float* yrow = y + (int64_t)i * n2;
     for (int b0 = kb; b0 < ke; b0 += bmax) {
         const int nb = min(bmax, ke - b0);
         if (b0 > kb) __syncthreads();   // every wave is done with the rows staged before
         // the outer entries go to LDS too: in the product loop they are wave-uniform
         // operands, and a global load of one address by 64 lanes costs a full memory access
-        if ((int)threadIdx.x < nb) {
-            oent[threadIdx.x] = outer[b0 + threadIdx.x];
+        if ((int)threadIdx.x < ((nb + 3) & ~3)) {
+            const int t = threadIdx.x;
+            if (t < nb) {
+                const uint4 e = outer[b0 + t];
+                olab[t] = EK == MGK_EK_CONST && !WEIGHTED ? 1.f : __uint_as_float(e.y);
+                olw[t] = __uint_as_float(e.z);
+            } else {   // padding: a label so far away that kappa_e is exactly 0; weight 0
+                olab[t] = EK == MGK_EK_CONST ? 0.f : 1e18f;
+                olw[t] = 0.f;
+            }
             if (ATTR) {
 #pragma unroll
                 for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a)
                     if (a < D)
-                        oattr[a * MGK_ROWS_MAX_BATCH + threadIdx.x] =
-                            X.attr_outer[(int64_t)a * X.nnz_total + g1.zoff + b0 + threadIdx.x] *
-                            prm.attr_scale[EK == MGK_EK_RCONV_SE ? 0 : a];
+                        oattr[a * MGK_ROWS_MAX_BATCH + t] = t < nb
+                            ? X.attr_outer[(int64_t)a * X.nnz_total + g1.zoff + b0 + t] *
+                              prm.attr_scale[EK == MGK_EK_RCONV_SE ? 0 : a]
+                            : 1e18f;
             }
         }
-        for (int r = 0; r < nb; ++r) {
-            const int j = (int)outer[b0 + r].x;   // wave-uniform
-            const float* src = p + (int64_t)j * n2;
-            float* dst = prow + r * n2;
-            if ((n2 & 3) == 0) {   // rows start on 16-byte boundaries
-                const float4* s4 = reinterpret_cast<const float4*>(src);
-                float4* d4 = reinterpret_cast<float4*>(dst);
+        // Short rows: the rows of p of the whole batch as one index space, four elements in
+        // flight per thread, so that the loads of different rows do not wait for each other
+        // (config 2 at density 0.2: 18.6 -> 15.6 ms).  The row of an index comes from a
+        // floating-point quotient (exact at these sizes) and one correction.
+        if ((n2 & 3) == 0 && n2 >= (int)blockDim.x) {
+            // long rows, 16-byte aligned: one after the other, every thread busy in each
+            for (int r = 0; r < nb; ++r) {
+                const int j = (int)outer[b0 + r].x;   // wave-uniform
+                const float4* s4 = reinterpret_cast<const float4*>(p + (int64_t)j * n2);
+                float4* d4 = reinterpret_cast<float4*>(prow + r * n2);
                 for (int t = threadIdx.x; t < (n2 >> 2); t += blockDim.x) d4[t] = s4[t];
-            } else {
-                for (int t = threadIdx.x; t < n2; t += blockDim.x) dst[t] = src[t];
+            }
+        } else if ((n2 & 3) == 0) {
+            const int n2q = n2 >> 2, total = nb * n2q;
+            const float inv = 1.0f / (float)n2q;
+            const float4* p4 = reinterpret_cast<const float4*>(p);
+            float4* d4 = reinterpret_cast<float4*>(prow);
+            for (int idx0 = threadIdx.x; idx0 < total; idx0 += 4 * blockDim.x) {
+                float4 v[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int idx = idx0 + q * (int)blockDim.x;
+                    if (idx < total) {
+                        int r = (int)(((float)idx + 0.5f) * inv);
+                        r += (idx - r * n2q >= n2q) - (idx - r * n2q < 0);   // guards the rounding
+                        const int j = (int)outer[b0 + r].x;
+                        v[q] = p4[(int64_t)j * n2q + (idx - r * n2q)];
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int idx = idx0 + q * (int)blockDim.x;
+                    if (idx < total) d4[idx] = v[q];
+                }
+            }
+        } else {
+            const int total = nb * n2;
+            const float inv = 1.0f / (float)n2;
+            for (int idx0 = threadIdx.x; idx0 < total; idx0 += 4 * blockDim.x) {
+                float v[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int idx = idx0 + q * (int)blockDim.x;
+                    if (idx < total) {
+                        int r = (int)(((float)idx + 0.5f) * inv);
+                        r += (idx - r * n2 >= n2) - (idx - r * n2 < 0);
+                        const int j = (int)outer[b0 + r].x;
+                        v[q] = p[(int64_t)j * n2 + (idx - r * n2)];
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int idx = idx0 + q * (int)blockDim.x;
+                    if (idx < total) prow[idx] = v[q];
+                }
             }
         }
         __syncthreads();
-        uint4 e2_next = wave < chunks ? inner[wave * 64 + lane] : make_uint4(0u, 0u, 0u, 0u);
-        for (int c = wave; c < chunks; c += nwaves) {
-            const uint4 e2 = e2_next;
-            if (c + nwaves < chunks) e2_next = inner[(c + nwaves) * 64 + lane];   // in flight during this chunk
-            const int ip = (int)e2.x;
-            const uint32_t jp4 = (e2.y & 0xffffffu) * 4u;
-            const uint32_t rank = (e2.y >> 24) & 0xfu;
-            const bool last = (e2.y >> 31) != 0u;
-            const float el2 = __uint_as_float(e2.z);
-            const float lw2 = __uint_as_float(e2.w);
-            const char* pb = reinterpret_cast<const char*>(prow) + jp4;
-            float e2a[MGK_MAX_LABEL_DIM] = {0.f, 0.f, 0.f, 0.f};   // this lane's attributes, prescaled
-            if (ATTR) {
-#pragma unroll
-                for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a)
-                    if (a < D)
-                        e2a[a] = Y.attr_inner[(int64_t)a * Y.lanes_total + g2.loff + c * 64 + lane] *
-                                 prm.attr_scale[EK == MGK_EK_RCONV_SE ? 0 : a];
-            }
-            float acc = 0.f;
-            for (int r0 = 0; r0 < nb; r0 += 4) {
-                uint4 e1[4];
-                float pv[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {   // past the batch: repeat its last entry with weight 0
-                    const int r = min(r0 + u, nb - 1);
-                    e1[u] = oent[r];            // wave-uniform LDS broadcast
-                    pv[u] = *reinterpret_cast<const float*>(pb + (size_t)r * n2 * 4);
-                    if (r0 + u >= nb) pv[u] = 0.f;
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    float cu;
-                    if (EK == MGK_EK_SE) {
-                        const float d = el2 - __uint_as_float(e1[u].y);
-                        cu = __builtin_amdgcn_exp2f(__builtin_fmaf(-d, d, WEIGHTED ? lw2 + __uint_as_float(e1[u].z) : lw2));
-                    } else if (EK == MGK_EK_POLY) {
-                        cu = mgk_poly_kernel(el2 - __uint_as_float(e1[u].y), prm.poly_c);
-                        if (WEIGHTED) cu *= __uint_as_float(e1[u].z);
-                    } else if (EK == MGK_EK_KRON_SE) {
-                        const int r = min(r0 + u, nb - 1);
-                        float t = WEIGHTED ? lw2 + __uint_as_float(e1[u].z) : lw2;
-#pragma unroll
-                        for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a)
-                            if (a < D) {
-                                const float d = e2a[a] - oattr[a * MGK_ROWS_MAX_BATCH + r];
-                                t = __builtin_fmaf(-d, d, t);
-                            }
-                        cu = __builtin_amdgcn_exp2f(t);
-                    } else if (EK == MGK_EK_RCONV_SE) {
-                        const int r = min(r0 + u, nb - 1);
-                        cu = 0.f;
-#pragma unroll
-                        for (int b = 0; b < MGK_MAX_LABEL_DIM; ++b)
-                            if (b < D) {
-                                const float e1b = oattr[b * MGK_ROWS_MAX_BATCH + r];
-#pragma unroll
-                                for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a)
-                                    if (a < D) {
-                                        const float d = e2a[a] - e1b;
-                                        cu += __builtin_amdgcn_exp2f(-d * d);
-                                    }
-                            }
-                        if (WEIGHTED) cu *= __uint_as_float(e1[u].z);
-                    } else {
-                        cu = WEIGHTED ? __uint_as_float(e1[u].y) : 1.f;
-                    }
-                    acc = __builtin_fmaf(cu, pv[u], acc);
-                }
-            }
-            if (EK == MGK_EK_CONST) acc *= ke_c * el2;
-            if (EK == MGK_EK_POLY) acc *= lw2;
-            if (EK == MGK_EK_RCONV_SE) acc *= lw2 * w2div;   // A'_i'j' / D^2 (0 on idle lanes)
-            const float m1 = rank >= 1 ? 1.f : 0.f, m2 = rank >= 2 ? 1.f : 0.f;
-            const float m4 = rank >= 4 ? 1.f : 0.f, m8 = rank >= 8 ? 1.f : 0.f;
-            if (P.nsteps > 0) acc = __builtin_fmaf(m1, row_shr<1>(acc), acc);
-            if (P.nsteps > 1) acc = __builtin_fmaf(m2, row_shr<2>(acc), acc);
-            if (P.nsteps > 2) acc = __builtin_fmaf(m4, row_shr<4>(acc), acc);
-            if (P.nsteps > 3) acc = __builtin_fmaf(m8, row_shr<8>(acc), acc);
-            if (last) {
-                float* dst = y + ((int64_t)i * n2 + ip);
-                // pairs with long inner rows add everywhere (y is cleared after every product)
-                if (P.atomic_rows) atomicAdd(dst, acc);
-                else if (b0 == kb) *dst = acc;
-                else *dst += acc;                   // same lane, later batch of this row
-            }
-        }
+        const bool first = b0 == kb;
+        rows_sweep<CB, WEIGHTED, EK>(inner, wave, nwaves, chunks, lane, [&](const uint4 (&e2v)[CB], int c0) {
+            rows_pass<CB, WEIGHTED, EK>(Y, g2, P, prm, e2v, c0, chunks, lane, prow, olab, olw, oattr, nb, n2, yrow, first);
+        });
     }
 }
 
@@ -713,27 +829,34 @@ hipError_t mgk_launch_large_iteration(const MgkBatchDev& X, const MgkBatchDev& Y
                                       bool weighted, int n_pairs, int xmv_blocks, int vec_blocks,
                                       int* n_active, bool first, const MgkDenseTiles* DX,
                                       const MgkDenseTiles* DY, int rows_threads, int rows_lds_bytes,
-                                      hipStream_t stream) {
+                                      int rows_chunks, hipStream_t stream) {
     const dim3 gx(xmv_blocks, n_pairs), gv(vec_blocks, n_pairs), gs((n_pairs + 63) / 64);
     if (DX == nullptr && rows_threads > 0) {
         // xmv_blocks = largest number of outer rows of a pair
-#define MGK_ROWS(EKV) \
-    case EKV: { \
-        auto kern = weighted ? mgk_large_xmv_rows_kernel<true, EKV> : mgk_large_xmv_rows_kernel<false, EKV>; \
-        static bool configured[2] = {false, false}; \
-        if (!configured[weighted ? 1 : 0]) { \
+#define MGK_ROWS_GO(WT, EKV, CBV, SLOT) \
+    { \
+        auto kern = mgk_large_xmv_rows_kernel<WT, EKV, CBV>; \
+        static bool configured = false; \
+        if (!configured) { \
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), \
                                                hipFuncAttributeMaxDynamicSharedMemorySize, MGK_LDS_LIMIT_BYTES); \
             if (e != hipSuccess) return e; \
-            configured[weighted ? 1 : 0] = true; \
+            configured = true; \
         } \
-        hipLaunchKernelGGL(kern, gx, dim3(rows_threads), rows_lds_bytes + MGK_ROWS_MAX_BATCH * (sizeof(uint4) + MGK_MAX_LABEL_DIM * sizeof(float)), stream, X, Y, EX, EY, pairs, state, vec, prm, rows_lds_bytes / 4); \
-        break; }
+        hipLaunchKernelGGL(kern, gx, dim3(rows_threads), rows_lds_bytes + 16 + MGK_ROWS_MAX_BATCH * (4 + MGK_MAX_LABEL_DIM) * sizeof(float), stream, X, Y, EX, EY, pairs, state, vec, prm, rows_lds_bytes / 4); \
+    }
+#define MGK_ROWS(EKV) \
+    case EKV: \
+        if (rows_chunks >= 4) { if (weighted) MGK_ROWS_GO(true, EKV, 4, 0) else MGK_ROWS_GO(false, EKV, 4, 1) } \
+        else if (rows_chunks >= 2) { if (weighted) MGK_ROWS_GO(true, EKV, 2, 2) else MGK_ROWS_GO(false, EKV, 2, 3) } \
+        else { if (weighted) MGK_ROWS_GO(true, EKV, 1, 4) else MGK_ROWS_GO(false, EKV, 1, 5) } \
+        break;
         switch (prm.edge_kernel) {
             MGK_ROWS(MGK_EK_SE) MGK_ROWS(MGK_EK_CONST) MGK_ROWS(MGK_EK_POLY)
             MGK_ROWS(MGK_EK_KRON_SE) MGK_ROWS(MGK_EK_RCONV_SE)
             default: return hipErrorInvalidValue;
         }
+#undef MGK_ROWS_GO
 #undef MGK_ROWS
     } else if (DX != nullptr) {
         if (prm.edge_kernel == MGK_EK_SE)

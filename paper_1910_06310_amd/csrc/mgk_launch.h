@@ -84,15 +84,16 @@ hipError_t mgk_launch_large_init(const MgkBatchDev& X, const MgkBatchDev& Y, con
 // (xmv_blocks = workgroups of 4 output blocks); else the sparse XMV on the
 // expanded lists: with rows_threads > 0 the one that stages rows of p in
 // rows_lds_bytes of LDS (xmv_blocks = outer rows, one workgroup of rows_threads
-// each; every row of p must fit), with rows_threads == 0 the one that gathers p
-// from global memory.
+// each; every row of p must fit; rows_chunks = 1, 2 or 4 chunks of the inner layout
+// per pass of a wavefront), with rows_threads == 0 the one that gathers p from global
+// memory.
 hipError_t mgk_launch_large_iteration(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkExpanded& EX,
                                       const MgkExpanded& EY, const MgkLargePair* pairs,
                                       MgkPairState* state, float* vec, const MgkParams& prm,
                                       bool weighted, int n_pairs, int xmv_blocks, int vec_blocks,
                                       int* n_active, bool first, const MgkDenseTiles* DX,
                                       const MgkDenseTiles* DY, int rows_threads, int rows_lds_bytes,
-                                      hipStream_t stream);
+                                      int rows_chunks, hipStream_t stream);
 // K = p_x^T x and the per-pair outputs.
 hipError_t mgk_launch_large_final(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkLargePair* pairs,
                                   MgkPairState* state, const float* vec, int n_pairs, int vec_blocks,
