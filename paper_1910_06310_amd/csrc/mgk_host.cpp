@@ -996,11 +996,12 @@ mgk_status mgk_load_graphs_attr(mgk_ctx* ctx, int32_t n_graphs, const int64_t* v
         for (int i = 0; i < n; ++i) { rowptr[v0 + i] = run; run += deg[i]; }
         // lane layout as inner operand: rows packed into groups of 16 lanes
         int32_t slot = 0, max_deg = 0;
+        for (int i = 0; i < n; ++i) max_deg = std::max(max_deg, deg[i]);
+        const bool packed = max_deg > MGK_LANE_GROUP;   // long rows: atomic adds anyway, no gaps
         for (int i = 0; i < n; ++i) {
             const int dg = deg[i];
-            max_deg = std::max(max_deg, dg);
             const int room = MGK_LANE_GROUP - slot % MGK_LANE_GROUP;
-            if (dg > room && room != MGK_LANE_GROUP) slot += room;  // start a new group
+            if (!packed && dg > room && room != MGK_LANE_GROUP) slot += room;  // start a new group
             lanepos[v0 + i] = slot;
             slot += dg;
         }
@@ -1033,11 +1034,9 @@ mgk_status mgk_load_graphs_attr(mgk_ctx* ctx, int32_t n_graphs, const int64_t* v
             const bool row_end = rank + 1 == deg[i];
             list_outer[(size_t)gd.zoff + rowptr[v0 + i] + rank] =
                 MgkEntry{i, j, ebits, wbits | (row_end ? 0x80000000u : 0u)};
-            const uint32_t run_rank = (uint32_t)rank % MGK_LANE_GROUP;
-            const uint32_t last = (row_end || run_rank == MGK_LANE_GROUP - 1) ? 1u : 0u;
-            const uint32_t longrow = deg[i] > MGK_LANE_GROUP ? 1u : 0u;
+            const MgkRunPos rp = mgk_run_pos(lanepos[v0 + i], rank, deg[i]);
             list_inner[(size_t)gd.loff + lanepos[v0 + i] + rank] =
-                MgkEntry{i | (run_rank << 20) | (longrow << 30) | (last << 31), j, ebits, wbits};
+                MgkEntry{i | (rp.rank << 20) | (rp.cut << 30) | (rp.last << 31), j, ebits, wbits};
             {
                 attr_pos_outer.push_back({(int64_t)gd.zoff + rowptr[v0 + i] + rank, nz[k].edge});
                 attr_pos_inner.push_back({(int64_t)gd.loff + lanepos[v0 + i] + rank, nz[k].edge});

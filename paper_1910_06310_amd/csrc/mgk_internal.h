@@ -30,10 +30,30 @@ struct MgkGraphDesc {
 };
 
 // Lane layout of a graph used as the inner operand of the on-chip XMV: the
-// nonzeros of a row occupy adjacent lanes that never cross a group of 16
-// lanes (rows longer than 16 are cut into runs of 16), so that the sum over a
-// row is a DPP shift-and-add inside one 16-lane row of a wavefront.
+// nonzeros of a row occupy adjacent lanes, and the sum over a row is a DPP
+// shift-and-add inside one 16-lane row of a wavefront.  In a graph whose rows
+// all have at most 16 nonzeros no row crosses a group of 16 lanes (a row that
+// does not fit the rest of a group starts the next one), so every y_ii' has one
+// writer.  A graph with longer rows needs atomic adds anyway (a long row is cut
+// into several runs); there the rows are packed without gaps and every row that
+// crosses a group boundary is cut at it.
 #define MGK_LANE_GROUP 16
+
+// Where nonzero `rank` of a row of `deg` nonzeros sits when the row starts at lane
+// slot `first`: its position in its run (the part of the row inside one lane group),
+// whether it is the last of the run, whether the row has more than one run.
+struct MgkRunPos {
+    uint32_t rank, last, cut;
+};
+static inline MGK_HD MgkRunPos mgk_run_pos(int first, int rank, int deg) {
+    const int pos = first + rank;
+    const int group = pos & ~(MGK_LANE_GROUP - 1);
+    MgkRunPos r;
+    r.rank = (uint32_t)(pos - (first > group ? first : group));
+    r.last = (rank + 1 == deg || pos - group == MGK_LANE_GROUP - 1) ? 1u : 0u;
+    r.cut = (first & (MGK_LANE_GROUP - 1)) + deg > MGK_LANE_GROUP ? 1u : 0u;
+    return r;
+}
 
 // One non-empty octile (Section IV-A/B): tile coordinates, occupancy bitmap
 // (bit 8*r + c <-> element (r, c) of the tile) and where its packed nonzeros

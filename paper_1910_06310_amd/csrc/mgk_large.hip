@@ -88,11 +88,10 @@ __global__ __launch_bounds__(256) void mgk_expand_kernel(MgkBatchDev B, MgkParam
     const float lw = (EK == MGK_EK_POLY || EK == MGK_EK_RCONV_SE) ? w : __log2f(w);
     const float lab = EK == MGK_EK_CONST ? w : el;
     outer[g.zoff + rp0 + rank] = make_uint4((uint32_t)col, __float_as_uint(lab), __float_as_uint(lw), (uint32_t)row);
-    const uint32_t run_rank = (uint32_t)rank % MGK_LANE_GROUP;
-    const uint32_t last = (rank + 1 == rp1 - rp0 || run_rank == MGK_LANE_GROUP - 1) ? 1u : 0u;
-    const uint32_t longrow = rp1 - rp0 > MGK_LANE_GROUP ? 1u : 0u;   // row cut into several runs
-    inner[g.loff + B.lanepos[g.voff + row] + rank] =
-        make_uint4((uint32_t)row, (uint32_t)col | (run_rank << 24) | (longrow << 30) | (last << 31), __float_as_uint(lab),
+    const int first = B.lanepos[g.voff + row];
+    const MgkRunPos rp = mgk_run_pos(first, rank, rp1 - rp0);
+    inner[g.loff + first + rank] =
+        make_uint4((uint32_t)row, (uint32_t)col | (rp.rank << 24) | (rp.cut << 30) | (rp.last << 31), __float_as_uint(lab),
                    __float_as_uint(lw));
 }
 

@@ -78,10 +78,8 @@ __device__ __forceinline__ void expand_nonzero(const MgkBatchDev& B, const MgkGr
     } else {
         const int lp = B.lanepos[g.voff + row];
         const int deg = rp1 - rp0;
-        const uint32_t run_rank = (uint32_t)rank % MGK_LANE_GROUP;
-        const uint32_t last = (rank + 1 == deg || run_rank == MGK_LANE_GROUP - 1) ? 1u : 0u;
-        const uint32_t longrow = deg > MGK_LANE_GROUP ? 1u : 0u;   // row cut into several runs
-        v.x = (uint32_t)(row * 4) | (run_rank << 20) | (longrow << 30) | (last << 31);
+        const MgkRunPos rp = mgk_run_pos(lp, rank, deg);   // cut: the row has several runs
+        v.x = (uint32_t)(row * 4) | (rp.rank << 20) | (rp.cut << 30) | (rp.last << 31);
         v.y = (uint32_t)(col * 4);
         v.z = __float_as_uint(EK == MGK_EK_CONST ? w : el);
         v.w = __float_as_uint(EK == MGK_EK_POLY ? w : WEIGHTED ? __log2f(w) : 0.f);
