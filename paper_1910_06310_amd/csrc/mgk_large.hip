@@ -278,16 +278,17 @@ __device__ __forceinline__ void rows_sweep(const uint4* inner, int wave, int nwa
 }
 
 // The products of one pass: this wave's CB chunks of the inner lane layout (chunk c0 + b,
-// idle past `chunks`) against the nb outer entries of the staged batch.  The labels and
-// log-weights of the batch sit in LDS as plain arrays padded to a multiple of four with
-// entries whose kernel value is exactly 0, and are read four at a time: one 16-byte
+// idle past `chunks`) against the nb outer entries of the staged batch.  The weight A_ij
+// of an outer entry is already in its staged row of p.  The labels of the batch sit in
+// LDS as a plain array padded to a multiple of four with entries whose kernel value is
+// exactly 0, and are read four at a time: one 16-byte
 // broadcast read serves 4 * CB products, where a read of a whole 16-byte entry per product
 // occupied the LDS four times as long as the gather of p it accompanied.
 template <int CB, bool WEIGHTED, int EK>
 __device__ __forceinline__ void rows_pass(const MgkBatchDev& Y, const MgkGraphDesc& g2,
                                           const MgkLargePair& P, const MgkParams& prm,
                                           const uint4 (&e2v)[CB], int c0, int chunks, int lane,
-                                          const float* prow, const float* olab, const float* olw,
+                                          const float* prow, const float* olab,
                                           const float* oattr, int nb, int n2, float* yrow,
                                           bool first_batch) {
     constexpr bool ATTR = EK == MGK_EK_KRON_SE || EK == MGK_EK_RCONV_SE;
@@ -320,10 +321,7 @@ __device__ __forceinline__ void rows_pass(const MgkBatchDev& Y, const MgkGraphDe
     const uint32_t n2x4 = (uint32_t)n2 * 4u;
     for (int r0 = 0; r0 < nb; r0 += 4) {
         const float4 l4 = *reinterpret_cast<const float4*>(olab + r0);   // wave-uniform broadcast
-        float4 w4 = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (WEIGHTED && EK != MGK_EK_CONST) w4 = *reinterpret_cast<const float4*>(olw + r0);
         const float lab[4] = {l4.x, l4.y, l4.z, l4.w};
-        const float lw1[4] = {w4.x, w4.y, w4.z, w4.w};
         float pv[4][CB];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -339,12 +337,11 @@ __device__ __forceinline__ void rows_pass(const MgkBatchDev& Y, const MgkGraphDe
                 float cu;
                 if (EK == MGK_EK_SE) {
                     const float d = el2[b] - lab[u];
-                    cu = __builtin_amdgcn_exp2f(__builtin_fmaf(-d, d, WEIGHTED ? lw2[b] + lw1[u] : lw2[b]));
+                    cu = __builtin_amdgcn_exp2f(__builtin_fmaf(-d, d, lw2[b]));
                 } else if (EK == MGK_EK_POLY) {
                     cu = mgk_poly_kernel(el2[b] - lab[u], prm.poly_c);
-                    if (WEIGHTED) cu *= lw1[u];
                 } else if (EK == MGK_EK_KRON_SE) {
-                    float t = WEIGHTED ? lw2[b] + lw1[u] : lw2[b];
+                    float t = lw2[b];
 #pragma unroll
                     for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a)
                         if (a < D) {
@@ -365,9 +362,8 @@ __device__ __forceinline__ void rows_pass(const MgkBatchDev& Y, const MgkGraphDe
                                     cu += __builtin_amdgcn_exp2f(-d * d);
                                 }
                         }
-                    if (WEIGHTED) cu *= lw1[u];
                 } else {
-                    cu = lab[u];   // A_ij, 1 without weights, 0 past the batch
+                    cu = lab[u];   // 1, 0 past the batch
                 }
                 acc[b] = __builtin_fmaf(cu, pv[u][b], acc[b]);
             }
@@ -420,11 +416,12 @@ __global__ __launch_bounds__(1024) void mgk_large_xmv_rows_kernel(
     const int nwaves = blockDim.x >> 6;
     // the host sizes LDS for at least one row of p, plus MGK_ROWS_MAX_BATCH outer entries
     const int bmax = min(max(lds_floats / n2, 1), MGK_ROWS_MAX_BATCH);
-    // labels (weights for the constant kernel) and log2 weights (weights for the polynomial
-    // and R-convolution kernels) of the batch's outer entries, then their label attributes,
-    // prescaled: oattr[a * MGK_ROWS_MAX_BATCH + r]
+    // labels of the batch's outer entries (1 for the constant kernel), their weights A_ij,
+    // the rows j of p they multiply, then their label attributes, prescaled:
+    // oattr[a * MGK_ROWS_MAX_BATCH + r]
     float* olab = prow + ((lds_floats + 3) & ~3);   // read four at a time: 16-byte aligned
-    float* olw = olab + MGK_ROWS_MAX_BATCH;
+    float* ow = olab + MGK_ROWS_MAX_BATCH;
+    int* oj = reinterpret_cast<int*>(olab + 2 * MGK_ROWS_MAX_BATCH);
     float* oattr = olab + MGK_ROWS_MAX_BATCH * 4;
     const float* p = vec + P.vec + 2 * (int64_t)P.npad;
     float* y = vec + P.vec + 4 * (int64_t)P.npad;
@@ -440,11 +437,15 @@ __global__ __launch_bounds__(1024) void mgk_large_xmv_rows_kernel(
             const int t = threadIdx.x;
             if (t < nb) {
                 const uint4 e = outer[b0 + t];
-                olab[t] = EK == MGK_EK_CONST && !WEIGHTED ? 1.f : __uint_as_float(e.y);
-                olw[t] = __uint_as_float(e.z);
-            } else {   // padding: a label so far away that kappa_e is exactly 0; weight 0
+                olab[t] = EK == MGK_EK_CONST ? 1.f : __uint_as_float(e.y);
+                // the entry carries log2 A_ij where the weight is folded into an exponent
+                ow[t] = !WEIGHTED ? 1.f
+                        : EK == MGK_EK_CONST ? __uint_as_float(e.y)
+                        : (EK == MGK_EK_SE || EK == MGK_EK_KRON_SE) ? __builtin_amdgcn_exp2f(__uint_as_float(e.z))
+                        : __uint_as_float(e.z);
+                oj[t] = (int)e.x;
+            } else {   // padding: a label so far away that kappa_e is exactly 0
                 olab[t] = EK == MGK_EK_CONST ? 0.f : 1e18f;
-                olw[t] = 0.f;
             }
             if (ATTR) {
 #pragma unroll
@@ -460,13 +461,20 @@ __global__ __launch_bounds__(1024) void mgk_large_xmv_rows_kernel(
         // flight per thread, so that the loads of different rows do not wait for each other
         // (config 2 at density 0.2: 18.6 -> 15.6 ms).  The row of an index comes from a
         // floating-point quotient (exact at these sizes) and one correction.
+        __syncthreads();   // oj, ow
+        // Row r of the batch is A_ij p_j. for its outer entry (i, j): the weight is applied
+        // once per element of the row here instead of once per product below.
         if ((n2 & 3) == 0 && n2 >= (int)blockDim.x) {
             // long rows, 16-byte aligned: one after the other, every thread busy in each
             for (int r = 0; r < nb; ++r) {
-                const int j = (int)outer[b0 + r].x;   // wave-uniform
-                const float4* s4 = reinterpret_cast<const float4*>(p + (int64_t)j * n2);
+                const float4* s4 = reinterpret_cast<const float4*>(p + (int64_t)oj[r] * n2);
                 float4* d4 = reinterpret_cast<float4*>(prow + r * n2);
-                for (int t = threadIdx.x; t < (n2 >> 2); t += blockDim.x) d4[t] = s4[t];
+                const float wr = ow[r];
+                for (int t = threadIdx.x; t < (n2 >> 2); t += blockDim.x) {
+                    float4 v = s4[t];
+                    if (WEIGHTED) { v.x *= wr; v.y *= wr; v.z *= wr; v.w *= wr; }
+                    d4[t] = v;
+                }
             }
         } else if ((n2 & 3) == 0) {
             const int n2q = n2 >> 2, total = nb * n2q;
@@ -481,8 +489,11 @@ __global__ __launch_bounds__(1024) void mgk_large_xmv_rows_kernel(
                     if (idx < total) {
                         int r = (int)(((float)idx + 0.5f) * inv);
                         r += (idx - r * n2q >= n2q) - (idx - r * n2q < 0);   // guards the rounding
-                        const int j = (int)outer[b0 + r].x;
-                        v[q] = p4[(int64_t)j * n2q + (idx - r * n2q)];
+                        v[q] = p4[(int64_t)oj[r] * n2q + (idx - r * n2q)];
+                        if (WEIGHTED) {
+                            const float wr = ow[r];
+                            v[q].x *= wr; v[q].y *= wr; v[q].z *= wr; v[q].w *= wr;
+                        }
                     }
                 }
 #pragma unroll
@@ -502,8 +513,8 @@ __global__ __launch_bounds__(1024) void mgk_large_xmv_rows_kernel(
                     if (idx < total) {
                         int r = (int)(((float)idx + 0.5f) * inv);
                         r += (idx - r * n2 >= n2) - (idx - r * n2 < 0);
-                        const int j = (int)outer[b0 + r].x;
-                        v[q] = p[(int64_t)j * n2 + (idx - r * n2)];
+                        v[q] = p[(int64_t)oj[r] * n2 + (idx - r * n2)];
+                        if (WEIGHTED) v[q] *= ow[r];
                     }
                 }
 #pragma unroll
@@ -516,7 +527,7 @@ __global__ __launch_bounds__(1024) void mgk_large_xmv_rows_kernel(
         __syncthreads();
         const bool first = b0 == kb;
         rows_sweep<CB, WEIGHTED, EK>(inner, wave, nwaves, chunks, lane, [&](const uint4 (&e2v)[CB], int c0) {
-            rows_pass<CB, WEIGHTED, EK>(Y, g2, P, prm, e2v, c0, chunks, lane, prow, olab, olw, oattr, nb, n2, yrow, first);
+            rows_pass<CB, WEIGHTED, EK>(Y, g2, P, prm, e2v, c0, chunks, lane, prow, olab, oattr, nb, n2, yrow, first);
         });
     }
 }
