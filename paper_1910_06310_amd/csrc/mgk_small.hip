@@ -36,10 +36,13 @@ namespace {
 // Inner graph: lane layout (rows in adjacent lanes inside groups of 16), entry
 // = {i'*4 | rank in run << 20 | row-longer-than-16 << 30 | last-of-run << 31,
 // j'*4, scaled label or weight, log2 weight}.
-template <bool OUTER, bool WEIGHTED, int EK>
+// PLANES (outer graph only): the four words of entry k go to four arrays of `stride`
+// words each (word w of entry k at ent[w * stride + k]) instead of one 16-byte record.
+template <bool OUTER, bool WEIGHTED, int EK, bool PLANES>
 __device__ __forceinline__ void expand_nonzero(const MgkBatchDev& B, const MgkGraphDesc& g,
                                                const MgkTile* tiles_lds, int k, uint4* ent,
-                                               uint32_t* rowend, int n_inner, const MgkParams& prm) {
+                                               uint32_t* rowend, int n_inner, const MgkParams& prm,
+                                               int stride) {
     int lo = 0, hi = g.n_tiles;   // last tile whose first packed nonzero is <= k
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
@@ -73,7 +76,15 @@ __device__ __forceinline__ void expand_nonzero(const MgkBatchDev& B, const MgkGr
         v.y = __float_as_uint(EK == MGK_EK_CONST ? w : el);
         v.z = __float_as_uint(EK == MGK_EK_POLY ? w : WEIGHTED ? __log2f(w) : 0.f);
         v.w = (uint32_t)(row * n_inner * 4);
-        ent[pos] = v;
+        if (PLANES) {
+            uint32_t* words = reinterpret_cast<uint32_t*>(ent);
+            words[pos] = v.x;
+            words[stride + pos] = v.y;
+            words[2 * stride + pos] = v.z;
+            words[3 * stride + pos] = v.w;
+        } else {
+            ent[pos] = v;
+        }
         if (pos + 1 == rp1) atomicOr(&rowend[pos >> 5], 1u << (pos & 31));
     } else {
         const int lp = B.lanepos[g.voff + row];
@@ -113,7 +124,8 @@ __device__ __forceinline__ int next_set_bit(const uint32_t* bits, int words, int
 template <int CB, int NSTEPS, bool WEIGHTED, int EK, bool ATOMIC>
 __device__ __forceinline__ void xmv_chunks(const uint4* ent1, const uint4* ent2c, const uint32_t* rowend,
                                            const char* pbytes, char* ybytes, int kbeg, int kend,
-                                           int kfirst, bool force_end, float ke_c, const float* pc) {
+                                           int kfirst, bool force_end, float ke_c, const float* pc,
+                                           int z1pad) {
     static_assert(CB == 1 || CB == 2 || CB == 4, "one, two or four chunks per pass");
     uint32_t ip4[CB], jp4[CB], rank[CB];
     bool last[CB], longrow[CB];
@@ -150,8 +162,23 @@ __device__ __forceinline__ void xmv_chunks(const uint4* ent1, const uint4* ent2c
         for (int k = k0; k < kstop; k += 4, window >>= 4) {
             uint4 e1[4];
             float pv[4][CB], cu[4][CB];
+            if constexpr (ATOMIC) {
+                // four arrays instead of records: one broadcast read brings a word of four
+                // entries (k is a multiple of 4 here); the offset of the row of y is read
+                // where a row ends, which is rare in graphs with long rows
+                const uint32_t* words = reinterpret_cast<const uint32_t*>(ent1);
+                const uint4 x4 = *reinterpret_cast<const uint4*>(words + k);
+                const uint4 y4 = *reinterpret_cast<const uint4*>(words + z1pad + k);
+                e1[0].x = x4.x; e1[1].x = x4.y; e1[2].x = x4.z; e1[3].x = x4.w;
+                e1[0].y = y4.x; e1[1].y = y4.y; e1[2].y = y4.z; e1[3].y = y4.w;
+                if (WEIGHTED && EK != MGK_EK_CONST) {
+                    const uint4 z4 = *reinterpret_cast<const uint4*>(words + 2 * z1pad + k);
+                    e1[0].z = z4.x; e1[1].z = z4.y; e1[2].z = z4.z; e1[3].z = z4.w;
+                }
+            } else {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) e1[u] = ent1[k + u];
+                for (int u = 0; u < 4; ++u) e1[u] = ent1[k + u];
+            }
 #pragma unroll
             for (int u = 0; u < 4; ++u)
 #pragma unroll
@@ -182,6 +209,8 @@ __device__ __forceinline__ void xmv_chunks(const uint4* ent1, const uint4* ent2c
                 if ((window >> u) & 1u) {   // end of outer row i: sum over each inner row
                     // wave-uniform: this wave holds only a part of outer row i
                     const bool part = ATOMIC && (k + u == kfirst || (force_end && k + u == kend - 1));
+                    const uint32_t yoff = ATOMIC ? reinterpret_cast<const uint32_t*>(ent1)[3 * z1pad + k + u]
+                                                 : e1[u].w;
 #pragma unroll
                     for (int b = 0; b < CB; ++b) {
                         if (EK == MGK_EK_CONST) acc[b] *= ke_c * el2[b];  // el2 = A'_i'j' (0 on idle lanes)
@@ -206,7 +235,7 @@ __device__ __forceinline__ void xmv_chunks(const uint4* ent1, const uint4* ent2c
 #pragma unroll
                     for (int b = 0; b < CB; ++b) {
                         if (last[b]) {
-                            float* dst = reinterpret_cast<float*>(ybytes + (e1[u].w + ip4[b]));
+                            float* dst = reinterpret_cast<float*>(ybytes + (yoff + ip4[b]));
                             if (ATOMIC && (longrow[b] || part))   // several sums add up to one y_ii'
                                 __hip_atomic_fetch_add(dst, acc[b], __ATOMIC_RELAXED,
                                                        __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -227,7 +256,7 @@ template <int NSTEPS, bool WEIGHTED, int EK, bool ATOMIC>
 __device__ __forceinline__ void xmv_pass(const uint4* ent1, const uint4* ent2, const uint32_t* rowend,
                                          const char* pbytes, char* ybytes, int len2, int kbeg,
                                          int kend, int kfirst, bool force_end, float ke_c,
-                                         const float* pc, int lane) {
+                                         const float* pc, int lane, int z1pad) {
     // A kernel's register count is that of its widest path: four chunks per pass only in
     // the kernels for graphs with long rows, whose inner layouts have many chunks.
     constexpr int CBMAX = ATOMIC ? 4 : 2;
@@ -235,14 +264,14 @@ __device__ __forceinline__ void xmv_pass(const uint4* ent1, const uint4* ent2, c
     if constexpr (CBMAX >= 4)
         for (; c + 256 <= len2; c += 256)
             xmv_chunks<4, NSTEPS, WEIGHTED, EK, ATOMIC>(ent1, ent2 + c + lane, rowend, pbytes, ybytes,
-                                                        kbeg, kend, kfirst, force_end, ke_c, pc);
+                                                        kbeg, kend, kfirst, force_end, ke_c, pc, z1pad);
     if constexpr (CBMAX >= 2)
         for (; c + 128 <= len2; c += 128)
             xmv_chunks<2, NSTEPS, WEIGHTED, EK, ATOMIC>(ent1, ent2 + c + lane, rowend, pbytes, ybytes,
-                                                        kbeg, kend, kfirst, force_end, ke_c, pc);
+                                                        kbeg, kend, kfirst, force_end, ke_c, pc, z1pad);
     for (; c < len2; c += 64)
         xmv_chunks<1, NSTEPS, WEIGHTED, EK, ATOMIC>(ent1, ent2 + c + lane, rowend, pbytes, ybytes,
-                                                    kbeg, kend, kfirst, force_end, ke_c, pc);
+                                                    kbeg, kend, kfirst, force_end, ke_c, pc, z1pad);
 }
 
 // ATOMIC: the inner graph has rows longer than 16 nonzeros; the runs of those rows are
@@ -291,7 +320,14 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
     for (int k = tid; k < L.rowend_words; k += NT) rowend[k] = 0u;
     // spare outer entries past z1 (read by the 4-wide loop, never used) and idle
     // lane slots of the inner layout: weight 0, address 0, never the end of a run
-    for (int k = z1 + tid; k < L.z1pad; k += NT) ent1[k] = make_uint4(0u, 0u, 0u, 0u);
+    for (int k = z1 + tid; k < L.z1pad; k += NT) {
+        if (ATOMIC) {   // entries as four arrays of z1pad words, see xmv_chunks
+            uint32_t* words = reinterpret_cast<uint32_t*>(ent1);
+            words[k] = words[L.z1pad + k] = words[2 * L.z1pad + k] = words[3 * L.z1pad + k] = 0u;
+        } else {
+            ent1[k] = make_uint4(0u, 0u, 0u, 0u);
+        }
+    }
     // idle slots: log2 w = -inf, or w = 0 where the entry carries the weight itself
     for (int k = tid; k < len2; k += NT) ent2[k] = make_uint4(0u, 0u, 0u, EK == MGK_EK_POLY ? 0u : 0xff800000u);
 #pragma unroll
@@ -301,9 +337,9 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
     // ---- expand the octiles, one thread per packed nonzero --------------------
     for (int k = tid; k < z1 + g2.nnz; k += NT) {
         if (k < z1)
-            expand_nonzero<true, WEIGHTED, EK>(X, g1, tl1, k, ent1, rowend, n2, prm);
+            expand_nonzero<true, WEIGHTED, EK, ATOMIC>(X, g1, tl1, k, ent1, rowend, n2, prm, L.z1pad);
         else
-            expand_nonzero<false, WEIGHTED, EK>(Y, g2, tl2, k - z1, ent2, nullptr, n2, prm);
+            expand_nonzero<false, WEIGHTED, EK, false>(Y, g2, tl2, k - z1, ent2, nullptr, n2, prm, 0);
     }
 
     // ---- Alg. 1 set-up: M = D_x V_x^{-1}, x = 0, r = b = D_x q_x, z = M^{-1} r,
@@ -375,11 +411,11 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
     while (it < max_iter) {
         // ---- XMV (Alg. 2): y_ii' = sum_{j,j'} A_ij A'_i'j' kappa_e(E_ij,E'_i'j') p_jj'
         switch (nsteps) {
-            case 0: xmv_pass<0, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane); break;
-            case 1: xmv_pass<1, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane); break;
-            case 2: xmv_pass<2, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane); break;
-            case 3: xmv_pass<3, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane); break;
-            default: xmv_pass<4, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane); break;
+            case 0: xmv_pass<0, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane, L.z1pad); break;
+            case 1: xmv_pass<1, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane, L.z1pad); break;
+            case 2: xmv_pass<2, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane, L.z1pad); break;
+            case 3: xmv_pass<3, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane, L.z1pad); break;
+            default: xmv_pass<4, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane, L.z1pad); break;
         }
         __syncthreads();
 
