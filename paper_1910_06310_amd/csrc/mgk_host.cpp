@@ -419,7 +419,7 @@ mgk_status ensure(mgk_ctx* ctx, DevBuf& b, size_t bytes) {
 // "hybrid dense-sparse"): the dense primitive evaluates all 4096 products of a
 // tile pair, the sparse one only nnz * nnz' of them but pays gathers and row
 // sums; the dense one wins when both graphs' tiles are well filled.
-constexpr int kDenseMinNnzPerTile = 46;
+constexpr int kDenseMinNnzPerTile = 53;   // measured crossover on 256-vertex graphs: density 0.82
 
 bool use_dense_tiles(const mgk_ctx* ctx, const MgkGraphDesc& a, const MgkGraphDesc& b) {
     if (ctx->edge_kernel == MGK_EK_KRON_SE || ctx->edge_kernel == MGK_EK_RCONV_SE) return false;
