@@ -283,7 +283,7 @@ __device__ __forceinline__ void rows_sweep(const uint4* inner, int wave, int nwa
 // LDS as a plain array padded to a multiple of four with entries whose kernel value is
 // exactly 0, and are read four at a time: one 16-byte
 // broadcast read serves 4 * CB products, where a read of a whole 16-byte entry per product
-// occupied the LDS four times as long as the gather of p it accompanied.
+// occupied the LDS twice as long as the gather of p it accompanied.
 template <int CB, bool WEIGHTED, int EK>
 __device__ __forceinline__ void rows_pass(const MgkBatchDev& Y, const MgkGraphDesc& g2,
                                           const MgkLargePair& P, const MgkParams& prm,

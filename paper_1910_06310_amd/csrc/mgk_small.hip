@@ -115,7 +115,7 @@ __device__ __forceinline__ int next_set_bit(const uint32_t* bits, int words, int
 // y_ii' = sum_{j,j'} A_ij A'_i'j' kappa_e(E_ij, E'_i'j') p_jj'.  NSTEPS DPP
 // shift-and-add steps sum the lanes of each inner row (rows of up to 2^NSTEPS
 // nonzeros).  Every outer entry is a 16-byte broadcast read, which costs the LDS
-// four times what a conflict-free gather of p does: with CB chunks per pass it is
+// twice what a conflict-free gather of p does: with CB chunks per pass it is
 // read 1/CB as often.
 // ATOMIC: the wave's share may begin and end inside an outer row.  kfirst is the
 // first row end of the share if that row began in the previous wave's share (-1
