@@ -463,11 +463,14 @@ __global__ __launch_bounds__(W * 64) void mgk_pcg_regs(MgkBatchDev X, MgkBatchDe
         //      loop then has a single exit and the register blocks stay in place)
         const float beta = s_rz2 * __builtin_amdgcn_rcpf(rho);
         rho = s_rz2;
+        // written as an instruction with the register of p as destination: the compiler's
+        // own choice accumulates into the register of z and copies it back, EPT moves per
+        // iteration
+        float beta_v = beta;
 #pragma unroll
         for (int m = 0; m < EPT; ++m) {
-            const float pn = __builtin_fmaf(beta, pr[m], zr[m]);
-            pr[m] = pn;
-            p[tid + m * NT] = pn;
+            asm("v_fma_f32 %0, %1, %0, %2" : "+v"(pr[m]) : "v"(beta_v), "v"(zr[m]));
+            p[tid + m * NT] = pr[m];
         }
         __syncthreads();
         if (s_rr <= thresh) { flag = 0; break; }
