@@ -98,8 +98,10 @@ mgk_status mgk_set_edge_kernel_const(mgk_ctx* ctx, float c);
  *   the factor 1 / dim^2 keeps the range inside [0, 1].  dim in 1..4.
  * The last two need batches loaded with the same number of attributes per
  * edge (mgk_load_graphs_attr); a solve with another batch fails with
- * MGK_ESTATE.  Pairs too large for the register-resident on-chip solver are
- * solved with vectors in global memory (poly: all solvers). */
+ * MGK_ESTATE.  All three run in both on-chip solvers and in the sparse
+ * product of the global-memory solver; the dense tile-pair product is built
+ * for poly only (pairs of well-filled graphs take the sparse product with the
+ * other two). */
 mgk_status mgk_set_edge_kernel_poly(mgk_ctx* ctx, int32_t n_coef, const float* coef, float rho);
 mgk_status mgk_set_edge_kernel_kron_se(mgk_ctx* ctx, int32_t dim, const float* length_scale);
 mgk_status mgk_set_edge_kernel_rconv_se(mgk_ctx* ctx, int32_t dim, float length_scale);

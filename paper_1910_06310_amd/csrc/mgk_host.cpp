@@ -71,7 +71,7 @@ struct mgk_batch {
     int gram_jobs_tile_path = 0;   // tile path setting the list was built for
     int gram_jobs_cache = 0;       // product-cache setting the list was built for
     int gram_jobs_sorted = 0;      // schedule setting the list was built for
-    int gram_jobs_streaming = 1;   // whether the edge kernel it was built for runs in every solver
+    int gram_jobs_attr_dim = -1;   // label attributes of the edge kernel it was built for (LDS plan)
 };
 
 struct mgk_ctx {
@@ -165,15 +165,15 @@ int balanced_split(const std::vector<int32_t>& deg, int n, int waves, int32_t* b
     return longest;
 }
 
-// kernels over label attributes are built into the register-resident and the
-// global-memory solver, not into the streaming on-chip one
-bool streaming_ok(const mgk_ctx* ctx) {
-    return ctx->edge_kernel != MGK_EK_KRON_SE && ctx->edge_kernel != MGK_EK_RCONV_SE;
+// attributes per edge label that the edge kernel reads (0 for the kernels on plain
+// scalar labels); the streaming on-chip solver keeps them in LDS for the outer graph
+int attr_dim_of(const mgk_ctx* ctx) {
+    return ctx->edge_kernel == MGK_EK_KRON_SE || ctx->edge_kernel == MGK_EK_RCONV_SE ? ctx->label_dim : 0;
 }
 
 // the batches must carry the number of label attributes the edge kernel reads
 mgk_status check_label_dim(mgk_ctx* ctx, const mgk_batch* X, const mgk_batch* Y) {
-    if (streaming_ok(ctx)) return MGK_OK;
+    if (attr_dim_of(ctx) == 0) return MGK_OK;
     if (X->label_dim != ctx->label_dim || Y->label_dim != ctx->label_dim)
         return fail(ctx, MGK_ESTATE, "edge kernel reads %d label attributes, the batches hold %d and %d",
                     ctx->label_dim, X->label_dim, Y->label_dim);
@@ -240,7 +240,7 @@ int64_t regs_cost(const MgkGraphDesc& o, const MgkGraphDesc& i, int waves) {
 }
 
 PairPlan plan_pair(const MgkGraphDesc& a, const MgkGraphDesc& b, bool may_swap, int forced_waves,
-                   int onchip_limit, bool product_cache, bool streaming_ok) {
+                   int onchip_limit, bool product_cache, int attr_dim) {
     // wave iterations of one XMV: outer nonzeros x 64-lane chunks of the inner layout
     auto passes = [](const MgkGraphDesc& o, const MgkGraphDesc& i) {
         return (int64_t)o.nnz * (i.lane_len / 64) + 2 * (int64_t)o.n * (i.lane_len / 64);
@@ -271,7 +271,6 @@ PairPlan plan_pair(const MgkGraphDesc& a, const MgkGraphDesc& b, bool may_swap, 
             return pl;
         }
     }
-    if (!streaming_ok) return pl;   // this edge kernel runs on chip in the register-resident solver only
     if (forced_waves > 0) {  // requested workgroup size, doubled until the pair fits
         for (int w = forced_waves; w <= 16 && pl.waves == 0; w *= 2)
             for (int e : kEpts)
@@ -283,7 +282,7 @@ PairPlan plan_pair(const MgkGraphDesc& a, const MgkGraphDesc& b, bool may_swap, 
     if (pl.waves == 0) return pl;
     const MgkGraphDesc& o = pl.swap ? b : a;
     const MgkGraphDesc& i = pl.swap ? a : b;
-    pl.lds_words = mgk_small_plan(o.n, i.n, o.nnz, i.lane_len, o.n_tiles, i.n_tiles, pl.waves, pl.ept).total;
+    pl.lds_words = mgk_small_plan(o.n, i.n, o.nnz, i.lane_len, o.n_tiles, i.n_tiles, pl.waves, pl.ept, attr_dim).total;
     if (pl.lds_words * 4 > MGK_LDS_LIMIT_BYTES) pl.waves = pl.ept = 0;
     return pl;
 }
@@ -1176,7 +1175,7 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
         (batch->gram_jobs_waves != ctx->waves || batch->gram_jobs_max_iter != ctx->max_iter ||
          batch->gram_jobs_limit != ctx->onchip_limit || batch->gram_jobs_tile_path != ctx->tile_path ||
          batch->gram_jobs_cache != ctx->product_cache || batch->gram_jobs_sorted != ctx->cost_sorted ||
-         batch->gram_jobs_streaming != (streaming_ok(ctx) ? 1 : 0))) {
+         batch->gram_jobs_attr_dim != attr_dim_of(ctx))) {
         MGK_HIP(ctx, hipStreamSynchronize(stream));  // launch shape changed: rebuild the job list
         MGK_HIP(ctx, hipFree(batch->gram_jobs.dev));
         batch->gram_jobs.dev = nullptr;
@@ -1190,14 +1189,15 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
         // several threads, row i starting at pair i G - i (i - 1) / 2
         std::vector<PairPlan> plans((size_t)(G * (G + 1) / 2));
         {
-            const bool cache = ctx->product_cache != 0, stream_ok = streaming_ok(ctx);
+            const bool cache = ctx->product_cache != 0;
+            const int attr_dim = attr_dim_of(ctx);
             const int forced = ctx->waves, limit = ctx->onchip_limit;
             const int T = (int)std::max<int64_t>(1, std::min<int64_t>({(int64_t)std::thread::hardware_concurrency(), 16, G / 64}));
             auto plan_worker = [&](int t) {
                 for (int64_t i = t; i < G; i += T) {
                     PairPlan* row = plans.data() + (i * G - i * (i - 1) / 2);
                     for (int64_t j = i; j < G; ++j)
-                        row[j - i] = plan_pair(batch->graphs[i], batch->graphs[j], true, forced, limit, cache, stream_ok);
+                        row[j - i] = plan_pair(batch->graphs[i], batch->graphs[j], true, forced, limit, cache, attr_dim);
                 }
             };
             std::vector<std::thread> pool;
@@ -1240,7 +1240,7 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
         batch->gram_jobs_tile_path = ctx->tile_path;
         batch->gram_jobs_cache = ctx->product_cache;
         batch->gram_jobs_sorted = ctx->cost_sorted;
-        batch->gram_jobs_streaming = streaming_ok(ctx) ? 1 : 0;
+        batch->gram_jobs_attr_dim = attr_dim_of(ctx);
         if (st != MGK_OK) return st;
     }
     const MgkOutputs out{K_dev, iters_dev, flag_dev, nullptr, nullptr};
@@ -1268,7 +1268,7 @@ static mgk_status pairs_impl(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n
         const int32_t i = i_host[k], j = j_host[k];
         if (i < 0 || i >= X->n_graphs || j < 0 || j >= Y->n_graphs)
             return fail(ctx, MGK_EINVAL, "pair %lld: graph index out of range", (long long)k);
-        const PairPlan pl = plan_pair(X->graphs[i], Y->graphs[j], true, ctx->waves, ctx->onchip_limit, ctx->product_cache != 0, streaming_ok(ctx));
+        const PairPlan pl = plan_pair(X->graphs[i], Y->graphs[j], true, ctx->waves, ctx->onchip_limit, ctx->product_cache != 0, attr_dim_of(ctx));
         HostJob& hj = jobs[(size_t)k];
         hj.job.g1 = pl.swap ? j : i;
         hj.job.g2 = pl.swap ? i : j;

@@ -150,6 +150,7 @@ __device__ __forceinline__ float mgk_poly_kernel(float d, const float* c) {
 struct MgkSmallPlan {
     int32_t p, y;            // vectors, padded to waves * 64 * ept words each
     int32_t ent1, ent2;      // expanded nonzeros, 4 words each
+    int32_t attr1;           // label attributes of the outer nonzeros, attr_dim arrays of z1pad words
     int32_t rowend;          // bit k set: outer entry k is the last of its row
     int32_t tiles1, tiles2;  // staged octile headers, 4 words each
     int32_t vtx1, vtx2;      // per vertex: d_i, start probability, label
@@ -160,9 +161,10 @@ struct MgkSmallPlan {
     int32_t rowend_words;
 };
 
+// attr_dim: attributes per edge label for the kernels over label attributes, else 0
 static inline MGK_HD MgkSmallPlan mgk_small_plan(int32_t n1, int32_t n2, int32_t z1,
                                                  int32_t lane_len2, int32_t t1, int32_t t2,
-                                                 int32_t waves, int32_t ept) {
+                                                 int32_t waves, int32_t ept, int32_t attr_dim) {
     MgkSmallPlan L;
     const int32_t np = waves * 64 * ept;   // >= n1 * n2: every thread owns ept elements
     (void)n1;
@@ -173,7 +175,8 @@ static inline MGK_HD MgkSmallPlan mgk_small_plan(int32_t n1, int32_t n2, int32_t
     L.p = 0;
     L.y = np;
     L.ent1 = 2 * np;
-    L.ent2 = L.ent1 + 4 * L.z1pad;
+    L.attr1 = L.ent1 + 4 * L.z1pad;
+    L.ent2 = L.attr1 + attr_dim * L.z1pad;
     L.rowend = L.ent2 + 4 * lane_len2;
     L.tiles1 = L.rowend + ((L.rowend_words + 3) & ~3);
     L.tiles2 = L.tiles1 + 4 * t1;

@@ -74,7 +74,7 @@ __device__ __forceinline__ void expand_nonzero(const MgkBatchDev& B, const MgkGr
         const int pos = rp0 + rank;
         v.x = (uint32_t)(col * n_inner * 4);
         v.y = __float_as_uint(EK == MGK_EK_CONST ? w : el);
-        v.z = __float_as_uint(EK == MGK_EK_POLY ? w : WEIGHTED ? __log2f(w) : 0.f);
+        v.z = __float_as_uint((EK == MGK_EK_POLY || EK == MGK_EK_RCONV_SE) ? w : WEIGHTED ? __log2f(w) : 0.f);
         v.w = (uint32_t)(row * n_inner * 4);
         if (PLANES) {
             uint32_t* words = reinterpret_cast<uint32_t*>(ent);
@@ -93,7 +93,7 @@ __device__ __forceinline__ void expand_nonzero(const MgkBatchDev& B, const MgkGr
         v.x = (uint32_t)(row * 4) | (rp.rank << 20) | (rp.cut << 30) | (rp.last << 31);
         v.y = (uint32_t)(col * 4);
         v.z = __float_as_uint(EK == MGK_EK_CONST ? w : el);
-        v.w = __float_as_uint(EK == MGK_EK_POLY ? w : WEIGHTED ? __log2f(w) : 0.f);
+        v.w = __float_as_uint((EK == MGK_EK_POLY || EK == MGK_EK_RCONV_SE) ? w : WEIGHTED ? __log2f(w) : 0.f);
         ent[lp + rank] = v;
     }
 }
@@ -121,15 +121,33 @@ __device__ __forceinline__ int next_set_bit(const uint32_t* bits, int words, int
 // first row end of the share if that row began in the previous wave's share (-1
 // otherwise), force_end says that the share ends inside a row; the sums of both
 // rows are added to y atomically, like those of inner rows cut into several runs.
+// What the kernels over label attributes read beside the entries: attribute a of outer
+// nonzero k, prescaled, at outer[a * z1pad + k] (LDS); attribute a of this lane's inner
+// nonzero of the chunk at inner[a * inner_stride] (global memory, 0 on idle slots).
+struct MgkAttrArgs {
+    const float* outer;
+    const float* inner;
+    int64_t inner_stride;
+    int dim;
+    float scale[MGK_MAX_LABEL_DIM];
+};
+
 template <int CB, int NSTEPS, bool WEIGHTED, int EK, bool ATOMIC>
 __device__ __forceinline__ void xmv_chunks(const uint4* ent1, const uint4* ent2c, const uint32_t* rowend,
                                            const char* pbytes, char* ybytes, int kbeg, int kend,
                                            int kfirst, bool force_end, float ke_c, const float* pc,
-                                           int z1pad) {
+                                           int z1pad, const MgkAttrArgs& at) {
     static_assert(CB == 1 || CB == 2 || CB == 4, "one, two or four chunks per pass");
+    constexpr bool ATTR = EK == MGK_EK_KRON_SE || EK == MGK_EK_RCONV_SE;
     uint32_t ip4[CB], jp4[CB], rank[CB];
     bool last[CB], longrow[CB];
     float el2[CB], lw2[CB], acc[CB];
+    float e2a[CB][MGK_MAX_LABEL_DIM];   // this lane's attributes, prescaled
+#pragma unroll
+    for (int b = 0; b < CB; ++b)
+#pragma unroll
+        for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a)
+            e2a[b][a] = ATTR && a < at.dim ? at.inner[a * at.inner_stride + 64 * b] * at.scale[a] : 0.f;
 #pragma unroll
     for (int b = 0; b < CB; ++b) {
         const uint4 e2 = ent2c[64 * b];
@@ -197,6 +215,31 @@ __device__ __forceinline__ void xmv_chunks(const uint4* ent1, const uint4* ent2c
                     } else if (EK == MGK_EK_POLY) {
                         cu[u][b] = mgk_poly_kernel(el2[b] - __uint_as_float(e1[u].y), pc);
                         if (WEIGHTED) cu[u][b] *= __uint_as_float(e1[u].z);     // A_ij
+                    } else if (EK == MGK_EK_KRON_SE) {
+                        // product of square exponentials over the attributes: one exponent
+                        float t = WEIGHTED ? lw2[b] + __uint_as_float(e1[u].z) : lw2[b];
+#pragma unroll
+                        for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a)
+                            if (a < at.dim) {
+                                const float d = e2a[b][a] - at.outer[a * z1pad + k + u];
+                                t = __builtin_fmaf(-d, d, t);
+                            }
+                        cu[u][b] = __builtin_amdgcn_exp2f(t);
+                    } else if (EK == MGK_EK_RCONV_SE) {
+                        // sum over all pairs of parts; A'_i'j' / D^2 is applied at the row end
+                        float sum = 0.f;
+#pragma unroll
+                        for (int q = 0; q < MGK_MAX_LABEL_DIM; ++q)
+                            if (q < at.dim) {
+                                const float e1q = at.outer[q * z1pad + k + u];
+#pragma unroll
+                                for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a)
+                                    if (a < at.dim) {
+                                        const float d = e2a[b][a] - e1q;
+                                        sum += __builtin_amdgcn_exp2f(-d * d);
+                                    }
+                            }
+                        cu[u][b] = WEIGHTED ? sum * __uint_as_float(e1[u].z) : sum;
                     } else {
                         cu[u][b] = WEIGHTED ? __uint_as_float(e1[u].y) : 1.f;  // A_ij
                     }
@@ -215,6 +258,7 @@ __device__ __forceinline__ void xmv_chunks(const uint4* ent1, const uint4* ent2c
                     for (int b = 0; b < CB; ++b) {
                         if (EK == MGK_EK_CONST) acc[b] *= ke_c * el2[b];  // el2 = A'_i'j' (0 on idle lanes)
                         if (EK == MGK_EK_POLY) acc[b] *= lw2[b];           // lw2 = A'_i'j' (0 on idle lanes)
+                        if (EK == MGK_EK_RCONV_SE) acc[b] *= lw2[b] * (1.0f / (float)(at.dim * at.dim));
                     }
                     if constexpr (CB == 1) {
                         if (NSTEPS > 0) acc[0] = shr_fmac<1>(acc[0], m1[0]);
@@ -256,22 +300,27 @@ template <int NSTEPS, bool WEIGHTED, int EK, bool ATOMIC>
 __device__ __forceinline__ void xmv_pass(const uint4* ent1, const uint4* ent2, const uint32_t* rowend,
                                          const char* pbytes, char* ybytes, int len2, int kbeg,
                                          int kend, int kfirst, bool force_end, float ke_c,
-                                         const float* pc, int lane, int z1pad) {
+                                         const float* pc, int lane, int z1pad, MgkAttrArgs at) {
     // A kernel's register count is that of its widest path: four chunks per pass only in
-    // the kernels for graphs with long rows, whose inner layouts have many chunks.
-    constexpr int CBMAX = ATOMIC ? 4 : 2;
+    // the kernels for graphs with long rows, whose inner layouts have many chunks; one for
+    // the kernels over label attributes, which hold up to four attributes per chunk.
+    constexpr bool ATTR = EK == MGK_EK_KRON_SE || EK == MGK_EK_RCONV_SE;
+    constexpr int CBMAX = ATTR ? 1 : ATOMIC ? 4 : 2;
+    const float* inner0 = at.inner;   // attribute 0 of lane slot `lane`
     int c = 0;
     if constexpr (CBMAX >= 4)
         for (; c + 256 <= len2; c += 256)
             xmv_chunks<4, NSTEPS, WEIGHTED, EK, ATOMIC>(ent1, ent2 + c + lane, rowend, pbytes, ybytes,
-                                                        kbeg, kend, kfirst, force_end, ke_c, pc, z1pad);
+                                                        kbeg, kend, kfirst, force_end, ke_c, pc, z1pad, at);
     if constexpr (CBMAX >= 2)
         for (; c + 128 <= len2; c += 128)
             xmv_chunks<2, NSTEPS, WEIGHTED, EK, ATOMIC>(ent1, ent2 + c + lane, rowend, pbytes, ybytes,
-                                                        kbeg, kend, kfirst, force_end, ke_c, pc, z1pad);
-    for (; c < len2; c += 64)
+                                                        kbeg, kend, kfirst, force_end, ke_c, pc, z1pad, at);
+    for (; c < len2; c += 64) {
+        if (ATTR) at.inner = inner0 + c;
         xmv_chunks<1, NSTEPS, WEIGHTED, EK, ATOMIC>(ent1, ent2 + c + lane, rowend, pbytes, ybytes,
-                                                    kbeg, kend, kfirst, force_end, ke_c, pc, z1pad);
+                                                    kbeg, kend, kfirst, force_end, ke_c, pc, z1pad, at);
+    }
 }
 
 // ATOMIC: the inner graph has rows longer than 16 nonzeros; the runs of those rows are
@@ -287,13 +336,16 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
     const MgkGraphDesc g1 = X.graphs[job.g1];
     const MgkGraphDesc g2 = Y.graphs[job.g2];
     const int n1 = g1.n, n2 = g2.n, N = n1 * n2, z1 = g1.nnz, len2 = g2.lane_len;
-    const MgkSmallPlan L = mgk_small_plan(n1, n2, z1, len2, g1.n_tiles, g2.n_tiles, WAVES, EPT);
+    constexpr bool ATTR = EK == MGK_EK_KRON_SE || EK == MGK_EK_RCONV_SE;   // labels with several attributes
+    const int attr_dim = ATTR ? prm.label_dim : 0;
+    const MgkSmallPlan L = mgk_small_plan(n1, n2, z1, len2, g1.n_tiles, g2.n_tiles, WAVES, EPT, attr_dim);
 
     float* p = reinterpret_cast<float*>(lds + L.p);
     float* y = reinterpret_cast<float*>(lds + L.y);
     uint4* ent1 = reinterpret_cast<uint4*>(lds + L.ent1);
     uint4* ent2 = reinterpret_cast<uint4*>(lds + L.ent2);
     uint32_t* rowend = lds + L.rowend;
+    float* oattr = reinterpret_cast<float*>(lds + L.attr1);
     MgkTile* tl1 = reinterpret_cast<MgkTile*>(lds + L.tiles1);
     MgkTile* tl2 = reinterpret_cast<MgkTile*>(lds + L.tiles2);
     float* dq1 = reinterpret_cast<float*>(lds + L.vtx1);           // d_i = rowsum + q
@@ -328,8 +380,16 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
             ent1[k] = make_uint4(0u, 0u, 0u, 0u);
         }
     }
+    // label attributes of the outer nonzeros (CSR order, as the entries), prescaled
+    if (ATTR) {
+        for (int a = 0; a < attr_dim; ++a) {
+            const float sc = prm.attr_scale[EK == MGK_EK_RCONV_SE ? 0 : a];
+            for (int k = tid; k < L.z1pad; k += NT)
+                oattr[a * L.z1pad + k] = k < z1 ? X.attr_outer[(int64_t)a * X.nnz_total + g1.zoff + k] * sc : 0.f;
+        }
+    }
     // idle slots: log2 w = -inf, or w = 0 where the entry carries the weight itself
-    for (int k = tid; k < len2; k += NT) ent2[k] = make_uint4(0u, 0u, 0u, EK == MGK_EK_POLY ? 0u : 0xff800000u);
+    for (int k = tid; k < len2; k += NT) ent2[k] = make_uint4(0u, 0u, 0u, (EK == MGK_EK_POLY || EK == MGK_EK_RCONV_SE) ? 0u : 0xff800000u);
 #pragma unroll
     for (int m = 0; m < EPT; ++m) y[tid + m * NT] = 0.f;  // entries no row pair reaches stay 0
     __syncthreads();
@@ -405,17 +465,24 @@ __global__ __launch_bounds__(WAVES * 64) void mgk_pcg_small(
     const char* pbytes = reinterpret_cast<const char*>(p);
     char* ybytes = reinterpret_cast<char*>(y);
     const float ke_c = prm.ke_const;
+    MgkAttrArgs at;
+    at.outer = oattr;
+    at.inner = Y.attr_inner + g2.loff + lane;
+    at.inner_stride = Y.lanes_total;
+    at.dim = attr_dim;
+#pragma unroll
+    for (int a = 0; a < MGK_MAX_LABEL_DIM; ++a) at.scale[a] = prm.attr_scale[EK == MGK_EK_RCONV_SE ? 0 : a];
 
     int it = 0;
     int flag = 1;
     while (it < max_iter) {
         // ---- XMV (Alg. 2): y_ii' = sum_{j,j'} A_ij A'_i'j' kappa_e(E_ij,E'_i'j') p_jj'
         switch (nsteps) {
-            case 0: xmv_pass<0, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane, L.z1pad); break;
-            case 1: xmv_pass<1, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane, L.z1pad); break;
-            case 2: xmv_pass<2, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane, L.z1pad); break;
-            case 3: xmv_pass<3, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane, L.z1pad); break;
-            default: xmv_pass<4, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane, L.z1pad); break;
+            case 0: xmv_pass<0, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane, L.z1pad, at); break;
+            case 1: xmv_pass<1, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane, L.z1pad, at); break;
+            case 2: xmv_pass<2, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane, L.z1pad, at); break;
+            case 3: xmv_pass<3, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane, L.z1pad, at); break;
+            default: xmv_pass<4, WEIGHTED, EK, ATOMIC>(ent1, ent2, rowend, pbytes, ybytes, len2, kbeg, kend, kfirst, force_end, ke_c, prm.poly_c, lane, L.z1pad, at); break;
         }
         __syncthreads();
 
@@ -532,7 +599,17 @@ hipError_t launch_we(bool weighted, bool atomic_rows, int ek, const MgkBatchDev&
         if (atomic_rows) MGK_GO(false, MGK_EK_POLY, true);
         MGK_GO(false, MGK_EK_POLY, false);
     }
-    if (ek != MGK_EK_CONST) return hipErrorInvalidValue;   // kernels over label attributes do not run here
+    if (ek == MGK_EK_KRON_SE) {
+        if (weighted) { if (atomic_rows) MGK_GO(true, MGK_EK_KRON_SE, true); MGK_GO(true, MGK_EK_KRON_SE, false); }
+        if (atomic_rows) MGK_GO(false, MGK_EK_KRON_SE, true);
+        MGK_GO(false, MGK_EK_KRON_SE, false);
+    }
+    if (ek == MGK_EK_RCONV_SE) {
+        if (weighted) { if (atomic_rows) MGK_GO(true, MGK_EK_RCONV_SE, true); MGK_GO(true, MGK_EK_RCONV_SE, false); }
+        if (atomic_rows) MGK_GO(false, MGK_EK_RCONV_SE, true);
+        MGK_GO(false, MGK_EK_RCONV_SE, false);
+    }
+    if (ek != MGK_EK_CONST) return hipErrorInvalidValue;
     if (weighted) { if (atomic_rows) MGK_GO(true, MGK_EK_CONST, true); MGK_GO(true, MGK_EK_CONST, false); }
     if (atomic_rows) MGK_GO(false, MGK_EK_CONST, true);
     MGK_GO(false, MGK_EK_CONST, false);

@@ -97,16 +97,19 @@ def test_attribute_kernels_on_chip_and_in_global_memory(torch, solver, kind, wei
     wa = W.with_label_attributes(wb, rng, dim, 0.3, prm)
     pi, pj = W.gram_pairs(8)
     ref = C.pairs(wa, pi, pj, tier=0)
-    for kw in (dict(), dict(onchip=0), dict(onchip=0, tile_path=M.TILE_SPARSE_GATHER), dict(reorder=M.REORDER_NONE)):
+    # register-resident, streaming on chip, both sparse products in global memory
+    for kw in (dict(), dict(cache=False), dict(onchip=0), dict(onchip=0, tile_path=M.TILE_SPARSE_GATHER),
+               dict(reorder=M.REORDER_NONE)):
         got = pairs_on(torch, solver, wa, pi, pj, **kw)
         np.testing.assert_allclose(got, ref, rtol=RTOL, err_msg=str(kw))
-    # larger, denser graphs: on chip nothing fits, the sparse product in global memory runs
+    # larger, denser graphs (rows longer than a lane group): streaming kernel with atomic
+    # row sums on chip, the sparse products in global memory
     er = W.erdos_renyi_batch(np.random.default_rng(5), 4, 24, 40, 0.5, (0.3, 1.3) if weighted else (1.0, 1.0),
                              (0.0, 2.0), 3, prm)
     ea = W.with_label_attributes(er, np.random.default_rng(6), dim, 0.5, prm)
     pi, pj = W.gram_pairs(4)
     ref = C.pairs(ea, pi, pj, tier=1)
-    for kw in (dict(), dict(tile_path=M.TILE_SPARSE_GATHER)):
+    for kw in (dict(), dict(onchip=0), dict(onchip=0, tile_path=M.TILE_SPARSE_GATHER)):
         got = pairs_on(torch, solver, ea, pi, pj, **kw)
         np.testing.assert_allclose(got, ref, rtol=RTOL, err_msg=str(kw))
 
