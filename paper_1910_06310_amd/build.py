@@ -17,7 +17,8 @@ OBJ_DIR = os.path.join(HERE, "_build")
 
 # (source, output tag, extra flags); the on-chip solver is compiled once per
 # workgroup size so the translation units build in parallel
-DEVICE_SOURCES = [("mgk_small.hip", "w%d" % w, ["-DMGK_SMALL_WAVES=%d" % w]) for w in (1, 2, 4, 8, 16)]
+DEVICE_SOURCES = [("mgk_small.hip", "w%d" % w, ["-DMGK_SMALL_WAVES=%d" % w]) for w in (4, 16, 8, 1, 2)]
+DEVICE_SOURCES.append(("mgk_small.hip", "w4fine", ["-DMGK_SMALL_WAVES=4", "-DMGK_SMALL_FINE"]))
 DEVICE_SOURCES += [("mgk_regs.hip", "w%dc%d" % (w, c), ["-DMGK_REGS_WAVES=%d" % w, "-DMGK_REGS_CHUNKS=%d" % c])
                    for w in (4, 8) for c in (1, 2)]
 DEVICE_SOURCES.append(("mgk_large.hip", "all", []))

@@ -24,6 +24,11 @@ MGK_DECL_SMALL(4)
 MGK_DECL_SMALL(8)
 MGK_DECL_SMALL(16)
 #undef MGK_DECL_SMALL
+// four wavefronts with 6, 10 or 14 elements per thread (a translation unit of its own)
+hipError_t mgk_launch_small_w4_fine(int ept, bool weighted, bool atomic_rows, const MgkBatchDev& X,
+                                    const MgkBatchDev& Y, const MgkJob* jobs_dev, int n_jobs,
+                                    const MgkParams& prm, size_t lds_bytes, const MgkOutputs& out,
+                                    hipStream_t stream);
 
 static inline hipError_t mgk_launch_small(int waves, int ept, bool weighted, bool atomic_rows, const MgkBatchDev& X,
                                           const MgkBatchDev& Y, const MgkJob* jobs_dev, int n_jobs,
@@ -32,7 +37,10 @@ static inline hipError_t mgk_launch_small(int waves, int ept, bool weighted, boo
     switch (waves) {
         case 1: return mgk_launch_small_w1(ept, weighted, atomic_rows, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
         case 2: return mgk_launch_small_w2(ept, weighted, atomic_rows, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
-        case 4: return mgk_launch_small_w4(ept, weighted, atomic_rows, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+        case 4:
+            if (ept == 6 || ept == 10 || ept == 14)
+                return mgk_launch_small_w4_fine(ept, weighted, atomic_rows, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+            return mgk_launch_small_w4(ept, weighted, atomic_rows, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
         case 8: return mgk_launch_small_w8(ept, weighted, atomic_rows, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
         case 16: return mgk_launch_small_w16(ept, weighted, atomic_rows, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
         default: return hipErrorInvalidValue;

@@ -625,21 +625,30 @@ hipError_t launch_we(bool weighted, bool atomic_rows, int ek, const MgkBatchDev&
 #define MGK_CAT2(a, b) a##b
 #define MGK_CAT(a, b) MGK_CAT2(a, b)
 
-// One translation unit per workgroup size keeps the build parallel.
+// One translation unit per workgroup size keeps the build parallel; the finer register
+// blocks of the four-wavefront size (6, 10, 14 elements per thread: the common size class)
+// are a unit of their own, compiled with -DMGK_SMALL_FINE.
+#ifdef MGK_SMALL_FINE
+hipError_t mgk_launch_small_w4_fine(
+    int ept, bool weighted, bool atomic_rows, const MgkBatchDev& X, const MgkBatchDev& Y,
+    const MgkJob* jobs_dev, int n_jobs, const MgkParams& prm, size_t lds_bytes,
+    const MgkOutputs& out, hipStream_t stream) {
+    static_assert(MGK_SMALL_WAVES == 4, "finer register blocks exist for four wavefronts only");
+    if (n_jobs <= 0) return hipSuccess;
+    switch (ept) {
+        case 6: return launch_we<4, 6>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+        case 10: return launch_we<4, 10>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+        case 14: return launch_we<4, 14>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+#else
 hipError_t MGK_CAT(mgk_launch_small_w, MGK_SMALL_WAVES)(
     int ept, bool weighted, bool atomic_rows, const MgkBatchDev& X, const MgkBatchDev& Y,
     const MgkJob* jobs_dev, int n_jobs, const MgkParams& prm, size_t lds_bytes,
     const MgkOutputs& out, hipStream_t stream) {
     if (n_jobs <= 0) return hipSuccess;
     constexpr int W = MGK_SMALL_WAVES;
-    if constexpr (W == 4) {  // the common size class gets a finer choice of register block
-        switch (ept) {
-            case 6: return launch_we<W, 6>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
-            case 10: return launch_we<W, 10>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
-            case 14: return launch_we<W, 14>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
-            default: break;
-        }
-    }
     if constexpr (W == 16) {  // 16 x 64 x 10 elements hold a pair of 96-vertex graphs
         if (ept == 10)
             return launch_we<W, 10>(weighted, atomic_rows, prm.edge_kernel, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
@@ -652,3 +661,4 @@ hipError_t MGK_CAT(mgk_launch_small_w, MGK_SMALL_WAVES)(
         default: return hipErrorInvalidValue;
     }
 }
+#endif
