@@ -1012,7 +1012,7 @@ mgk_status mgk_load_graphs_attr(mgk_ctx* ctx, int32_t n_graphs, const int64_t* v
             const int run4 = balanced_split(deg, n, 4, bounds);
             const int run8 = balanced_split(deg, n, 8, bounds + MGK_REGS_SPLIT_W8);
             regs_split.insert(regs_split.end(), bounds, bounds + MGK_REGS_SPLIT_STRIDE);
-            gd.regs_runs = std::min(run4, 0xffff) | (std::min(run8, 0xffff) << 16);
+            gd.regs_runs = (int32_t)((uint32_t)std::min(run4, 0xffff) | ((uint32_t)std::min(run8, 0xffff) << 16));
         }
         lanes_total += gd.lane_len;
         if (lanes_total >= (int64_t)1 << 31) return fail(ctx, MGK_ELIMIT, "batch too large for 32-bit offsets");
