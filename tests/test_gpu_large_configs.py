@@ -130,3 +130,16 @@ def test_geometric_graphs_reduced_size_all_pairs(torch, solver):
     K, it, fl = run_pairs(torch, solver, B, pi, pj)
     np.testing.assert_allclose(K, C.pairs(wb, pi, pj, tier=1), rtol=RTOL)
     assert (fl == 0).all()
+
+
+def test_geometric_graphs_with_rows_of_p_not_a_multiple_of_four(torch, solver):
+    """n' = 259: the rows of p do not start on 16-byte boundaries, so the sparse product
+    stages them element by element, several rounds per thread."""
+    wb = W.config3(3, 259)
+    solver.configure(wb.params)
+    solver.set_solver(1e-6, 0)
+    B = solver.load_batch(wb)
+    pi, pj = W.gram_pairs(3)
+    K, it, fl = run_pairs(torch, solver, B, pi, pj)
+    np.testing.assert_allclose(K, C.pairs(wb, pi, pj, tier=1), rtol=RTOL)
+    assert (fl == 0).all()
