@@ -165,6 +165,40 @@ def test_nonuniform_start_probability():
         O.kernel_value(g1, g2, q, h, ls, p1=p1, p2=p2), rel=1e-10)
 
 
+def test_c_oracle_start_probabilities_over_a_batch():
+    """The C edition slices a batch-wide array of starting probabilities per graph.  Four
+    graphs of different sizes with non-uniform p: every pair, both tiers, against the numpy
+    definition, and the explicit walk enumeration of Appendix A (first equation) must give
+    the leading terms of each value.  A slice shifted by one vertex changes every number
+    here (the sizes differ and no two probabilities are equal)."""
+    from mgk_workloads.generators import _assemble
+    rng = np.random.default_rng(31)
+    sizes = [3, 4, 2, 5]
+    graphs = [random_graph(rng, n, prob=0.8) for n in sizes]
+    q, h, ls = 0.25, 0.5, 0.9
+    wb = _assemble(graphs, W.KernelParams(q=q, h=h, length_scale=ls), "start")
+    sp = np.concatenate([(lambda v: v / v.sum())(rng.uniform(0.2, 1.0, n)) for n in sizes])
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    pi, pj = W.gram_pairs(len(sizes))
+    d = C.pairs(wb, pi, pj, tier=0, start_prob=sp)
+    m = C.pairs(wb, pi, pj, tier=1, start_prob=sp)
+    for k, (i, j) in enumerate(zip(pi, pj)):
+        p1, p2 = sp[off[i]:off[i + 1]], sp[off[j]:off[j + 1]]
+        gi, gj = wb.graph(int(i)), wb.graph(int(j))
+        ref = O.kernel_value(gi, gj, q, h, ls, p1=p1, p2=p2)
+        assert d[k] == pytest.approx(ref, rel=1e-12)
+        assert m[k] == pytest.approx(ref, rel=1e-10)
+        # walks of up to 3 vertices: the first three terms of the series whose sum is K;
+        # the rest is positive and bounded by the geometric tail (1 - q/d_max)^2 per step
+        walks = O.kernel_walks(gi, gj, q, h, ls, max_len=3, p1=p1, p2=p2)
+        assert walks.sum() < d[k]
+        terms = O.series_terms(gi, gj, q, h, ls, n_terms=200, p1=p1, p2=p2)
+        np.testing.assert_allclose(walks, terms[:3], rtol=1e-12)
+        assert terms.sum() == pytest.approx(d[k], rel=1e-9)
+    # uniform p is a different number on every pair
+    assert np.all(np.abs(C.pairs(wb, pi, pj, tier=0) - d) > 1e-6 * d)
+
+
 # ---- independent assembly with library Kronecker products ------------------
 def test_dense_system_matches_kron_construction():
     rng = np.random.default_rng(3)
