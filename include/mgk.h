@@ -33,7 +33,9 @@
  *    such pair, plus expanded nonzero lists of the batches).  Such pairs are
  *    solved in groups of at most 4096 pairs and 8 GiB of vectors.
  *  - Non-convergence is data, not an error: the pair's flag is set to 1 and the
- *    value of the last iterate is still written.
+ *    value of the last iterate is still written.  Flag 2 with a NaN value marks
+ *    a pair that a kernel refused because it did not fit the launch shape the
+ *    host chose for it (an internal error; it is never solved in part).
  *  - Precision: fp32 on the device.  Product index of (i,i') is i*n'+i'.
  */
 #ifndef MGK_H
@@ -203,6 +205,15 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev,
 mgk_status mgk_pairs(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
                      const int32_t* i_host, const int32_t* j_host, float* K_dev,
                      int32_t* iters_dev, int32_t* flag_dev, void* stream);
+
+/* mgk_pairs_dev: mgk_pairs with the index arrays in device memory (int32, on the
+ * ctx's device, written before work enqueued on `stream` so far completes).  The
+ * launch shape of a pair is chosen on the host from the sizes of its two graphs
+ * (Section V-B), so the indices are copied to the host first: the call
+ * synchronises `stream` once before it enqueues the solve. */
+mgk_status mgk_pairs_dev(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
+                         const int32_t* i_dev, const int32_t* j_dev, float* K_dev,
+                         int32_t* iters_dev, int32_t* flag_dev, void* stream);
 
 /* mgk_pairs_nodal: as mgk_pairs, and also the node-wise similarity (Section I):
  * the solution x = V_x r_inf of Eq. 1 itself.  For pair k the n x n' values, in

@@ -28,7 +28,7 @@ EXPORTS = [
     "mgk_set_stop_prob", "mgk_set_solver", "mgk_set_tile_path", "mgk_set_launch",
     "mgk_set_onchip_limit", "mgk_set_product_cache", "mgk_set_schedule",
     "mgk_load_graphs", "mgk_free_batch", "mgk_batch_stats", "mgk_batch_permutation",
-    "mgk_batch_get_tiles", "mgk_gram", "mgk_pairs", "mgk_pairs_nodal", "mgk_normalize_gram",
+    "mgk_batch_get_tiles", "mgk_gram", "mgk_pairs", "mgk_pairs_dev", "mgk_pairs_nodal", "mgk_normalize_gram",
 ]
 
 
@@ -263,6 +263,16 @@ class Solver:
         self._check(load_library().mgk_pairs(
             self._h, X._h, Y._h, n, pi, pj, _dev_ptr(K, "float32", n),
             _dev_ptr(iters, "int32", n), _dev_ptr(flags, "int32", n), _stream_ptr(stream)))
+
+    def pairs_dev(self, X: Batch, Y: Batch, i_idx, j_idx, K, iters=None, flags=None, stream=None):
+        """As pairs(), with the two index arrays as int32 cuda tensors."""
+        n = int(i_idx.numel())
+        if int(j_idx.numel()) != n:
+            raise ValueError("index arrays differ in length")
+        self._check(load_library().mgk_pairs_dev(
+            self._h, X._h, Y._h, n, _dev_ptr(i_idx, "int32", n), _dev_ptr(j_idx, "int32", n),
+            _dev_ptr(K, "float32", n), _dev_ptr(iters, "int32", n), _dev_ptr(flags, "int32", n),
+            _stream_ptr(stream)))
 
     def pairs_nodal(self, X: Batch, Y: Batch, i_idx, j_idx, K, x, x_off, iters=None, flags=None,
                     stream=None):

@@ -49,7 +49,18 @@ def _run(cmd):
         sys.stderr.write(out + "\n")
 
 
-def build(verbose: bool = False) -> str:
+def _stale(obj: str, src: str, incremental: bool) -> bool:
+    """Without `incremental` everything is compiled.  With it, an object is kept when it is
+    newer than its source, every header beside it, the public header and this file."""
+    if not incremental or not os.path.exists(obj):
+        return True
+    deps = [src, os.path.abspath(__file__), os.path.join(os.path.dirname(HERE), "include", "mgk.h")]
+    deps += [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
+    t = os.path.getmtime(obj)
+    return any(os.path.getmtime(d) > t for d in deps)
+
+
+def build(verbose: bool = False, incremental: bool = False) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
     hipcc = _hipcc()
     inc = ["-I" + os.path.join(os.path.dirname(HERE), "include"), "-I" + CSRC,
@@ -57,14 +68,17 @@ def build(verbose: bool = False) -> str:
     objs, cmds = [], []
     for src, tag, extra in DEVICE_SOURCES:
         obj = os.path.join(OBJ_DIR, "%s.%s.o" % (src, tag))
-        cmds.append([hipcc] + HIP_FLAGS + extra + inc + ["-c", os.path.join(CSRC, src), "-o", obj])
+        if _stale(obj, os.path.join(CSRC, src), incremental):
+            cmds.append([hipcc] + HIP_FLAGS + extra + inc + ["-c", os.path.join(CSRC, src), "-o", obj])
         objs.append(obj)
     for src in HOST_SOURCES:
         obj = os.path.join(OBJ_DIR, src + ".o")
-        cmds.append(["g++"] + HOST_FLAGS + inc + ["-c", os.path.join(CSRC, src), "-o", obj])
+        if _stale(obj, os.path.join(CSRC, src), incremental):
+            cmds.append(["g++"] + HOST_FLAGS + inc + ["-c", os.path.join(CSRC, src), "-o", obj])
         objs.append(obj)
-    with ThreadPoolExecutor(max_workers=min(8, len(cmds))) as pool:
-        list(pool.map(_run, cmds))
+    if cmds:
+        with ThreadPoolExecutor(max_workers=min(8, len(cmds))) as pool:
+            list(pool.map(_run, cmds))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-pthread", "-o", LIB] + objs)
     if verbose:
         print("built", LIB)
@@ -72,4 +86,4 @@ def build(verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    build(verbose=True)
+    build(verbose=True, incremental="--incremental" in sys.argv[1:])

@@ -3,13 +3,16 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
 #include <new>
 #include <numeric>
+#include <stdexcept>
 #include <string>
+#include <system_error>
 #include <thread>
 #include <vector>
 
@@ -103,14 +106,14 @@ struct mgk_ctx {
 
 namespace {
 
-mgk_status fail(mgk_ctx* ctx, mgk_status st, const char* fmt, ...) {
+mgk_status fail(mgk_ctx* ctx, mgk_status st, const char* fmt, ...) noexcept {
     if (ctx) {
         char buf[512];
         va_list ap;
         va_start(ap, fmt);
         vsnprintf(buf, sizeof buf, fmt, ap);
         va_end(ap);
-        ctx->err = buf;
+        try { ctx->err = buf; } catch (...) { ctx->err.clear(); }   // capacity is reserved at creation
     }
     return st;
 }
@@ -121,6 +124,41 @@ mgk_status fail(mgk_ctx* ctx, mgk_status st, const char* fmt, ...) {
         if (e_ != hipSuccess)                                                           \
             return fail(ctx, MGK_EDEVICE, "%s failed: %s", #call, hipGetErrorString(e_)); \
     } while (0)
+
+// Runs `body` and turns any C++ exception into a status, so that nothing unwinds
+// across the C ABI.  The message is stored without allocating when memory is short.
+template <class F>
+mgk_status guarded(mgk_ctx* ctx, F&& body) noexcept {
+    mgk_status st = MGK_EINVAL;
+    const char* what = "unexpected exception";
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        st = MGK_ENOMEM;
+        what = "out of host memory";
+    } catch (const std::length_error&) {
+        st = MGK_ELIMIT;
+        what = "request exceeds the largest host array";
+    } catch (const std::system_error&) {
+        st = MGK_ENOMEM;
+        what = "could not start a worker thread";
+    } catch (...) {
+    }
+    if (ctx) {
+        try { ctx->err = what; } catch (...) { ctx->err.clear(); }
+    }
+    return st;
+}
+
+// Worker threads that are always joined, also when starting one of them throws.
+struct JoiningThreads {
+    std::vector<std::thread> t;
+    ~JoiningThreads() { join(); }
+    void join() {
+        for (std::thread& th : t)
+            if (th.joinable()) th.join();
+    }
+};
 
 template <class T>
 size_t append_bytes(std::vector<char>& blob, const std::vector<T>& v) {
@@ -633,6 +671,7 @@ mgk_status mgk_create(mgk_ctx** out, int device) {
     mgk_ctx* ctx = new (std::nothrow) mgk_ctx();
     if (!ctx) return MGK_ENOMEM;
     ctx->device = device;
+    try { ctx->err.reserve(512); } catch (...) { delete ctx; return MGK_ENOMEM; }
     if (device >= 0 && hipSetDevice(device) != hipSuccess) { delete ctx; return MGK_EDEVICE; }
     *out = ctx;
     return MGK_OK;
@@ -783,11 +822,28 @@ mgk_status mgk_load_graphs(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_of
                                 1, edge_label, reorder, out);
 }
 
+static mgk_status load_graphs_body(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_off,
+                                   const int32_t* vtx_label, const float* start_prob,
+                                   const int64_t* edge_off, const int32_t* src, const int32_t* dst,
+                                   const float* weight, int32_t label_dim, const float* edge_label,
+                                   int32_t reorder, mgk_batch** out);
+
 mgk_status mgk_load_graphs_attr(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_off,
                                 const int32_t* vtx_label, const float* start_prob,
                                 const int64_t* edge_off, const int32_t* src, const int32_t* dst,
                                 const float* weight, int32_t label_dim, const float* edge_label,
                                 int32_t reorder, mgk_batch** out) {
+    return guarded(ctx, [&] {
+        return load_graphs_body(ctx, n_graphs, vtx_off, vtx_label, start_prob, edge_off, src, dst, weight,
+                                label_dim, edge_label, reorder, out);
+    });
+}
+
+static mgk_status load_graphs_body(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_off,
+                                   const int32_t* vtx_label, const float* start_prob,
+                                   const int64_t* edge_off, const int32_t* src, const int32_t* dst,
+                                   const float* weight, int32_t label_dim, const float* edge_label,
+                                   int32_t reorder, mgk_batch** out) {
     if (!ctx || !out) return MGK_EINVAL;
     *out = nullptr;
     if (label_dim < 1 || label_dim > MGK_MAX_LABEL_DIM)
@@ -797,6 +853,11 @@ mgk_status mgk_load_graphs_attr(mgk_ctx* ctx, int32_t n_graphs, const int64_t* v
     if (reorder < MGK_REORDER_NONE || reorder > MGK_REORDER_RCM)
         return fail(ctx, MGK_EINVAL, "unknown reorder mode %d", reorder);
     if (vtx_off[0] != 0 || edge_off[0] != 0) return fail(ctx, MGK_EINVAL, "offset arrays must start at 0");
+    // every array below is sized by the last offsets: they must bound all the others
+    for (int32_t g = 0; g < n_graphs; ++g) {
+        if (vtx_off[g + 1] <= vtx_off[g]) return fail(ctx, MGK_EINVAL, "graph %d has no vertices", g);
+        if (edge_off[g + 1] < edge_off[g]) return fail(ctx, MGK_EINVAL, "graph %d: edge offsets decrease", g);
+    }
     const int64_t tot_v = vtx_off[n_graphs], tot_e = edge_off[n_graphs];
     if (tot_v > 0 && !vtx_label) return fail(ctx, MGK_EINVAL, "vtx_label is null");
     if (tot_e > 0 && (!src || !dst)) return fail(ctx, MGK_EINVAL, "src/dst is null");
@@ -842,6 +903,7 @@ mgk_status mgk_load_graphs_attr(mgk_ctx* ctx, int32_t n_graphs, const int64_t* v
     if (reorder != MGK_REORDER_NONE && n_graphs >= 8) {
         const int T = (int)std::max(1u, std::min({std::thread::hardware_concurrency(), 16u, (unsigned)n_graphs / 4u}));
         auto order_worker = [&](int t) {
+          try {   // a worker that runs out of memory stops; the loop below orders what it left
             MgkAdj a;
             std::vector<int32_t> cur;
             for (int32_t g = t; g < n_graphs; g += T) {
@@ -868,11 +930,13 @@ mgk_status mgk_load_graphs_attr(mgk_ctx* ctx, int32_t n_graphs, const int64_t* v
                 for (int i = 0; i < n; ++i) std::sort(a.idx.begin() + a.ptr[i], a.idx.begin() + a.ptr[i + 1]);
                 pre_perm[(size_t)g] = reorder == MGK_REORDER_PBR ? mgk_order_pbr(a, kTile) : mgk_order_rcm(a);
             }
+          } catch (...) {
+          }
         };
-        std::vector<std::thread> pool;
-        for (int t = 1; t < T; ++t) pool.emplace_back(order_worker, t);
+        JoiningThreads pool;
+        for (int t = 1; t < T; ++t) pool.t.emplace_back(order_worker, t);
         order_worker(0);
-        for (std::thread& th : pool) th.join();
+        pool.join();
     }
 
     for (int32_t g = 0; g < n_graphs; ++g) {
@@ -1161,8 +1225,16 @@ mgk_status mgk_batch_get_tiles(const mgk_batch* b, int32_t g, int32_t* n_tiles, 
 }
 
 // ----------------------------------------------------------------------------
+static mgk_status gram_body(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters_dev,
+                            int32_t* flag_dev, void* stream_);
+
 mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters_dev,
                     int32_t* flag_dev, void* stream_) {
+    return guarded(ctx, [&] { return gram_body(ctx, batch, K_dev, iters_dev, flag_dev, stream_); });
+}
+
+static mgk_status gram_body(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters_dev,
+                            int32_t* flag_dev, void* stream_) {
     if (!ctx || !batch || !K_dev) return fail(ctx, MGK_EINVAL, "null argument");
     if (batch->owner != ctx) return fail(ctx, MGK_ESTATE, "batch belongs to another context");
     if (ctx->device < 0) return fail(ctx, MGK_ESTATE, "host-only context cannot solve");
@@ -1193,17 +1265,17 @@ mgk_status mgk_gram(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_t* iters
             const int attr_dim = attr_dim_of(ctx);
             const int forced = ctx->waves, limit = ctx->onchip_limit;
             const int T = (int)std::max<int64_t>(1, std::min<int64_t>({(int64_t)std::thread::hardware_concurrency(), 16, G / 64}));
-            auto plan_worker = [&](int t) {
+            auto plan_worker = [&](int t) {   // allocates nothing, cannot throw
                 for (int64_t i = t; i < G; i += T) {
                     PairPlan* row = plans.data() + (i * G - i * (i - 1) / 2);
                     for (int64_t j = i; j < G; ++j)
                         row[j - i] = plan_pair(batch->graphs[i], batch->graphs[j], true, forced, limit, cache, attr_dim);
                 }
             };
-            std::vector<std::thread> pool;
-            for (int t = 1; t < T; ++t) pool.emplace_back(plan_worker, t);
+            JoiningThreads pool;
+            for (int t = 1; t < T; ++t) pool.t.emplace_back(plan_worker, t);
             plan_worker(0);
-            for (std::thread& th : pool) th.join();
+            pool.join();
         }
         size_t next_plan = 0;
         for (int64_t i = 0; i < G; ++i)
@@ -1319,7 +1391,30 @@ static mgk_status pairs_impl(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n
 mgk_status mgk_pairs(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
                      const int32_t* i_host, const int32_t* j_host, float* K_dev, int32_t* iters_dev,
                      int32_t* flag_dev, void* stream_) {
-    return pairs_impl(ctx, X, Y, n_pairs, i_host, j_host, K_dev, nullptr, nullptr, iters_dev, flag_dev, stream_);
+    return guarded(ctx, [&] {
+        return pairs_impl(ctx, X, Y, n_pairs, i_host, j_host, K_dev, nullptr, nullptr, iters_dev, flag_dev, stream_);
+    });
+}
+
+mgk_status mgk_pairs_dev(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
+                         const int32_t* i_dev, const int32_t* j_dev, float* K_dev, int32_t* iters_dev,
+                         int32_t* flag_dev, void* stream_) {
+    return guarded(ctx, [&]() -> mgk_status {
+        if (!ctx || !X || !Y) return fail(ctx, MGK_EINVAL, "null argument");
+        if (ctx->device < 0) return fail(ctx, MGK_ESTATE, "host-only context cannot solve");
+        if (n_pairs < 0 || n_pairs >= (int64_t)1 << 31) return fail(ctx, MGK_EINVAL, "bad pair count");
+        if (n_pairs == 0) return MGK_OK;
+        if (!i_dev || !j_dev) return fail(ctx, MGK_EINVAL, "null argument");
+        // the launch shape of a pair is chosen on the host from the sizes of its graphs
+        hipStream_t stream = static_cast<hipStream_t>(stream_);
+        MGK_HIP(ctx, hipSetDevice(ctx->device));
+        std::vector<int32_t> ij((size_t)(2 * n_pairs));
+        MGK_HIP(ctx, hipMemcpyAsync(ij.data(), i_dev, (size_t)n_pairs * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+        MGK_HIP(ctx, hipMemcpyAsync(ij.data() + n_pairs, j_dev, (size_t)n_pairs * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+        MGK_HIP(ctx, hipStreamSynchronize(stream));
+        return pairs_impl(ctx, X, Y, n_pairs, ij.data(), ij.data() + n_pairs, K_dev, nullptr, nullptr, iters_dev,
+                          flag_dev, stream_);
+    });
 }
 
 mgk_status mgk_pairs_nodal(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
@@ -1327,7 +1422,9 @@ mgk_status mgk_pairs_nodal(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_p
                            const int64_t* x_off_host, int32_t* iters_dev, int32_t* flag_dev,
                            void* stream_) {
     if (n_pairs > 0 && (!x_dev || !x_off_host)) return fail(ctx, MGK_EINVAL, "null nodal output");
-    return pairs_impl(ctx, X, Y, n_pairs, i_host, j_host, K_dev, x_dev, x_off_host, iters_dev, flag_dev, stream_);
+    return guarded(ctx, [&] {
+        return pairs_impl(ctx, X, Y, n_pairs, i_host, j_host, K_dev, x_dev, x_off_host, iters_dev, flag_dev, stream_);
+    });
 }
 
 mgk_status mgk_normalize_gram(mgk_ctx* ctx, int32_t n, float* K_dev, void* stream_) {

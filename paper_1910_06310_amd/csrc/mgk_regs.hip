@@ -308,7 +308,10 @@ __global__ __launch_bounds__(W * 64) void mgk_pcg_regs(MgkBatchDev X, MgkBatchDe
     int kend = rend < n1 ? X.rowptr[g1.voff + rend] : z1;
     kbeg = __builtin_amdgcn_readfirstlane(kbeg);
     kend = __builtin_amdgcn_readfirstlane(kend);
-    const int S = min(kend - kbeg, SMAX);   // the host only sends pairs whose runs fit
+    // The host only sends pairs whose runs fit the unrolled loop; every wavefront reports
+    // whether its run does, and the workgroup checks after the next barrier.
+    if (lane == 0) red[56 + wave] = kend - kbeg > SMAX ? 1.f : 0.f;
+    const int S = kend - kbeg;
 
     // lane l < S holds the wave's l-th outer nonzero
     const bool live1 = lane < S;
@@ -378,6 +381,22 @@ __global__ __launch_bounds__(W * 64) void mgk_pcg_regs(MgkBatchDev X, MgkBatchDe
         }
     }
     __syncthreads();   // per-vertex data staged
+    {
+        // A pair that does not fit is not solved with part of its matrix: value NaN, flag 2.
+        float misfit = 0.f;
+#pragma unroll
+        for (int w = 0; w < W; ++w) misfit += red[56 + w];
+        if (misfit != 0.f) {   // the same in every thread
+            if (tid == 0) {
+                const float bad = __builtin_nanf("");
+                out.K[job.out0] = bad;
+                if (job.out1 >= 0) out.K[job.out1] = bad;
+                if (out.iters) { out.iters[job.out0] = 0; if (job.out1 >= 0) out.iters[job.out1] = 0; }
+                if (out.flags) { out.flags[job.out0] = 2; if (job.out1 >= 0) out.flags[job.out1] = 2; }
+            }
+            return;
+        }
+    }
 
     // ---- Alg. 1 set-up: M = D_x V_x^{-1}, x = 0, r = b = D_x q_x, z = M^{-1} r,
     //      p = z, rho = r^T z ----------------------------------------------------

@@ -510,3 +510,24 @@ def test_edge_cases(torch, solver):
     K1, _, _ = run_gram(torch, solver, _assemble(graphs[:1], prm, "one"))
     assert K1.shape == (1, 1) and K1[0, 0] == pytest.approx(0.0025, rel=1e-6)
     one.free()
+
+
+def test_pairs_with_index_arrays_on_the_device(torch, solver):
+    """mgk_pairs_dev takes the pair indices from device memory; same values, bit for bit, as
+    the entry point that takes them from the host, and within tolerance of the oracle."""
+    wb = W.config1(24)
+    solver.configure(wb.params)
+    solver.set_solver(1e-6, 0)
+    B = solver.load_batch(wb)
+    rng = np.random.default_rng(3)
+    pi = rng.integers(0, 24, 200).astype(np.int32)
+    pj = rng.integers(0, 24, 200).astype(np.int32)
+    K_host, it_host, fl_host = run_pairs(torch, solver, B, B, pi, pj)
+    K = torch.full((200,), float("nan"), dtype=torch.float32, device="cuda")
+    it = torch.zeros((200,), dtype=torch.int32, device="cuda")
+    fl = torch.full((200,), -1, dtype=torch.int32, device="cuda")
+    solver.pairs_dev(B, B, torch.from_numpy(pi).cuda(), torch.from_numpy(pj).cuda(), K, it, fl)
+    torch.cuda.synchronize()
+    assert (K.cpu().numpy().astype(np.float64) == K_host).all()
+    assert (it.cpu().numpy() == it_host).all() and (fl.cpu().numpy() == 0).all()
+    np.testing.assert_allclose(K_host, C.pairs(wb, pi, pj, tier=1), rtol=RTOL)

@@ -156,3 +156,26 @@ def test_morton_numbering_of_geometric_graphs():
     t_mort = s.load_batch(big_m, reorder=M.REORDER_NONE).stats()["n_offdiag_tiles"]
     t_pbr = s.load_batch(big_r, reorder=M.REORDER_PBR).stats()["n_offdiag_tiles"]
     assert t_pbr < t_mort < 0.5 * t_rand
+
+
+def test_offsets_are_validated_before_anything_is_sized_by_them(solver):
+    """Offset arrays that decrease in the middle (the last entry is then not a bound for the
+    others) and absurd totals are rejected with a status: no write past the arrays they size,
+    no exception across the C ABI."""
+    lab = np.zeros(150, np.int32)
+    # graph 0 claims 100 vertices although the total is 50
+    with pytest.raises(M.MgkError) as ei:
+        solver.load_graphs([0, 100, 50], lab, [0, 0, 0], [], [])
+    assert ei.value.status == 1
+    # edge offsets that come back below an earlier one
+    src = np.zeros(8, np.int32); dst = np.ones(8, np.int32)
+    with pytest.raises(M.MgkError) as ei:
+        solver.load_graphs([0, 2, 4], lab, [0, 8, 1], src, dst)
+    assert ei.value.status == 1
+    # a vertex total no host can hold: refused by the 32-bit limit, not by a failed allocation
+    with pytest.raises(M.MgkError) as ei:
+        solver.load_graphs([0, 2 ** 40], lab, [0, 0], [], [])
+    assert ei.value.status in (1, 5)
+    # the context is still usable
+    b = W.config0()
+    assert solver.load_batch(b).stats()["n_graphs"] == 4
