@@ -216,7 +216,7 @@ def main() -> int:
     solver.set_solver(1e-6, 0)
     solver.set_launch(args.waves)
     solver.set_tile_path(args.tile_path)
-    solver.set_product_cache(bool(args.product_cache))
+    solver.set_product_cache(int(args.product_cache))
     t0 = time.perf_counter()
     B = solver.load_batch(wb, reorder=args.reorder)
     load_s = time.perf_counter() - t0

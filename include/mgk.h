@@ -132,9 +132,12 @@ mgk_status mgk_set_onchip_limit(mgk_ctx* ctx, int32_t max_product);
  * every product, as Alg. 2 does.  1 (default): for a pair small enough that its
  * nnz * nnz' entries fit in the vector registers of one workgroup they are
  * generated once per solve and kept there (they are never written to memory);
- * other pairs are handled as with 0.  Both give the same iterates up to the
- * rounding of the entries.  Ignored while mgk_set_launch forces a workgroup
- * size. */
+ * other pairs are handled as with 0.  3: as 1, but pairs of graphs with at most
+ * 64 vertices of degree at most 4 (edge kernels on scalar labels) go to a second
+ * entry-keeping kernel in which every lane owns whole rows of the system; it is
+ * slower on the benchmark workloads and kept for comparison (2 is accepted and
+ * means 1).  All give the same iterates up to the rounding of the entries.
+ * Ignored while mgk_set_launch forces a workgroup size. */
 mgk_status mgk_set_product_cache(mgk_ctx* ctx, int32_t enable);
 /* Order of the on-chip jobs inside a launch (Section V-B, dynamic scheduling).
  * 1 (default): most expensive pairs first, so that the hardware dispatcher,

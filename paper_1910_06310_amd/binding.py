@@ -220,8 +220,10 @@ class Solver:
     def set_schedule(self, cost_sorted: bool = True):
         self._check(load_library().mgk_set_schedule(self._h, 1 if cost_sorted else 0))
 
-    def set_product_cache(self, enable: bool = True):
-        self._check(load_library().mgk_set_product_cache(self._h, 1 if enable else 0))
+    def set_product_cache(self, enable=True):
+        """False / 0: entries regenerated in every product; True / 1: kept in registers for small
+        pairs; 3: the same with the owner-computes kernel where a pair fits it."""
+        self._check(load_library().mgk_set_product_cache(self._h, int(enable)))
 
     def load_graphs(self, vtx_off, vtx_label, edge_off, src, dst, weight=None, edge_label=None,
                     start_prob=None, reorder: int = REORDER_PBR) -> Batch:

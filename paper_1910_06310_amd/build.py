@@ -21,6 +21,7 @@ DEVICE_SOURCES = [("mgk_small.hip", "w%d" % w, ["-DMGK_SMALL_WAVES=%d" % w]) for
 DEVICE_SOURCES.append(("mgk_small.hip", "w4fine", ["-DMGK_SMALL_WAVES=4", "-DMGK_SMALL_FINE"]))
 DEVICE_SOURCES += [("mgk_regs.hip", "w%dc%d" % (w, c), ["-DMGK_REGS_WAVES=%d" % w, "-DMGK_REGS_CHUNKS=%d" % c])
                    for w in (4, 8) for c in (1, 2)]
+DEVICE_SOURCES += [("mgk_sell.hip", "w%d" % w, ["-DMGK_SELL_WAVES=%d" % w]) for w in (8, 4, 16)]
 DEVICE_SOURCES.append(("mgk_large.hip", "all", []))
 HOST_SOURCES = ["mgk_host.cpp", "mgk_reorder.cpp"]
 

@@ -31,6 +31,7 @@ struct JobBin {
     size_t lds_bytes = 0;
     int waves = 0, ept = 0;
     int chunks = 0;            // > 0: register-resident solver with this many inner chunks
+    int sell_regs = 0;         // > 0: owner-computes solver with this many entry registers per lane
     bool atomic_rows = false;  // an inner graph has a row longer than one lane group
     bool swapped = false;      // outer graphs come from batch Y, inner from X
 };
@@ -64,6 +65,7 @@ struct mgk_batch {
     std::vector<float> w, e;
     std::vector<int32_t> perm;     // [n_vertices], perm[voff + old] = new
     std::vector<int64_t> vtx_off;  // [G+1]
+    std::vector<MgkSellDesc> sell_desc;   // per graph, for the planner
     // device
     void* blob = nullptr;
     MgkBatchDev dev{};
@@ -90,7 +92,7 @@ struct mgk_ctx {
     int tile_path = MGK_TILE_AUTO;
     int waves = 0;
     int onchip_limit = MGK_SMALL_MAX_N;  // largest n n' given to the on-chip solver
-    int product_cache = 1;      // small pairs keep their matrix entries in registers
+    int product_cache = 1;      // small pairs keep their matrix entries in registers (2, 3: one of the two kernels only)
     int cost_sorted = 1;        // expensive pairs first inside a launch
     int row_staging = 1;        // global-memory sparse product stages rows of p in LDS
     JobList pair_jobs;          // reused by mgk_pairs
@@ -257,6 +259,7 @@ struct PairPlan {
     int64_t lds_words = 0;
     int waves = 0, ept = 0;  // 0: does not fit
     int chunks = 0;          // > 0: register-resident solver
+    int sell_regs = 0;       // > 0: owner-computes solver
 };
 
 // Register-resident solver for (outer o, inner i) with `waves` wavefronts: every
@@ -277,8 +280,37 @@ int64_t regs_cost(const MgkGraphDesc& o, const MgkGraphDesc& i, int waves) {
            (int64_t)waves * (8 * ept + 45);
 }
 
-PairPlan plan_pair(const MgkGraphDesc& a, const MgkGraphDesc& b, bool may_swap, int forced_waves,
-                   int onchip_limit, bool product_cache, int attr_dim) {
+// Owner-computes solver for (outer o, inner i): the cheapest launch shape that holds the
+// pair.  Cost in wave instructions of one iteration: the entries of the most loaded
+// wavefront (a gather, weighted by its bank conflicts, and a multiply-add each), the
+// vector part per slot, the three workgroup sums, and the share of the compute unit the
+// workgroup occupies.  Returns -1 when no shape fits.
+int64_t sell_cost(const MgkSellDesc& o, const MgkSellDesc& i, int* waves, int* ept, int* regs) {
+    int64_t best = -1;
+    for (int w = 4; w <= 16; w *= 2) {
+        int32_t slots = 0, executed = 0;
+        const int32_t need = mgk_sell_need(o, i, w, &slots, &executed);
+        for (const MgkSellShape& sh : kMgkSellShapes)
+            if (sh.waves == w && sh.ept >= slots && sh.regs >= need) {
+                const int64_t c = (int64_t)executed * 4 + (int64_t)w * (13 * slots + 45);
+                if (best < 0 || c < best) {
+                    best = c;
+                    *waves = w;
+                    *ept = sh.ept;
+                    *regs = sh.regs;
+                }
+                break;   // shapes of a workgroup size are listed smallest first
+            }
+    }
+    return best;
+}
+
+// cache: 0 entries regenerated in every product; 1 (and 2) kept in registers by the kernel
+// in which a wavefront owns rows of the outer graph; 3 by the owner-computes kernel where
+// a pair fits it, else as 1
+PairPlan plan_pair(const MgkGraphDesc& a, const MgkGraphDesc& b, const MgkSellDesc* sa, const MgkSellDesc* sb,
+                   bool may_swap, int forced_waves, int onchip_limit, int cache, int attr_dim) {
+    const bool product_cache = cache != 0;
     // wave iterations of one XMV: outer nonzeros x 64-lane chunks of the inner layout
     auto passes = [](const MgkGraphDesc& o, const MgkGraphDesc& i) {
         return (int64_t)o.nnz * (i.lane_len / 64) + 2 * (int64_t)o.n * (i.lane_len / 64);
@@ -291,6 +323,30 @@ PairPlan plan_pair(const MgkGraphDesc& a, const MgkGraphDesc& b, bool may_swap, 
     const int64_t N = (int64_t)a.n * b.n;
     pl.cost = (pl.swap ? swp : keep) * 64 + 16 * N;
     if (N > MGK_SMALL_MAX_N || N > onchip_limit) return pl;
+    if (cache == 3 && forced_waves == 0 && attr_dim == 0 && sa && sb &&
+        mgk_sell_ok(*sa) && mgk_sell_ok(*sb)) {
+        int64_t best = -1;
+        for (int sw = 0; sw < (may_swap ? 2 : 1); ++sw) {
+            int w = 0, ept = 0, regs = 0;
+            const int64_t c = sw ? sell_cost(*sb, *sa, &w, &ept, &regs) : sell_cost(*sa, *sb, &w, &ept, &regs);
+            if (c >= 0 && (best < 0 || c < best)) {
+                best = c;
+                pl.waves = w;
+                pl.ept = ept;
+                pl.sell_regs = regs;
+                pl.swap = sw != 0;
+            }
+        }
+        if (best >= 0) {
+            const MgkGraphDesc& o = pl.swap ? b : a;
+            const MgkGraphDesc& i = pl.swap ? a : b;
+            pl.atomic_rows = false;
+            pl.chunks = 0;
+            pl.cost = best * 16 + 16 * N;
+            pl.lds_words = mgk_sell_plan(o.n, i.n, pl.waves, pl.ept).total;
+            return pl;
+        }
+    }
     if (product_cache && forced_waves == 0) {
         int64_t best = -1;
         for (int w = 4; w <= 8; w *= 2)
@@ -330,6 +386,7 @@ struct HostJob {
     int64_t cost;
     int32_t lds_words;
     int16_t waves, ept, chunks;
+    int16_t sell_regs = 0;
     bool atomic_rows, swapped;
 };
 
@@ -341,9 +398,9 @@ struct HostJob {
 constexpr int64_t kMinJobsPerLaunch = 4096;
 
 void merge_small_shapes(std::vector<HostJob>& jobs) {
-    struct Shape { int waves, ept, chunks; bool atomic_rows, swapped; int64_t count; };
+    struct Shape { int waves, ept, chunks, sell_regs; bool atomic_rows, swapped; int64_t count; };
     auto same = [](const Shape& s, const HostJob& j) {
-        return s.waves == j.waves && s.ept == j.ept && s.chunks == j.chunks &&
+        return s.waves == j.waves && s.ept == j.ept && s.chunks == j.chunks && s.sell_regs == j.sell_regs &&
                s.atomic_rows == j.atomic_rows && s.swapped == j.swapped;
     };
     std::vector<Shape> frozen;   // shapes whose jobs would outgrow LDS in the larger shape
@@ -351,7 +408,7 @@ void merge_small_shapes(std::vector<HostJob>& jobs) {
         std::vector<Shape> shapes;
         for (const HostJob& j : jobs) {
             auto it = std::find_if(shapes.begin(), shapes.end(), [&](const Shape& s) { return same(s, j); });
-            if (it == shapes.end()) shapes.push_back({j.waves, j.ept, j.chunks, j.atomic_rows, j.swapped, 1});
+            if (it == shapes.end()) shapes.push_back({j.waves, j.ept, j.chunks, j.sell_regs, j.atomic_rows, j.swapped, 1});
             else it->count++;
         }
         // smallest shape below the threshold that has somewhere to go
@@ -360,31 +417,36 @@ void merge_small_shapes(std::vector<HostJob>& jobs) {
         for (const Shape& a : shapes) {
             if (a.count >= kMinJobsPerLaunch) continue;
             if (std::any_of(frozen.begin(), frozen.end(), [&](const Shape& f) {
-                    return f.waves == a.waves && f.ept == a.ept && f.chunks == a.chunks &&
+                    return f.waves == a.waves && f.ept == a.ept && f.chunks == a.chunks && f.sell_regs == a.sell_regs &&
                            f.atomic_rows == a.atomic_rows && f.swapped == a.swapped; }))
                 continue;
             const Shape* best = nullptr;
             for (const Shape& b : shapes) {
                 if (&a == &b || a.waves != b.waves || a.atomic_rows != b.atomic_rows || a.swapped != b.swapped ||
-                    (a.chunks > 0) != (b.chunks > 0) || b.chunks < a.chunks || b.ept < a.ept)
+                    (a.chunks > 0) != (b.chunks > 0) || b.chunks < a.chunks || b.ept < a.ept ||
+                    (a.sell_regs > 0) != (b.sell_regs > 0) || b.sell_regs < a.sell_regs)
                     continue;
-                if (!best || b.ept * 4 + b.chunks < best->ept * 4 + best->chunks) best = &b;
+                if (!best || b.ept * 4 + b.chunks + b.sell_regs < best->ept * 4 + best->chunks + best->sell_regs) best = &b;
             }
             if (best && (!from || a.ept * 4 + a.chunks < from->ept * 4 + from->chunks)) { from = &a; to = best; }
         }
         if (!from) return;
-        const int vectors = from->chunks > 0 ? 4 : 2;   // padded vectors in the LDS plan of each solver
+        // padded vectors in the LDS plan of each solver (the owner-computes one also has a
+        // schedule word per wavefront and slot; 4 words of alignment slack)
+        const int vectors = from->sell_regs > 0 ? 3 : from->chunks > 0 ? 4 : 2;
+        const int extra = from->sell_regs > 0 ? from->waves * (to->ept - from->ept) + 4 : 0;
         bool fits = true;
         for (const HostJob& j : jobs)
             if (same(*from, j) &&
-                ((int64_t)j.lds_words + vectors * j.waves * 64 * (to->ept - j.ept)) * 4 > MGK_LDS_LIMIT_BYTES)
+                ((int64_t)j.lds_words + vectors * j.waves * 64 * (to->ept - j.ept) + extra) * 4 > MGK_LDS_LIMIT_BYTES)
                 fits = false;
         if (!fits) { frozen.push_back(*from); continue; }
         for (HostJob& j : jobs)
             if (same(*from, j)) {
-                j.lds_words += vectors * j.waves * 64 * (to->ept - j.ept);
+                j.lds_words += vectors * j.waves * 64 * (to->ept - j.ept) + extra;
                 j.ept = (int16_t)to->ept;
                 j.chunks = (int16_t)to->chunks;
+                j.sell_regs = (int16_t)to->sell_regs;
             }
     }
 }
@@ -399,6 +461,7 @@ mgk_status build_job_list(mgk_ctx* ctx, std::vector<HostJob>& jobs, JobList& out
         if (ka != kb) return ka > kb;
         if (a.waves != b.waves) return a.waves > b.waves;
         if (a.chunks != b.chunks) return a.chunks > b.chunks;
+        if (a.sell_regs != b.sell_regs) return a.sell_regs > b.sell_regs;
         if (a.atomic_rows != b.atomic_rows) return a.atomic_rows;
         if (a.swapped != b.swapped) return b.swapped;
         return by_cost && a.cost > b.cost;
@@ -410,6 +473,7 @@ mgk_status build_job_list(mgk_ctx* ctx, std::vector<HostJob>& jobs, JobList& out
         flat[k] = jobs[k].job;
         if (out.bins.empty() || jobs[k].waves != out.bins.back().waves ||
             jobs[k].ept != out.bins.back().ept || jobs[k].chunks != out.bins.back().chunks ||
+            jobs[k].sell_regs != out.bins.back().sell_regs ||
             jobs[k].atomic_rows != out.bins.back().atomic_rows ||
             jobs[k].swapped != out.bins.back().swapped) {
             JobBin b;
@@ -417,6 +481,7 @@ mgk_status build_job_list(mgk_ctx* ctx, std::vector<HostJob>& jobs, JobList& out
             b.waves = jobs[k].waves;
             b.ept = jobs[k].ept;
             b.chunks = jobs[k].chunks;
+            b.sell_regs = jobs[k].sell_regs;
             b.atomic_rows = jobs[k].atomic_rows;
             b.swapped = jobs[k].swapped;
             out.bins.push_back(b);
@@ -618,7 +683,10 @@ mgk_status launch_jobs(mgk_ctx* ctx, const mgk_batch* X, const mgk_batch* Y, con
             const int64_t chunk = std::min<int64_t>(b.count - done, (int64_t)1 << 30);
             const MgkBatchDev& o = b.swapped ? Y->dev : X->dev;
             const MgkBatchDev& i = b.swapped ? X->dev : Y->dev;
-            hipError_t e = b.chunks > 0
+            hipError_t e = b.sell_regs > 0
+                ? mgk_launch_sell(b.waves, b.ept, b.sell_regs, o, i, jl.dev + b.first + done, (int)chunk, prm,
+                                  b.lds_bytes, out, stream)
+                : b.chunks > 0
                 ? mgk_launch_regs(b.waves, b.chunks, b.ept, weighted, o, i, jl.dev + b.first + done, (int)chunk,
                                   prm, b.lds_bytes, out, stream)
                 : mgk_launch_small(b.waves, b.ept, weighted, b.atomic_rows, o, i,
@@ -791,7 +859,7 @@ mgk_status mgk_set_onchip_limit(mgk_ctx* ctx, int32_t max_product) {
 
 mgk_status mgk_set_product_cache(mgk_ctx* ctx, int32_t enable) {
     if (!ctx) return MGK_EINVAL;
-    if (enable != 0 && enable != 1) return fail(ctx, MGK_EINVAL, "product cache must be 0 or 1, got %d", enable);
+    if (enable < 0 || enable > 3) return fail(ctx, MGK_EINVAL, "product cache must be 0 to 3, got %d", enable);
     ctx->product_cache = enable;
     return MGK_OK;
 }
@@ -877,6 +945,9 @@ static mgk_status load_graphs_body(mgk_ctx* ctx, int32_t n_graphs, const int64_t
     B->vtx_off.assign(vtx_off, vtx_off + n_graphs + 1);
     B->perm.resize((size_t)tot_v);
     std::vector<int32_t> vlabel((size_t)tot_v), rowptr((size_t)tot_v), lanepos((size_t)tot_v), iperm((size_t)tot_v), trow_ptr, tile_graph;
+    std::vector<MgkSellVertex> sell_vtx;            // records of the owner-computes solver
+    std::vector<MgkSellNbr> sell_nbr;
+    B->sell_desc.reserve((size_t)n_graphs);
     std::vector<MgkEntry> list_outer, list_inner;   // nonzero lists for the register-resident solver
     std::vector<int32_t> regs_split;                // its division of every graph's rows among wavefronts
     list_outer.reserve((size_t)(2 * tot_e));
@@ -1106,6 +1177,47 @@ static mgk_status load_graphs_body(mgk_ctx* ctx, int32_t n_graphs, const int64_t
             }
         }
         tile_graph.resize(B->tiles.size(), g);
+
+        // ---- records of the owner-computes solver: vertices sorted by degree (descending),
+        //      four neighbour records per vertex
+        {
+            MgkSellDesc sd{};
+            sd.voff = (int32_t)sell_vtx.size();
+            if (n <= MGK_SELL_MAX_N && max_deg <= MGK_SELL_MAX_DEG) {
+                std::vector<int32_t> order(n), pos(n);
+                std::iota(order.begin(), order.end(), 0);
+                std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return deg[x] > deg[y]; });
+                for (int k = 0; k < n; ++k) pos[order[k]] = k;
+                const int r8 = (n + 7) & ~7;
+                for (int k = 0; k < r8; ++k) {
+                    MgkSellVertex sv{0.f, 0.f, -1, 0xffffu};
+                    MgkSellNbr sn[MGK_SELL_MAX_DEG] = {};   // weight 0, position 0: no entry
+                    if (k < n) {
+                        const int v = order[k];
+                        sv.rowsum = rowsum[v0 + v];
+                        sv.start = start[v0 + v];
+                        sv.label = vlabel[v0 + v];
+                        sv.id_deg = (uint32_t)v | ((uint32_t)deg[v] << 16);
+                        for (int a = 0; a < deg[v]; ++a) {
+                            const MgkEntry& en = list_outer[(size_t)gd.zoff + rowptr[v0 + v] + a];
+                            const uint32_t wbits = en.w & 0x7fffffffu;
+                            sn[a].pos = (uint32_t)pos[en.y];
+                            memcpy(&sn[a].w, &wbits, 4);
+                            memcpy(&sn[a].e, &en.z, 4);
+                        }
+                    }
+                    sell_vtx.push_back(sv);
+                    sell_nbr.insert(sell_nbr.end(), sn, sn + MGK_SELL_MAX_DEG);
+                }
+                uint32_t ga[MGK_SELL_MAX_DEG + 1] = {}, gb[MGK_SELL_MAX_DEG + 1] = {};
+                for (int k = 0; k < n; k += MGK_SELL_OUTER_GROUP) ga[deg[order[k]]]++;
+                for (int k = 0; k < n; k += MGK_SELL_INNER_GROUP) gb[deg[order[k]]]++;
+                sd.ga03 = ga[0] | (ga[1] << 8) | (ga[2] << 16) | (ga[3] << 24);
+                sd.gb03 = gb[0] | (gb[1] << 8) | (gb[2] << 16) | (gb[3] << 24);
+                sd.hi = ga[4] | (gb[4] << 8) | (1u << 16);
+            }
+            B->sell_desc.push_back(sd);
+        }
     }
     B->n_vertices = tot_v;
     B->nnz = (int64_t)B->w.size();
@@ -1142,6 +1254,9 @@ static mgk_status load_graphs_body(mgk_ctx* ctx, int32_t n_graphs, const int64_t
     }
     const size_t o_ao = append_bytes(blob, attr_outer);
     const size_t o_ai = append_bytes(blob, attr_inner);
+    const size_t o_sd = append_bytes(blob, B->sell_desc);
+    const size_t o_sv = append_bytes(blob, sell_vtx);
+    const size_t o_sn = append_bytes(blob, sell_nbr);
     B->dev.label_dim = D;
     B->dev.uniform_start = start_prob ? 0 : 1;
     B->dev.n_graphs = n_graphs;
@@ -1174,6 +1289,9 @@ static mgk_status load_graphs_body(mgk_ctx* ctx, int32_t n_graphs, const int64_t
     B->dev.regs_split = reinterpret_cast<const int32_t*>(base + o_sp);
     B->dev.attr_outer = reinterpret_cast<const float*>(base + o_ao);
     B->dev.attr_inner = reinterpret_cast<const float*>(base + o_ai);
+    B->dev.sell_desc = reinterpret_cast<const MgkSellDesc*>(base + o_sd);
+    B->dev.sell_vtx = reinterpret_cast<const MgkSellVertex*>(base + o_sv);
+    B->dev.sell_nbr = reinterpret_cast<const MgkSellNbr*>(base + o_sn);
 
     guard.b = nullptr;
     *out = B;
@@ -1261,7 +1379,7 @@ static mgk_status gram_body(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_
         // several threads, row i starting at pair i G - i (i - 1) / 2
         std::vector<PairPlan> plans((size_t)(G * (G + 1) / 2));
         {
-            const bool cache = ctx->product_cache != 0;
+            const int cache = ctx->product_cache;
             const int attr_dim = attr_dim_of(ctx);
             const int forced = ctx->waves, limit = ctx->onchip_limit;
             const int T = (int)std::max<int64_t>(1, std::min<int64_t>({(int64_t)std::thread::hardware_concurrency(), 16, G / 64}));
@@ -1269,7 +1387,8 @@ static mgk_status gram_body(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_
                 for (int64_t i = t; i < G; i += T) {
                     PairPlan* row = plans.data() + (i * G - i * (i - 1) / 2);
                     for (int64_t j = i; j < G; ++j)
-                        row[j - i] = plan_pair(batch->graphs[i], batch->graphs[j], true, forced, limit, cache, attr_dim);
+                        row[j - i] = plan_pair(batch->graphs[i], batch->graphs[j], &batch->sell_desc[(size_t)i],
+                                               &batch->sell_desc[(size_t)j], true, forced, limit, cache, attr_dim);
                 }
             };
             JoiningThreads pool;
@@ -1291,6 +1410,7 @@ static mgk_status gram_body(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_
                 hj.waves = (int16_t)pl.waves;
                 hj.ept = (int16_t)pl.ept;
                 hj.chunks = (int16_t)pl.chunks;
+                hj.sell_regs = (int16_t)pl.sell_regs;
                 hj.atomic_rows = pl.atomic_rows;
                 hj.swapped = false;  // one batch: swapping is done through the indices
                 if (pl.waves == 0) {  // vectors do not fit on chip
@@ -1340,7 +1460,8 @@ static mgk_status pairs_impl(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n
         const int32_t i = i_host[k], j = j_host[k];
         if (i < 0 || i >= X->n_graphs || j < 0 || j >= Y->n_graphs)
             return fail(ctx, MGK_EINVAL, "pair %lld: graph index out of range", (long long)k);
-        const PairPlan pl = plan_pair(X->graphs[i], Y->graphs[j], true, ctx->waves, ctx->onchip_limit, ctx->product_cache != 0, attr_dim_of(ctx));
+        const PairPlan pl = plan_pair(X->graphs[i], Y->graphs[j], &X->sell_desc[(size_t)i], &Y->sell_desc[(size_t)j], true,
+                                      ctx->waves, ctx->onchip_limit, ctx->product_cache, attr_dim_of(ctx));
         HostJob& hj = jobs[(size_t)k];
         hj.job.g1 = pl.swap ? j : i;
         hj.job.g2 = pl.swap ? i : j;
@@ -1351,6 +1472,7 @@ static mgk_status pairs_impl(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n
         hj.waves = (int16_t)pl.waves;
         hj.ept = (int16_t)pl.ept;
         hj.chunks = (int16_t)pl.chunks;
+        hj.sell_regs = (int16_t)pl.sell_regs;
         hj.atomic_rows = pl.atomic_rows;
         hj.swapped = pl.swap && X != Y;
         if (pl.waves == 0) {
@@ -1370,13 +1492,13 @@ static mgk_status pairs_impl(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n
     }
     jobs.erase(std::remove_if(jobs.begin(), jobs.end(), [](const HostJob& h) { return h.waves == 0; }),
                jobs.end());
+    MgkOutputs out{K_dev, iters_dev, flag_dev, nullptr, nullptr};
     mgk_status st = build_job_list(ctx, jobs, ctx->pair_jobs, stream, &ctx->pair_jobs_cap);
     if (st != MGK_OK) return st;
     for (int a = 0; a < 2; ++a)
         for (int b = 0; b < 2; ++b) ctx->pair_jobs.large[a][b] = std::move(large[a][b]);
     ctx->pair_jobs_stream = stream;
     ctx->pair_jobs_busy = true;
-    MgkOutputs out{K_dev, iters_dev, flag_dev, nullptr, nullptr};
     if (x_dev) {
         if ((st = ensure(ctx, ctx->nodal_off, (size_t)n_pairs * sizeof(int64_t))) != MGK_OK) return st;
         MGK_HIP(ctx, hipMemcpyAsync(ctx->nodal_off.p, x_off_host, (size_t)n_pairs * sizeof(int64_t),

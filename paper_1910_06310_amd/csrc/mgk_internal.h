@@ -83,6 +83,9 @@ struct MgkBatchDev {
     const int32_t* regs_split;  // per graph MGK_REGS_SPLIT_STRIDE row boundaries, see below
     const float* attr_outer;  // label attribute a of nonzero k (CSR order): attr_outer[a * nnz_total + zoff + k]
     const float* attr_inner;  // the same in lane order: attr_inner[a * lanes_total + loff + slot], 0 on idle slots
+    const struct MgkSellDesc* sell_desc;    // per graph, see MgkSellDesc
+    const struct MgkSellVertex* sell_vtx;   // records of the owner-computes solver
+    const struct MgkSellNbr* sell_nbr;
     int32_t n_graphs, n_tiles_total, nnz_total, lanes_total;
     int32_t label_dim;        // attributes per edge label (1 for plain scalar labels)
     int32_t uniform_start;    // 1: no starting probabilities were given, p_i = 1/n on every graph
@@ -223,6 +226,138 @@ static inline MGK_HD MgkRegsPlan mgk_regs_plan(int32_t n1, int32_t n2, int32_t w
     L.red = (L.vtx2 + 3 * n2 + 3) & ~3;
     L.total = L.red + 64;
     return L;
+}
+
+// ---- owner-computes on-chip solver (graphs of at most 64 vertices, degree <= 4) ----
+// Every element (i, i') of the product vectors has one owning lane, which keeps the
+// off-diagonal entries of its row of the system -- deg(i) deg(i') of them, about four on
+// molecule-like graphs -- in registers together with the LDS address of the element of p
+// each one multiplies.  Lanes that work side by side must own rows of equal length, so
+// the vertices of a graph are sorted by degree (descending) at load and grouped: groups
+// of 4 when the graph is the outer operand, groups of 8 when it is the inner one.  A
+// "tile" is (outer group U) x (inner group V): 32 elements = one half of a wavefront,
+// all of whose rows have at most maxdeg(U) * maxdeg(V) entries.  Tiles are enumerated by
+// (maxdeg(U) descending, maxdeg(V) descending); tile number h is held by lanes
+// 32 (h & 1) .. + 31 of a wavefront (mgk_sell_wave_of) in its vector slot (h / 2) / W, lane
+// 8 u + v owning (vertex u of U, vertex v of V).  An element's p value lives in LDS at
+// a word that is 8 u + v modulo 32, so its bank is 8 (k & 3) + (k' & 7) for sorted positions k, k':
+// a gather by the 32 lanes of a tile is free of bank conflicts when the a-th neighbours
+// of the 4 outer vertices sit at positions distinct mod 4 and the b-th neighbours of the
+// 8 inner vertices at positions distinct mod 8 (the loader orders the vertices inside a
+// degree class, and each vertex's neighbour list, toward that).
+#define MGK_SELL_MAX_N 64        // vertices per graph
+#define MGK_SELL_MAX_DEG 4
+#define MGK_SELL_OUTER_GROUP 4
+#define MGK_SELL_INNER_GROUP 8
+
+// Per graph: where its records start (8 ceil(n / 8) vertex records, 4 neighbour records
+// each) and how many outer / inner groups have each maximum degree 0..4.  ok == 0: the
+// graph does not qualify (too many vertices or a vertex of higher degree).
+struct MgkSellDesc {
+    int32_t voff;
+    uint32_t ga03;   // groups of 4 whose maximum degree is 0..3, one byte each
+    uint32_t gb03;   // groups of 8 whose maximum degree is 0..3
+    uint32_t hi;     // groups of 4 with maximum degree 4 | groups of 8 with maximum degree 4 << 8 | ok << 16
+};
+static inline MGK_HD int mgk_sell_ga(const MgkSellDesc& d, int deg) {
+    return (int)((deg < 4 ? d.ga03 >> (8 * deg) : d.hi) & 0xffu);
+}
+static inline MGK_HD int mgk_sell_gb(const MgkSellDesc& d, int deg) {
+    return (int)((deg < 4 ? d.gb03 >> (8 * deg) : d.hi >> 8) & 0xffu);
+}
+static inline MGK_HD bool mgk_sell_ok(const MgkSellDesc& d) { return ((d.hi >> 16) & 1u) != 0u; }
+// Vertex at sorted position k: row sum of A, starting probability, label, and
+// (vertex id in stored order) | degree << 16.  Positions >= n are padding (degree 0, id 0xffff).
+struct alignas(16) MgkSellVertex {
+    float rowsum, start;
+    int32_t label;
+    uint32_t id_deg;
+};
+// a-th neighbour of the vertex at sorted position k (record 4 k + a): the neighbour's
+// sorted position, A_ij, E_ij.  a >= degree: weight 0, position k itself.
+struct alignas(16) MgkSellNbr {
+    uint32_t pos;
+    float w, e;
+    uint32_t pad;
+};
+
+// Tiles 2 s and 2 s + 1 share vector slot s / W of wavefront s % W, counted back and forth
+// (W - 1 - s % W in odd rounds): rows get shorter with s, and this way no wavefront takes
+// the longest rows of every round.
+static inline MGK_HD int mgk_sell_wave_of(int s, int waves) {
+    const int m = s / waves, j = s - m * waves;
+    return (m & 1) ? waves - 1 - j : j;
+}
+
+// LDS plan of the owner-computes solver, in words.
+struct MgkSellPlan {
+    int32_t p, y, x;          // slot layout, waves * 64 * ept words each
+    int32_t vtx1, nbr1, vtx2, nbr2;
+    int32_t table, rankof;    // tile number -> (U, V, A, B); U * G2 + V -> byte address of the tile's 32 words of p
+    int32_t sched;            // per wavefront and slot: entries | (entries per outer neighbour) << 8
+    int32_t misfit;           // per wavefront: 1 when its rows do not fit the launch shape
+    int32_t red, total;
+};
+static inline MGK_HD MgkSellPlan mgk_sell_plan(int32_t n1, int32_t n2, int32_t waves, int32_t ept) {
+    MgkSellPlan L;
+    const int32_t np = waves * 64 * ept;
+    const int32_t r1 = (n1 + 7) & ~7, r2 = (n2 + 7) & ~7;   // staged records per graph
+    const int32_t tiles = ((n1 + 3) / 4) * ((n2 + 7) / 8);
+    L.p = 0;
+    L.y = np;
+    L.x = 2 * np;
+    L.vtx1 = 3 * np;
+    L.nbr1 = L.vtx1 + 4 * r1;
+    L.vtx2 = L.nbr1 + 16 * r1;
+    L.nbr2 = L.vtx2 + 4 * r2;
+    L.table = L.nbr2 + 16 * r2;
+    L.rankof = L.table + ((tiles + 3) & ~3);
+    L.sched = L.rankof + ((tiles + 3) & ~3);
+    L.misfit = L.sched + waves * ept;
+    L.red = (L.misfit + waves + 3) & ~3;
+    L.total = L.red + 64;
+    return L;
+}
+
+// Order of the tile classes (A, B) = (largest degree of the outer group, of the inner
+// group): classes with entries first, by A descending then B descending, then the classes
+// without entries (A or B zero: isolated vertices) in the same order.  True when class
+// (a, b) comes before class (A, B).
+static inline MGK_HD bool mgk_sell_class_before(int a, int b, int A, int B) {
+    const bool z = a * b == 0, Z = A * B == 0;
+    if (z != Z) return Z;
+    return a > A || (a == A && b > B);
+}
+
+// Walk of the tiles of a pair in the order the kernel numbers them, for the host planner
+// (does the pair fit a launch shape?): returns the largest number of entry registers any
+// wavefront needs with `waves` wavefronts, the number of vector slots per lane in *slots
+// and the entries all wavefronts execute together in *executed.
+static inline int32_t mgk_sell_need(const MgkSellDesc& o, const MgkSellDesc& i, int32_t waves, int32_t* slots,
+                                    int32_t* executed) {
+    int32_t per_wave[16] = {0};
+    int32_t h = 0, prevA = 0, prevB = 0;
+    for (int pass = 0; pass < 2; ++pass)   // classes with entries, then those without
+        for (int A = MGK_SELL_MAX_DEG; A >= 0; --A)
+            for (int B = MGK_SELL_MAX_DEG; B >= 0; --B) {
+                if ((A * B == 0) != (pass == 1)) continue;
+                const int32_t cnt = mgk_sell_ga(o, A) * mgk_sell_gb(i, B);
+                for (int32_t k = 0; k < cnt; ++k, ++h) {
+                    if (h & 1) {
+                        const int32_t a = A > prevA ? A : prevA, b = B > prevB ? B : prevB;
+                        per_wave[mgk_sell_wave_of(h >> 1, waves)] += a * b;
+                    } else {
+                        prevA = A;
+                        prevB = B;
+                    }
+                }
+            }
+    if (h & 1) per_wave[mgk_sell_wave_of(h >> 1, waves)] += prevA * prevB;
+    int32_t need = 0, sum = 0;
+    for (int w = 0; w < waves; ++w) { need = per_wave[w] > need ? per_wave[w] : need; sum += per_wave[w]; }
+    *slots = ((h + 1) / 2 + waves - 1) / waves;
+    if (executed) *executed = sum;
+    return need;
 }
 
 // ---- solver with vectors in global memory (pairs too large for LDS) ---------

@@ -75,6 +75,39 @@ static inline hipError_t mgk_launch_regs(int waves, int chunks, int ept, bool we
     }
 }
 
+// Owner-computes on-chip solver (mgk_sell.hip): `waves` (4, 8 or 16) wavefronts per job,
+// `ept` vector slots per lane (2 waves ept >= tiles of every job), `regs` entry registers
+// per lane (>= what mgk_sell_need returns for every job), `lds_bytes` the largest
+// MgkSellPlan::total of the jobs.  Launch shapes (waves, ept, regs); one translation unit
+// per workgroup size.
+#define MGK_SELL_SHAPES_W4(F) F(4, 4, 32) F(4, 6, 40) F(4, 8, 48)
+#define MGK_SELL_SHAPES_W8(F) F(8, 2, 16) F(8, 3, 24) F(8, 4, 32) F(8, 5, 36)
+#define MGK_SELL_SHAPES_W16(F) F(16, 3, 24) F(16, 4, 28)
+struct MgkSellShape { int waves, ept, regs; };
+static const MgkSellShape kMgkSellShapes[] = {
+#define MGK_SELL_ROW(W, E, R) {W, E, R},
+    MGK_SELL_SHAPES_W4(MGK_SELL_ROW) MGK_SELL_SHAPES_W8(MGK_SELL_ROW) MGK_SELL_SHAPES_W16(MGK_SELL_ROW)
+#undef MGK_SELL_ROW
+};
+#define MGK_DECL_SELL(W)                                                                             \
+    hipError_t mgk_launch_sell_w##W(int ept, int regs, const MgkBatchDev& X, const MgkBatchDev& Y,    \
+                                    const MgkJob* jobs_dev, int n_jobs, const MgkParams& prm,         \
+                                    size_t lds_bytes, const MgkOutputs& out, hipStream_t stream);
+MGK_DECL_SELL(4)
+MGK_DECL_SELL(8)
+MGK_DECL_SELL(16)
+#undef MGK_DECL_SELL
+static inline hipError_t mgk_launch_sell(int waves, int ept, int regs, const MgkBatchDev& X, const MgkBatchDev& Y,
+                                         const MgkJob* jobs_dev, int n_jobs, const MgkParams& prm,
+                                         size_t lds_bytes, const MgkOutputs& out, hipStream_t stream) {
+    switch (waves) {
+        case 4: return mgk_launch_sell_w4(ept, regs, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+        case 8: return mgk_launch_sell_w8(ept, regs, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+        case 16: return mgk_launch_sell_w16(ept, regs, X, Y, jobs_dev, n_jobs, prm, lds_bytes, out, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 // ---- solver with vectors in global memory (mgk_large.hip) --------------------
 // Expand every octile of batch B into the outer (CSR order) and inner (lane
 // layout) entry lists; `outer` holds B.nnz_total entries, `inner` B.lanes_total.

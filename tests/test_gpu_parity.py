@@ -531,3 +531,54 @@ def test_pairs_with_index_arrays_on_the_device(torch, solver):
     assert (K.cpu().numpy().astype(np.float64) == K_host).all()
     assert (it.cpu().numpy() == it_host).all() and (fl.cpu().numpy() == 0).all()
     np.testing.assert_allclose(K_host, C.pairs(wb, pi, pj, tier=1), rtol=RTOL)
+
+
+def test_owner_computes_kernel_agrees_with_oracle(torch, solver):
+    """mgk_set_product_cache(3): every lane owns rows of the system (degree-sorted tiles).
+    All pairs of the 100 molecule-like graphs and of the 4 small random graphs (isolated
+    vertices, weights), start probabilities and the nodal solution included."""
+    solver.set_solver(1e-6, 0)
+    solver.set_launch(0)
+    solver.set_product_cache(3)
+    try:
+        wb = W.config1()
+        K, it, fl = run_gram(torch, solver, wb)
+        pi, pj = W.gram_pairs(100)
+        ref = C.pairs(wb, pi, pj, tier=1)
+        err = np.abs(K[pi, pj] - ref) / ref
+        assert err.max() <= RTOL, (err.max(), int(err.argmax()))
+        assert (K == K.T).all() and (fl == 0).all() and (it > 0).all()
+        solver.set_product_cache(1)
+        K1, it1, _ = run_gram(torch, solver, wb)
+        solver.set_product_cache(3)
+        assert (it1 == it).all()   # same iteration, same stopping rule
+        np.testing.assert_allclose(K, K1, rtol=2e-5)
+
+        wb = W.config0()
+        K, it, fl = run_gram(torch, solver, wb)
+        pi, pj = W.gram_pairs(4)
+        np.testing.assert_allclose(K[pi, pj], O.gram_values(wb, pi, pj), rtol=RTOL)
+        assert (fl == 0).all()
+
+        # nodal solution in the caller's numbering, with non-uniform start probabilities
+        wb = W.config1(6)
+        rng = np.random.default_rng(5)
+        sp = np.concatenate([(lambda v: v / v.sum())(rng.uniform(0.2, 1.0, n)) for n in wb.sizes()]).astype(np.float32)
+        solver.configure(wb.params)
+        B = solver.load_batch(wb, start_prob=sp)
+        pi, pj = W.gram_pairs(6)
+        sizes = wb.sizes()
+        off = np.concatenate([[0], np.cumsum(sizes[pi] * sizes[pj])]).astype(np.int64)
+        Kd = torch.zeros(len(pi), dtype=torch.float32, device="cuda")
+        xd = torch.full((int(off[-1]),), float("nan"), dtype=torch.float32, device="cuda")
+        solver.pairs_nodal(B, B, pi, pj, Kd, xd, off[:-1])
+        torch.cuda.synchronize()
+        ref = C.pairs(wb, pi, pj, tier=0, start_prob=sp.astype(np.float64))
+        np.testing.assert_allclose(Kd.cpu().numpy(), ref, rtol=RTOL)
+        xs = xd.cpu().numpy().astype(np.float64)
+        for k in (0, 7, len(pi) - 1):
+            _, xref = C.pair_nodal(wb.graph(int(pi[k])), wb.graph(int(pj[k])), wb.params.q, wb.params.h,
+                                   wb.params.length_scale, tier=0)
+            np.testing.assert_allclose(xs[off[k]:off[k + 1]], xref.reshape(-1), rtol=RTOL)
+    finally:
+        solver.set_product_cache(1)
