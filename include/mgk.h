@@ -218,6 +218,23 @@ mgk_status mgk_pairs_dev(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pai
                          const int32_t* i_dev, const int32_t* j_dev, float* K_dev,
                          int32_t* iters_dev, int32_t* flag_dev, void* stream);
 
+/* mgk_pairs_noalloc: mgk_pairs for callers that cannot allocate device memory (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).  Same
+ * arguments, same kernels and bit-identical values, but the call makes no hipMalloc /
+ * hipFree (nor any other allocating HIP or library call): the job list its kernels read
+ * lives in a fixed 1 MiB array in device memory that every GPU the library runs on holds
+ * until the process ends.  Limits: at most 65536 pairs per call, and every pair must be
+ * solvable on chip (n n' <= the on-chip limit); otherwise MGK_ELIMIT and nothing is
+ * enqueued.  All calls on a GPU share that one array, which keeps the jobs of the last
+ * call: calls that overlap in time on the same GPU (other streams, other contexts,
+ * other threads) race on it; within one context a call first waits for the previous
+ * mgk_pairs_noalloc call's stream.  The index arrays are copied to the device from the
+ * caller's host memory and the stream is synchronised once before the kernels start,
+ * as in mgk_pairs. */
+mgk_status mgk_pairs_noalloc(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
+                             const int32_t* i_host, const int32_t* j_host, float* K_dev,
+                             int32_t* iters_dev, int32_t* flag_dev, void* stream);
+
 /* mgk_pairs_nodal: as mgk_pairs, and also the node-wise similarity (Section I):
  * the solution x = V_x r_inf of Eq. 1 itself.  For pair k the n x n' values, in
  * the caller's original vertex numbering, row-major (vertex i of the X graph,

@@ -28,7 +28,7 @@ EXPORTS = [
     "mgk_set_stop_prob", "mgk_set_solver", "mgk_set_tile_path", "mgk_set_launch",
     "mgk_set_onchip_limit", "mgk_set_product_cache", "mgk_set_schedule",
     "mgk_load_graphs", "mgk_free_batch", "mgk_batch_stats", "mgk_batch_permutation",
-    "mgk_batch_get_tiles", "mgk_gram", "mgk_pairs", "mgk_pairs_dev", "mgk_pairs_nodal", "mgk_normalize_gram",
+    "mgk_batch_get_tiles", "mgk_gram", "mgk_pairs", "mgk_pairs_dev", "mgk_pairs_noalloc", "mgk_pairs_nodal", "mgk_normalize_gram",
 ]
 
 
@@ -263,6 +263,19 @@ class Solver:
         if len(jj) != n:
             raise ValueError("index arrays differ in length")
         self._check(load_library().mgk_pairs(
+            self._h, X._h, Y._h, n, pi, pj, _dev_ptr(K, "float32", n),
+            _dev_ptr(iters, "int32", n), _dev_ptr(flags, "int32", n), _stream_ptr(stream)))
+
+    def pairs_noalloc(self, X: Batch, Y: Batch, i_idx: Sequence[int], j_idx: Sequence[int], K,
+                      iters=None, flags=None, stream=None):
+        """As pairs(), without any device allocation inside the library (on-chip pairs only,
+        at most 65536 per call)."""
+        ii, pi = _host(i_idx, np.int32)
+        jj, pj = _host(j_idx, np.int32)
+        n = len(ii)
+        if len(jj) != n:
+            raise ValueError("index arrays differ in length")
+        self._check(load_library().mgk_pairs_noalloc(
             self._h, X._h, Y._h, n, pi, pj, _dev_ptr(K, "float32", n),
             _dev_ptr(iters, "int32", n), _dev_ptr(flags, "int32", n), _stream_ptr(stream)))
 

@@ -23,6 +23,7 @@ DEVICE_SOURCES += [("mgk_regs.hip", "w%dc%d" % (w, c), ["-DMGK_REGS_WAVES=%d" % 
                    for w in (4, 8) for c in (1, 2)]
 DEVICE_SOURCES += [("mgk_sell.hip", "w%d" % w, ["-DMGK_SELL_WAVES=%d" % w]) for w in (8, 4, 16)]
 DEVICE_SOURCES.append(("mgk_large.hip", "all", []))
+DEVICE_SOURCES.append(("mgk_noalloc.hip", "all", []))
 HOST_SOURCES = ["mgk_host.cpp", "mgk_reorder.cpp"]
 
 # packed fp32 instructions are switched off on purpose for the test machines

@@ -99,6 +99,8 @@ struct mgk_ctx {
     int64_t pair_jobs_cap = 0;
     hipStream_t pair_jobs_stream = nullptr;
     bool pair_jobs_busy = false;
+    hipStream_t fixed_jobs_stream = nullptr;   // last mgk_pairs_noalloc call of this context
+    bool fixed_jobs_busy = false;
     // scratch of the global-memory solver
     DevBuf exp_outer[2], exp_inner[2];  // expanded entry lists of batch X / batch Y
     DevBuf dense_tiles[2][3];           // dense 8x8 expansions (weight, label, log2 weight)
@@ -451,8 +453,10 @@ void merge_small_shapes(std::vector<HostJob>& jobs) {
     }
 }
 
+// `fixed`: the job array is storage the caller provides (`out.dev` set, *capacity jobs);
+// nothing is allocated or freed then.
 mgk_status build_job_list(mgk_ctx* ctx, std::vector<HostJob>& jobs, JobList& out,
-                          hipStream_t stream, int64_t* capacity) {
+                          hipStream_t stream, int64_t* capacity, bool fixed = false) {
     merge_small_shapes(jobs);
     // group by launch shape (largest first), inside a group big pairs start first
     const bool by_cost = ctx->cost_sorted != 0;
@@ -490,7 +494,10 @@ mgk_status build_job_list(mgk_ctx* ctx, std::vector<HostJob>& jobs, JobList& out
         b.count++;
         b.lds_bytes = std::max(b.lds_bytes, (size_t)jobs[k].lds_words * 4);
     }
-    if (capacity == nullptr || *capacity < out.n) {
+    if (fixed) {
+        if (out.n > *capacity) return fail(ctx, MGK_ELIMIT, "job list of %lld pairs exceeds the fixed storage of %lld",
+                                           (long long)out.n, (long long)*capacity);
+    } else if (capacity == nullptr || *capacity < out.n) {
         if (out.dev) MGK_HIP(ctx, hipFree(out.dev));
         out.dev = nullptr;
         const int64_t cap = std::max<int64_t>(out.n, 1);
@@ -1439,10 +1446,13 @@ static mgk_status gram_body(mgk_ctx* ctx, mgk_batch* batch, float* K_dev, int32_
     return launch_jobs(ctx, batch, batch, batch->gram_jobs, out, stream);
 }
 
+// no_alloc: the job list goes to the fixed device array of mgk_noalloc.hip, pairs that need
+// the global-memory solver (whose vectors the library would allocate) are refused, and no
+// HIP allocation call is made on any path.
 static mgk_status pairs_impl(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
                              const int32_t* i_host, const int32_t* j_host, float* K_dev,
                              float* x_dev, const int64_t* x_off_host, int32_t* iters_dev,
-                             int32_t* flag_dev, void* stream_) {
+                             int32_t* flag_dev, void* stream_, bool no_alloc = false) {
     if (!ctx || !X || !Y) return fail(ctx, MGK_EINVAL, "null argument");
     if (X->owner != ctx || Y->owner != ctx) return fail(ctx, MGK_ESTATE, "batch belongs to another context");
     if (ctx->device < 0) return fail(ctx, MGK_ESTATE, "host-only context cannot solve");
@@ -1476,6 +1486,9 @@ static mgk_status pairs_impl(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n
         hj.atomic_rows = pl.atomic_rows;
         hj.swapped = pl.swap && X != Y;
         if (pl.waves == 0) {
+            if (no_alloc)
+                return fail(ctx, MGK_ELIMIT, "pair %lld (%d x %d vertices) needs the global-memory solver, "
+                            "which allocates its vectors", (long long)k, X->graphs[i].n, Y->graphs[j].n);
             if ((int64_t)X->graphs[i].n * Y->graphs[j].n >= ((int64_t)1 << 31) - 64)
                 return fail(ctx, MGK_ELIMIT, "pair %lld is too large", (long long)k);
             bool sw;
@@ -1493,6 +1506,24 @@ static mgk_status pairs_impl(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n
     jobs.erase(std::remove_if(jobs.begin(), jobs.end(), [](const HostJob& h) { return h.waves == 0; }),
                jobs.end());
     MgkOutputs out{K_dev, iters_dev, flag_dev, nullptr, nullptr};
+    if (no_alloc) {
+        // Job list in the fixed array of this GPU.  All calls on the GPU share it: a call
+        // that overlaps another one's kernels would overwrite the jobs they still read,
+        // so within this context the previous such call is waited for first.
+        if (ctx->fixed_jobs_busy) {
+            MGK_HIP(ctx, hipStreamSynchronize(ctx->fixed_jobs_stream));
+            ctx->fixed_jobs_busy = false;
+        }
+        JobList fixed;
+        int64_t cap = 0;
+        hipError_t e = mgk_noalloc_job_storage(ctx->device, &fixed.dev, &cap);
+        if (e != hipSuccess) return fail(ctx, MGK_EDEVICE, "fixed job storage: %s", hipGetErrorString(e));
+        mgk_status st = build_job_list(ctx, jobs, fixed, stream, &cap, true);
+        if (st != MGK_OK) return st;
+        ctx->fixed_jobs_stream = stream;
+        ctx->fixed_jobs_busy = true;
+        return launch_jobs(ctx, X, Y, fixed, out, stream);
+    }
     mgk_status st = build_job_list(ctx, jobs, ctx->pair_jobs, stream, &ctx->pair_jobs_cap);
     if (st != MGK_OK) return st;
     for (int a = 0; a < 2; ++a)
@@ -1536,6 +1567,18 @@ mgk_status mgk_pairs_dev(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pai
         MGK_HIP(ctx, hipStreamSynchronize(stream));
         return pairs_impl(ctx, X, Y, n_pairs, ij.data(), ij.data() + n_pairs, K_dev, nullptr, nullptr, iters_dev,
                           flag_dev, stream_);
+    });
+}
+
+mgk_status mgk_pairs_noalloc(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_pairs,
+                             const int32_t* i_host, const int32_t* j_host, float* K_dev, int32_t* iters_dev,
+                             int32_t* flag_dev, void* stream_) {
+    return guarded(ctx, [&]() -> mgk_status {
+        if (n_pairs > MGK_NOALLOC_MAX_PAIRS)
+            return fail(ctx, MGK_ELIMIT, "mgk_pairs_noalloc takes at most %d pairs per call, got %lld",
+                        MGK_NOALLOC_MAX_PAIRS, (long long)n_pairs);
+        return pairs_impl(ctx, X, Y, n_pairs, i_host, j_host, K_dev, nullptr, nullptr, iters_dev, flag_dev, stream_,
+                          true);
     });
 }
 

@@ -108,6 +108,11 @@ static inline hipError_t mgk_launch_sell(int waves, int ept, int regs, const Mgk
     }
 }
 
+// Fixed job-list array in device memory for the entry point that allocates nothing
+// (mgk_noalloc.hip): its device address on `device` and how many jobs it holds.
+#define MGK_NOALLOC_MAX_PAIRS 65536
+hipError_t mgk_noalloc_job_storage(int device, MgkJob** jobs, int64_t* capacity);
+
 // ---- solver with vectors in global memory (mgk_large.hip) --------------------
 // Expand every octile of batch B into the outer (CSR order) and inner (lane
 // layout) entry lists; `outer` holds B.nnz_total entries, `inner` B.lanes_total.
