@@ -30,16 +30,35 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3   # MI355X published fp32 vector peak (packed FM
 FLOPS_PER_ELEMENT_PAIR = 8        # SE-labeled element pair: 3 + kappa_e (sub, square, scale, exp, mul)
 
 
+def _is_named_workload(workload, args):
+    return (args.graphs == 2000 and args.product_cache == 1 and not args.waves and args.edge_kernel == "se"
+            and args.reorder == 1 and args.tile_path == 0)
+
+
 def hbm_traffic(workload, args):
     """HBM bytes per step from the committed counter summary (two rocprofv3 --pmc
-    runs, FETCH_SIZE and WRITE_SIZE, each scaled by what the counter reads for a
-    copy of known size).  Only for the exact workload it was measured on."""
-    path = os.path.join(ROOT, "profiles", "mgk_pcg_regs_config4_hbm.json")
-    if (workload != "config4" or args.graphs != 2000 or not args.product_cache or args.waves
-            or args.edge_kernel != "se" or not os.path.exists(path)):
+    runs of this very command, FETCH_SIZE and WRITE_SIZE, each scaled by what the
+    counter reads for a copy of known size).  Counters cannot be read from inside this
+    process, so the figure is only given for the exact workloads and default settings it
+    was measured on (profiles/hbm_traffic.json names the command of every entry)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not _is_named_workload(workload, args) or not os.path.exists(path):
         return None
     with open(path) as fh:
-        return json.load(fh)["bytes_per_step"]
+        entry = json.load(fh).get(workload)
+    return entry["bytes_per_step"] if entry else None
+
+
+def counted_flops(workload, args):
+    """fp32 flops per step executed by the vector ALUs, from the committed rocprofv3 counter
+    summary of this command (SQ_INSTS_VALU_ADD_F32 + MUL_F32 + 2 FMA_F32 + TRANS_F32 wave
+    instructions x 64 lanes); same restriction as hbm_traffic."""
+    path = os.path.join(ROOT, "profiles", "valu_flops.json")
+    if not _is_named_workload(workload, args) or not os.path.exists(path):
+        return None
+    with open(path) as fh:
+        entry = json.load(fh).get(workload)
+    return entry["flops_per_step"] if entry else None
 
 
 def _time_steps(torch, step, steps):
@@ -306,7 +325,7 @@ def main() -> int:
             "rtol": 1e-6, "reorder": {0: "none", 1: "pbr", 2: "rcm"}[args.reorder],
             "waves_per_pair": args.waves or "auto",
             "tile_path": {0: "auto", 1: "sparse", 2: "dense", 3: "sparse, global gathers"}[args.tile_path],
-            "product_cache": bool(args.product_cache),
+            "product_cache": int(args.product_cache),
         },
         "matvec_element_pairs_per_s": element_pairs / kernel_s,
         "mean_iterations": pair_iterations / n_pairs,
@@ -314,21 +333,58 @@ def main() -> int:
         "not_converged": not_converged,
         "tiles": stats["n_tiles"], "offdiag_tiles": stats["n_offdiag_tiles"], "nnz": stats["nnz"],
         "load_and_pack_s": load_s, "first_call_s": first_s,
-        "roofline": {
-            "bound": "alu",
-            "kernel": ("mgk_pcg_regs" if wl in ("config4", "config1") and args.product_cache and not args.waves
-                       else "mgk_pcg_small" if wl in ("config4", "config1", "nws", "ba")
-                       else "mgk_pcg_regs / mgk_pcg_small" if wl == "config0"
-                       else "mgk_large_xmv_rows_kernel / mgk_large_xmv_dense_kernel (+ vector kernels)"),
-            "achieved": achieved_tflops,
-            "peak": FP32_VECTOR_PEAK_TFLOPS,
-            "unit": "TFLOP/s",
-            "frac": achieved_tflops / FP32_VECTOR_PEAK_TFLOPS,
-            "traffic": hbm_traffic(wl, args),
-            "flops_per_element_pair": flops_per_element_pair,
-            "element_pairs_per_step": element_pairs,
-            "kernel_ms_per_step": kernel_s * 1e3,
-        },
+        "roofline": None,
+    }
+    # which kernels ran: from the library's own record of the launches of the last step
+    launches = [ln for ln in solver.launch_log().splitlines() if ln.strip()]
+
+    def _pairs_of(ln):
+        for tok in ln.split():
+            if tok.startswith("pairs="):
+                return int(tok[6:])
+        return 0
+
+    dominant = max(launches, key=_pairs_of).split(" pairs=")[0] if launches else "none"
+    families = sorted({ln.split("<")[0].split(" ")[0] for ln in launches})
+    cached_pairs = sum(_pairs_of(ln) for ln in launches if "entries_cached=1" in ln)
+    entries_cached = cached_pairs > 0
+    # Executed flops of the product.  Entries regenerated (Alg. 2 as printed): the algorithmic
+    # count per element pair and iteration.  Entries cached in registers: one multiply-add
+    # (2 flop) per element pair and iteration, plus the one-off generation of each entry.
+    zz = float((z[pi] * z[pj]).sum())
+    if entries_cached and cached_pairs == n_pairs:
+        executed_flops = 2.0 * element_pairs + (flops_per_element_pair - 2) * zz
+        executed_per_pair_iter = 2
+    elif not entries_cached:
+        executed_flops = alg_flops
+        executed_per_pair_iter = flops_per_element_pair
+    else:
+        executed_flops = None       # mixed launch: no single figure
+        executed_per_pair_iter = None
+    traffic = hbm_traffic(wl, args)
+    cflops = counted_flops(wl, args)
+    out["roofline"] = {
+        "bound": "alu",
+        "kernel": dominant,
+        "kernel_families": families,
+        "launch_shapes": len(launches),
+        "entries_cached": entries_cached,
+        "achieved": achieved_tflops,
+        "peak": FP32_VECTOR_PEAK_TFLOPS,
+        "unit": "TFLOP/s",
+        "frac": achieved_tflops / FP32_VECTOR_PEAK_TFLOPS,
+        "frac_is": "algorithmic: %d flop per element pair and iteration (the paper's cost model for "
+                   "this edge kernel) x element pairs / kernel time / peak" % flops_per_element_pair,
+        "flops_per_element_pair": flops_per_element_pair,
+        "executed_flops_per_element_pair": executed_per_pair_iter,
+        "frac_executed": (executed_flops / kernel_s / 1e12 / FP32_VECTOR_PEAK_TFLOPS
+                          if executed_flops is not None else None),
+        "frac_executed_counters": (cflops / kernel_s / 1e12 / FP32_VECTOR_PEAK_TFLOPS
+                                   if cflops is not None else None),
+        "traffic": traffic,
+        "hbm_GBps": traffic / kernel_s / 1e9 if traffic is not None else None,
+        "element_pairs_per_step": element_pairs,
+        "kernel_ms_per_step": kernel_s * 1e3,
     }
 
     if args.cpu_sample > 0:

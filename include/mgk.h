@@ -28,14 +28,22 @@
  *  - A ctx is bound to one device and is not thread-safe.  Batches belong to
  *    the ctx that loaded them.
  *  - Calls that include pairs too large for the on-chip solver synchronise the
- *    stream before returning (the host watches how many of them still iterate)
+ *    stream before returning (iterations are enqueued without waiting, as many
+ *    as the previous such call needed; then the host reads how many pairs still
+ *    iterate, normally once per call)
  *    and allocate device scratch owned by the ctx (5 vectors of n n' floats per
  *    such pair, plus expanded nonzero lists of the batches).  Such pairs are
  *    solved in groups of at most 4096 pairs and 8 GiB of vectors.
  *  - Non-convergence is data, not an error: the pair's flag is set to 1 and the
  *    value of the last iterate is still written.  Flag 2 with a NaN value marks
  *    a pair that a kernel refused because it did not fit the launch shape the
- *    host chose for it (an internal error; it is never solved in part).
+ *    host chose for it (an internal error; it is never solved in part).  Flag 3
+ *    (pairs solved with vectors in global memory): the iteration met the stop
+ *    test of Alg. 1 on its recursively updated residual, but the solution is
+ *    more than 32 times the Jacobi guess M^{-1} b somewhere and the residual
+ *    b - S x recomputed with one more product is so large in fp32 that the
+ *    value may be off by more than 1e-4 relative (an ill-conditioned pair, for
+ *    example a dense graph against itself with all base kernels equal to 1).
  *  - Precision: fp32 on the device.  Product index of (i,i') is i*n'+i'.
  */
 #ifndef MGK_H
@@ -245,6 +253,14 @@ mgk_status mgk_pairs_nodal(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_p
                            const int32_t* i_host, const int32_t* j_host, float* K_dev, float* x_dev,
                            const int64_t* x_off_host, int32_t* iters_dev, int32_t* flag_dev,
                            void* stream);
+
+/* Which kernels the last mgk_gram / mgk_pairs* call on ctx enqueued (for measurement
+ * reports): one text line per launch shape, "<kernel and template arguments> pairs=<n>
+ * entries_cached=<0|1>" (entries_cached: the off-diagonal entries are kept in registers
+ * instead of being regenerated in every product of Alg. 2).  Copies at most capacity - 1
+ * characters and a terminating 0 into buf (host memory, may be NULL) and returns the size
+ * needed including the 0, or -1 for a null ctx. */
+int64_t mgk_launch_log(const mgk_ctx* ctx, char* buf, int64_t capacity);
 
 /* Normalised Gram matrix (Section "Related Work"): K[i][j] /= sqrt(K[i][i] K[j][j])
  * in place on the n x n row-major device matrix K_dev. */

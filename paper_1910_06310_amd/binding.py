@@ -28,7 +28,7 @@ EXPORTS = [
     "mgk_set_stop_prob", "mgk_set_solver", "mgk_set_tile_path", "mgk_set_launch",
     "mgk_set_onchip_limit", "mgk_set_product_cache", "mgk_set_schedule",
     "mgk_load_graphs", "mgk_free_batch", "mgk_batch_stats", "mgk_batch_permutation",
-    "mgk_batch_get_tiles", "mgk_gram", "mgk_pairs", "mgk_pairs_dev", "mgk_pairs_noalloc", "mgk_pairs_nodal", "mgk_normalize_gram",
+    "mgk_batch_get_tiles", "mgk_gram", "mgk_pairs", "mgk_pairs_dev", "mgk_pairs_noalloc", "mgk_pairs_nodal", "mgk_normalize_gram", "mgk_launch_log",
 ]
 
 
@@ -79,11 +79,16 @@ def load_library(path: Optional[str] = None):
     lib.mgk_batch_get_tiles.argtypes = [vp, i32, c.POINTER(i32), c.POINTER(i32), vp, vp, vp, vp, vp]
     lib.mgk_gram.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.mgk_pairs.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp, vp]
+    lib.mgk_pairs_dev.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp, vp]
+    lib.mgk_pairs_noalloc.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp, vp]
     lib.mgk_pairs_nodal.argtypes = [vp, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.mgk_launch_log.argtypes = [vp, vp, i64]
     lib.mgk_normalize_gram.argtypes = [vp, i32, vp, vp]
     for name in EXPORTS:
         fn = getattr(lib, name)
-        if name not in ("mgk_destroy", "mgk_free_batch", "mgk_last_error"):
+        if name == "mgk_launch_log":
+            fn.restype = c.c_int64
+        elif name not in ("mgk_destroy", "mgk_free_batch", "mgk_last_error"):
             fn.restype = c.c_int
     _lib = lib
     return lib
@@ -305,6 +310,14 @@ class Solver:
         self._check(load_library().mgk_pairs_nodal(
             self._h, X._h, Y._h, n, pi, pj, _dev_ptr(K, "float32", n), _dev_ptr(x, "float32", need), po,
             _dev_ptr(iters, "int32", n), _dev_ptr(flags, "int32", n), _stream_ptr(stream)))
+
+    def launch_log(self) -> str:
+        """Kernels the last gram / pairs call enqueued, one line per launch shape."""
+        lib = load_library()
+        need = int(lib.mgk_launch_log(self._h, None, ctypes.c_int64(0)))
+        buf = ctypes.create_string_buffer(max(need, 1))
+        lib.mgk_launch_log(self._h, buf, ctypes.c_int64(len(buf)))
+        return buf.value.decode()
 
     def normalize_gram(self, n: int, K, stream=None):
         self._check(load_library().mgk_normalize_gram(self._h, n, _dev_ptr(K, "float32", n * n),

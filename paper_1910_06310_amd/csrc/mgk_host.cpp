@@ -105,7 +105,13 @@ struct mgk_ctx {
     DevBuf exp_outer[2], exp_inner[2];  // expanded entry lists of batch X / batch Y
     DevBuf dense_tiles[2][3];           // dense 8x8 expansions (weight, label, log2 weight)
     DevBuf vec, lpairs, lstate, lactive, nodal_off, diag;
-    int* active_host = nullptr;         // pinned
+    int* active_host = nullptr;         // pinned: {pairs still iterating, most iterations needed}
+    void* pin = nullptr;                // pinned staging of the pair records of a call
+    size_t pin_cap = 0;
+    hipEvent_t pin_event = nullptr;     // recorded after the last copy out of `pin`
+    bool pin_busy = false;
+    int large_iter_guess = 12;          // iterations the last call of the global-memory solver needed
+    std::string launch_log;             // kernels the last solve call enqueued, one line each
 };
 
 namespace {
@@ -120,6 +126,16 @@ mgk_status fail(mgk_ctx* ctx, mgk_status st, const char* fmt, ...) noexcept {
         try { ctx->err = buf; } catch (...) { ctx->err.clear(); }   // capacity is reserved at creation
     }
     return st;
+}
+
+void log_launch(mgk_ctx* ctx, const char* fmt, ...) {
+    char buf[256];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    ctx->launch_log += buf;
+    ctx->launch_log += '\n';
 }
 
 #define MGK_HIP(ctx, call)                                                              \
@@ -654,28 +670,59 @@ mgk_status solve_large(mgk_ctx* ctx, const mgk_batch* A, const mgk_batch* Bb, in
     MgkPairState* dstate = (MgkPairState*)ctx->lstate.p;
     int* dactive = (int*)ctx->lactive.p;
     float* vec = (float*)ctx->vec.p;
-    MGK_HIP(ctx, hipMemcpyAsync(dpairs, pairs.data(), (size_t)n_pairs * sizeof(MgkLargePair),
-                                hipMemcpyHostToDevice, stream));
+    // The pair records go through pinned memory owned by the context, so that the copy needs
+    // no wait; the previous use of that buffer is waited for instead (long finished).
+    {
+        const size_t bytes = (size_t)n_pairs * sizeof(MgkLargePair);
+        if (ctx->pin_busy) {
+            MGK_HIP(ctx, hipEventSynchronize(ctx->pin_event));
+            ctx->pin_busy = false;
+        }
+        if (bytes > ctx->pin_cap) {
+            if (ctx->pin) MGK_HIP(ctx, hipHostFree(ctx->pin));
+            ctx->pin = nullptr;
+            ctx->pin_cap = 0;
+            MGK_HIP(ctx, hipHostMalloc(&ctx->pin, bytes, hipHostMallocDefault));
+            ctx->pin_cap = bytes;
+        }
+        if (!ctx->pin_event) MGK_HIP(ctx, hipEventCreateWithFlags(&ctx->pin_event, hipEventDisableTiming));
+        memcpy(ctx->pin, pairs.data(), bytes);
+        MGK_HIP(ctx, hipMemcpyAsync(dpairs, ctx->pin, bytes, hipMemcpyHostToDevice, stream));
+    }
     MGK_HIP(ctx, hipMemsetAsync(dstate, 0, (size_t)n_pairs * sizeof(MgkPairState), stream));
-    *ctx->active_host = n_pairs;
-    MGK_HIP(ctx, hipMemcpyAsync(dactive, ctx->active_host, sizeof(int), hipMemcpyHostToDevice, stream));
-    MGK_HIP(ctx, hipStreamSynchronize(stream));  // `pairs` and active_host are reused below
+    ctx->active_host[0] = n_pairs;   // pairs still iterating
+    ctx->active_host[1] = 0;         // most iterations any pair needed
+    MGK_HIP(ctx, hipMemcpyAsync(dactive, ctx->active_host, 2 * sizeof(int), hipMemcpyHostToDevice, stream));
+    MGK_HIP(ctx, hipEventRecord(ctx->pin_event, stream));
+    ctx->pin_busy = true;
     hipError_t e = mgk_launch_large_init(A->dev, Bb->dev, dpairs, dstate, vec, prm, n_pairs, vec_blocks, stream);
     if (e != hipSuccess) return fail(ctx, MGK_EDEVICE, "init launch failed: %s", hipGetErrorString(e));
-    const int check_every = 4;
-    for (int it = 0; it < max_iter; ++it) {
-        e = mgk_launch_large_iteration(A->dev, Bb->dev, ex[0], ex[1], dpairs, dstate, vec, prm, weighted,
-                                       n_pairs, xmv_blocks, vec_blocks, dactive, it == 0,
-                                       dense ? &dt[0] : nullptr, dense ? &dt[1] : nullptr, rows_threads,
-                                       rows_lds_bytes, rows_chunks, stream);
-        if (e != hipSuccess) return fail(ctx, MGK_EDEVICE, "iteration launch failed: %s", hipGetErrorString(e));
-        if ((it + 1) % check_every == 0 || it + 1 == max_iter) {
-            MGK_HIP(ctx, hipMemcpyAsync(ctx->active_host, dactive, sizeof(int), hipMemcpyDeviceToHost, stream));
-            MGK_HIP(ctx, hipStreamSynchronize(stream));
-            if (*ctx->active_host <= 0) break;
+    // The kernels of an iteration return at once for pairs that have stopped, so iterations
+    // are enqueued without waiting: as many as the previous call of this kind needed, then
+    // the host reads how many pairs still iterate, and goes on four at a time if any do.
+    int it = 0;
+    const int first_batch = std::max(1, std::min(max_iter, ctx->large_iter_guess));
+    while (it < max_iter) {
+        const int upto = it == 0 ? first_batch : std::min(max_iter, it + 4);
+        for (; it < upto; ++it) {
+            e = mgk_launch_large_iteration(A->dev, Bb->dev, ex[0], ex[1], dpairs, dstate, vec, prm, weighted,
+                                           n_pairs, xmv_blocks, vec_blocks, dactive, it,
+                                           dense ? &dt[0] : nullptr, dense ? &dt[1] : nullptr, rows_threads,
+                                           rows_lds_bytes, rows_chunks, stream);
+            if (e != hipSuccess) return fail(ctx, MGK_EDEVICE, "iteration launch failed: %s", hipGetErrorString(e));
         }
+        MGK_HIP(ctx, hipMemcpyAsync(ctx->active_host, dactive, 2 * sizeof(int), hipMemcpyDeviceToHost, stream));
+        MGK_HIP(ctx, hipStreamSynchronize(stream));
+        ctx->pin_busy = false;
+        if (ctx->active_host[0] <= 0) break;
     }
-    e = mgk_launch_large_final(A->dev, Bb->dev, dpairs, dstate, vec, n_pairs, vec_blocks, out, stream);
+    if (ctx->active_host[0] <= 0) ctx->large_iter_guess = std::max(1, ctx->active_host[1]);
+    log_launch(ctx, "%s pairs=%d iterations_enqueued=%d entries_cached=0 (+ mgk_large_dot / update / pupdate per iteration)",
+               dense ? "mgk_large_xmv_dense_kernel" : rows_threads > 0 ? "mgk_large_xmv_rows_kernel" : "mgk_large_xmv_kernel",
+               n_pairs, it);
+    e = mgk_launch_large_final(A->dev, Bb->dev, ex[0], ex[1], dpairs, dstate, vec, prm, weighted, n_pairs, xmv_blocks,
+                               vec_blocks, dense ? &dt[0] : nullptr, dense ? &dt[1] : nullptr, rows_threads,
+                               rows_lds_bytes, rows_chunks, out, stream);
     if (e != hipSuccess) return fail(ctx, MGK_EDEVICE, "final launch failed: %s", hipGetErrorString(e));
     return MGK_OK;
 }
@@ -684,7 +731,16 @@ mgk_status launch_jobs(mgk_ctx* ctx, const mgk_batch* X, const mgk_batch* Y, con
                        const MgkOutputs& out, hipStream_t stream) {
     const MgkParams prm = make_params(ctx, X);
     const bool weighted = X->weighted || Y->weighted;
+    ctx->launch_log.clear();
     for (const JobBin& b : jl.bins) {
+        if (b.sell_regs > 0)
+            log_launch(ctx, "mgk_pcg_sell<%d, %d, %d> pairs=%lld entries_cached=1", b.waves, b.ept, b.sell_regs, (long long)b.count);
+        else if (b.chunks > 0)
+            log_launch(ctx, "mgk_pcg_regs<%d, %d, %d, %d> pairs=%lld entries_cached=1", b.waves,
+                       b.waves == 4 ? MGK_REGS_SMAX_W4 : MGK_REGS_SMAX_W8, b.ept, b.chunks, (long long)b.count);
+        else
+            log_launch(ctx, "mgk_pcg_small<%d, %d%s> pairs=%lld entries_cached=0", b.waves, b.ept,
+                       b.atomic_rows ? ", atomic rows" : "", (long long)b.count);
         int64_t done = 0;
         while (done < b.count) {  // grid dimension limit
             const int64_t chunk = std::min<int64_t>(b.count - done, (int64_t)1 << 30);
@@ -761,6 +817,8 @@ void mgk_destroy(mgk_ctx* ctx) {
                       &ctx->dense_tiles[1][0], &ctx->dense_tiles[1][1], &ctx->dense_tiles[1][2]})
         if (b->p) (void)hipFree(b->p);
     if (ctx->active_host) (void)hipHostFree(ctx->active_host);
+    if (ctx->pin) (void)hipHostFree(ctx->pin);
+    if (ctx->pin_event) (void)hipEventDestroy(ctx->pin_event);
     delete ctx;
 }
 
@@ -1590,6 +1648,17 @@ mgk_status mgk_pairs_nodal(mgk_ctx* ctx, mgk_batch* X, mgk_batch* Y, int64_t n_p
     return guarded(ctx, [&] {
         return pairs_impl(ctx, X, Y, n_pairs, i_host, j_host, K_dev, x_dev, x_off_host, iters_dev, flag_dev, stream_);
     });
+}
+
+int64_t mgk_launch_log(const mgk_ctx* ctx, char* buf, int64_t capacity) {
+    if (!ctx) return -1;
+    const int64_t need = (int64_t)ctx->launch_log.size() + 1;
+    if (buf && capacity > 0) {
+        const int64_t n = std::min<int64_t>(capacity - 1, (int64_t)ctx->launch_log.size());
+        memcpy(buf, ctx->launch_log.data(), (size_t)n);
+        buf[n] = 0;
+    }
+    return need;
 }
 
 mgk_status mgk_normalize_gram(mgk_ctx* ctx, int32_t n, float* K_dev, void* stream_) {

@@ -413,10 +413,28 @@ struct MgkLargePair {
     int32_t atomic_rows;   // inner graph has rows longer than a lane group
 };
 
+// Scalars of one pair in the global-memory solver.  The three sums of iteration `it` go
+// to slot it & 1 of their pair of accumulators; the other slot is cleared meanwhile, by a
+// kernel that runs when nobody reads it (no separate scalar kernels, no host round trip):
+//   rz[it & 1]        r^T z after the update of iteration it; rz[(it + 1) & 1] is the one
+//                     of the iteration before (rho of Alg. 1; the set-up puts it in rz[1])
+//   pa[it & 1]        p^T a of iteration it
+//   rr[it & 1]        r^T r after the update of iteration it
 struct MgkPairState {
-    float rho, pa, rz, rr, thresh, alpha, beta, kval;
-    int32_t iters, done, flag, pad;
+    float rz[2], pa[2], rr[2];
+    float bb;       // b^T b
+    float kval;
+    int32_t iters, done, flag;
+    int32_t growth; // bits of max_i x_i / (M^{-1} b)_i >= 1: how far the solution exceeds the Jacobi guess
 };
+
+// A pair whose solution exceeds M^{-1} b by more than this factor somewhere is checked
+// after the solve: one more product gives the true residual b - S x in fp32, and if
+// (true relative residual) x (that factor) exceeds MGK_VERIFY_ACCURACY the pair's flag
+// becomes 3.  Below the threshold even a residual at fp32 rounding level cannot move the
+// value by that much, so nothing is checked.
+#define MGK_VERIFY_GROWTH 32.0f
+#define MGK_VERIFY_ACCURACY 1e-4f
 
 #define MGK_LARGE_ROWS_PER_BLOCK 8    // outer rows per workgroup of the large XMV
 #define MGK_LARGE_CHUNKS_PER_WAVE 2   // 64-lane chunks of the inner layout per wave

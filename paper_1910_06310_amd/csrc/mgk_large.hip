@@ -126,8 +126,8 @@ __global__ __launch_bounds__(256) void mgk_large_init_kernel(MgkBatchDev X, MgkB
         s_rz = __builtin_fmaf(b, z0, s_rz);
         s_bb = __builtin_fmaf(b, b, s_bb);
     }
-    block_accumulate(s_rz, &state[blockIdx.y].rho, red);
-    block_accumulate(s_bb, &state[blockIdx.y].thresh, red);  // scaled by rtol^2 in the first scalar step
+    block_accumulate(s_rz, &state[blockIdx.y].rz[1], red);   // rho of iteration 0
+    block_accumulate(s_bb, &state[blockIdx.y].bb, red);
 }
 
 // ---- XMV ---------------------------------------------------------------------------
@@ -650,10 +650,14 @@ __global__ __launch_bounds__(256) void mgk_large_xmv_dense_kernel(
 }
 
 // ---- p^T a with a = M p - y ---------------------------------------------------------
+// Also clears the accumulators of r^T z and r^T r that the update of this iteration adds to
+// (their values, from two iterations ago, were last read by the kernel before this one).
 __global__ __launch_bounds__(256) void mgk_large_dot_kernel(const MgkLargePair* pairs,
-                                                            MgkPairState* state, const float* vec) {
+                                                            MgkPairState* state, const float* vec, int it) {
     __shared__ float red[8];
-    if (state[blockIdx.y].done) return;
+    MgkPairState& st = state[blockIdx.y];
+    if (st.done) return;
+    if (blockIdx.x == 0 && threadIdx.x == 0) { st.rz[it & 1] = 0.f; st.rr[it & 1] = 0.f; }
     const MgkLargePair P = pairs[blockIdx.y];
     const float* p = vec + P.vec + 2 * (int64_t)P.npad;
     const float* M = p + P.npad;
@@ -663,28 +667,19 @@ __global__ __launch_bounds__(256) void mgk_large_dot_kernel(const MgkLargePair* 
         const float pv = p[idx];
         s = __builtin_fmaf(pv, __builtin_fmaf(M[idx], pv, -y[idx]), s);
     }
-    block_accumulate(s, &state[blockIdx.y].pa, red);
+    block_accumulate(s, &st.pa[it & 1], red);
 }
 
-// scalar step 1: alpha = rho / p^T a
-__global__ void mgk_large_scalar1_kernel(MgkPairState* state, int n_pairs, float rtol2, int first) {
-    const int k = blockIdx.x * blockDim.x + threadIdx.x;
-    if (k >= n_pairs) return;
-    MgkPairState& s = state[k];
-    if (first) s.thresh *= rtol2;   // holds b^T b after the set-up kernel
-    if (s.done) return;
-    s.alpha = s.rho / s.pa;
-    s.rz = 0.f;
-    s.rr = 0.f;
-}
-
-// ---- x += alpha p; r -= alpha a; z = M^{-1} r (stored over y); rho' = r^T z; r^T r ----
+// ---- alpha = rho / p^T a; x += alpha p; r -= alpha a; z = M^{-1} r (stored over y);
+//      rho' = r^T z; r^T r.  Clears the accumulator of the next iteration's p^T a.
 __global__ __launch_bounds__(256) void mgk_large_update_kernel(const MgkLargePair* pairs,
-                                                               MgkPairState* state, float* vec) {
+                                                               MgkPairState* state, float* vec, int it) {
     __shared__ float red[8];
-    if (state[blockIdx.y].done) return;
+    MgkPairState& st = state[blockIdx.y];
+    if (st.done) return;
     const MgkLargePair P = pairs[blockIdx.y];
-    const float alpha = state[blockIdx.y].alpha;
+    const float alpha = st.rz[(it + 1) & 1] / st.pa[it & 1];
+    if (blockIdx.x == 0 && threadIdx.x == 0) st.pa[(it + 1) & 1] = 0.f;
     float* x = vec + P.vec;
     float* r = x + P.npad;
     const float* p = r + P.npad;
@@ -702,31 +697,34 @@ __global__ __launch_bounds__(256) void mgk_large_update_kernel(const MgkLargePai
         s_rz = __builtin_fmaf(rv, zv, s_rz);
         s_rr = __builtin_fmaf(rv, rv, s_rr);
     }
-    block_accumulate(s_rz, &state[blockIdx.y].rz, red);
-    block_accumulate(s_rr, &state[blockIdx.y].rr, red);
+    block_accumulate(s_rz, &st.rz[it & 1], red);
+    block_accumulate(s_rr, &st.rr[it & 1], red);
 }
 
-// scalar step 2: convergence test, beta = rho' / rho
-__global__ void mgk_large_scalar2_kernel(const MgkLargePair* pairs, MgkPairState* state, int n_pairs,
-                                         int* n_active) {
-    const int k = blockIdx.x * blockDim.x + threadIdx.x;
-    if (k >= n_pairs) return;
-    MgkPairState& s = state[k];
-    if (s.done) return;
-    s.iters += 1;
-    s.pa = 0.f;
-    if (s.rr <= s.thresh) { s.done = 1; s.flag = 0; atomicSub(n_active, 1); return; }
-    if (s.iters >= pairs[k].max_iter) { s.done = 1; s.flag = 1; atomicSub(n_active, 1); return; }
-    s.beta = s.rz / s.rho;
-    s.rho = s.rz;
-}
-
-// ---- p = z + beta p; y cleared for the next product ------------------------------------
+// ---- stop test; beta = rho' / rho; p = z + beta p; y cleared for the next product.
+// Every workgroup takes the same decision from the sums of this iteration, which no one
+// writes during this kernel; one thread per pair records it (a workgroup that starts after
+// that and sees the pair marked done would have stopped anyway).
 __global__ __launch_bounds__(256) void mgk_large_pupdate_kernel(const MgkLargePair* pairs,
-                                                                const MgkPairState* state, float* vec) {
-    if (state[blockIdx.y].done) return;
+                                                                MgkPairState* state, float* vec, int it,
+                                                                float rtol2, int* n_active) {
+    MgkPairState& st = state[blockIdx.y];
+    if (st.done) return;
     const MgkLargePair P = pairs[blockIdx.y];
-    const float beta = state[blockIdx.y].beta;
+    const float rz = st.rz[it & 1], rho = st.rz[(it + 1) & 1];
+    const bool converged = st.rr[it & 1] <= rtol2 * st.bb;
+    const bool stop = converged || it + 1 >= P.max_iter;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        st.iters = it + 1;
+        if (stop) {
+            st.flag = converged ? 0 : 1;
+            st.done = 1;
+            atomicSub(n_active, 1);
+            atomicMax(n_active + 1, it + 1);   // most iterations any pair of the call needed
+        }
+    }
+    if (stop) return;
+    const float beta = rz / rho;
     float* p = vec + P.vec + 2 * (int64_t)P.npad;
     float* y = p + 2 * (int64_t)P.npad;
     for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < P.npad; idx += gridDim.x * blockDim.x) {
@@ -735,11 +733,11 @@ __global__ __launch_bounds__(256) void mgk_large_pupdate_kernel(const MgkLargePa
     }
 }
 
-// ---- K = p_x^T x ---------------------------------------------------------------------------
+// ---- K = p_x^T x; the nodal solution; how far x exceeds the Jacobi guess M^{-1} b ------------
 __global__ __launch_bounds__(256) void mgk_large_final_kernel(MgkBatchDev X, MgkBatchDev Y,
                                                               const MgkLargePair* pairs,
                                                               MgkPairState* state, const float* vec,
-                                                              MgkOutputs out) {
+                                                              MgkOutputs out, MgkParams prm) {
     __shared__ float red[8];
     const MgkLargePair P = pairs[blockIdx.y];
     const int N = P.n1 * P.n2;
@@ -747,20 +745,75 @@ __global__ __launch_bounds__(256) void mgk_large_final_kernel(MgkBatchDev X, Mgk
     const float* x = vec + P.vec;
     float* nodal = out.nodal ? out.nodal + out.nodal_off[P.out0] : nullptr;
     const bool swapped = P.out1 == MGK_OUT1_SWAPPED;
-    float s = 0.f;
+    const float inv_qq = 1.0f / (prm.q * prm.q), inv_h = 1.0f / prm.h;
+    float s = 0.f, growth = 0.f;
     for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < N; idx += gridDim.x * blockDim.x) {
         const int i = idx / P.n2, ip = idx - i * P.n2;
         const float xv = x[idx];
         s = __builtin_fmaf(X.start[g1.voff + i] * Y.start[g2.voff + ip], xv, s);
+        // (M^{-1} b)_ii' = kappa_v q^2
+        const bool same = X.vlabel[g1.voff + i] == Y.vlabel[g2.voff + ip];
+        growth = fmaxf(growth, xv * inv_qq * (same ? 1.f : inv_h));
         if (nodal) {
             const int64_t oi = X.iperm[g1.voff + i], oip = Y.iperm[g2.voff + ip];
             nodal[swapped ? oip * P.n1 + oi : oi * P.n2 + oip] = xv;
         }
     }
+    // positive floats order like their bit patterns
+    growth = fmaxf(growth, 0.f);
+    for (int off = 32; off > 0; off >>= 1) growth = fmaxf(growth, __shfl_xor(growth, off));
+    if ((threadIdx.x & 63) == 0 && growth > 0.f) atomicMax(&state[blockIdx.y].growth, __float_as_int(growth));
     block_accumulate(s, &state[blockIdx.y].kval, red);
 }
 
-__global__ void mgk_large_store_kernel(const MgkLargePair* pairs, const MgkPairState* state,
+// ---- check of pairs with a large growth factor: y = XMV(x), true residual b - (M x - y) ----
+// Marks those pairs as running again (done = 0) with p = x and y = 0, so that the product
+// kernels of one more launch take them; all other pairs stay done.
+__global__ __launch_bounds__(256) void mgk_large_verify_prepare_kernel(const MgkLargePair* pairs,
+                                                                       MgkPairState* state, float* vec) {
+    MgkPairState& st = state[blockIdx.y];
+    if (__int_as_float(st.growth) <= MGK_VERIFY_GROWTH) return;
+    const MgkLargePair P = pairs[blockIdx.y];
+    const float* x = vec + P.vec;
+    float* p = vec + P.vec + 2 * (int64_t)P.npad;
+    float* y = p + 2 * (int64_t)P.npad;
+    for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < P.npad; idx += gridDim.x * blockDim.x) {
+        p[idx] = x[idx];
+        y[idx] = 0.f;
+    }
+    // every workgroup of the pair writes the same values; the product kernels come later
+    if (threadIdx.x == 0) { st.done = 0; st.rr[0] = 0.f; }
+}
+
+__global__ __launch_bounds__(256) void mgk_large_verify_residual_kernel(MgkBatchDev X, MgkBatchDev Y,
+                                                                        const MgkLargePair* pairs,
+                                                                        MgkPairState* state, const float* vec,
+                                                                        MgkParams prm) {
+    __shared__ float red[8];
+    MgkPairState& st = state[blockIdx.y];
+    if (st.done) return;   // only the pairs under check are marked as running
+    const MgkLargePair P = pairs[blockIdx.y];
+    const int N = P.n1 * P.n2;
+    const MgkGraphDesc g1 = X.graphs[P.g1], g2 = Y.graphs[P.g2];
+    const float* x = vec + P.vec;
+    const float* M = x + 3 * (int64_t)P.npad;
+    const float* y = M + P.npad;
+    const float qq = prm.q * prm.q;
+    float s = 0.f;
+    for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < N; idx += gridDim.x * blockDim.x) {
+        const int i = idx / P.n2, ip = idx - i * P.n2;
+        const bool same = X.vlabel[g1.voff + i] == Y.vlabel[g2.voff + ip];
+        const float m = M[idx];
+        const float b = m * (same ? qq : prm.h * qq);            // b = M kappa_v q^2 = d d' q^2
+        const float rho = b - __builtin_fmaf(m, x[idx], -y[idx]);
+        s = __builtin_fmaf(rho, rho, s);
+    }
+    block_accumulate(s, &st.rr[0], red);
+}
+
+// Per-pair outputs.  A checked pair whose true residual, times its growth factor, says that
+// the value may be off by more than MGK_VERIFY_ACCURACY gets flag 3.
+__global__ void mgk_large_store_kernel(const MgkLargePair* pairs, MgkPairState* state,
                                        int n_pairs, MgkOutputs out) {
     float* K = out.K;
     int32_t* iters = out.iters;
@@ -768,11 +821,18 @@ __global__ void mgk_large_store_kernel(const MgkLargePair* pairs, const MgkPairS
     const int k = blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= n_pairs) return;
     const MgkLargePair P = pairs[k];
-    const MgkPairState s = state[k];
+    MgkPairState& s = state[k];
+    int flag = s.flag;
+    if (!s.done) {   // was under check
+        const float growth = __int_as_float(s.growth);
+        const float rel = sqrtf(s.rr[0] / s.bb);
+        if (flag == 0 && rel * growth > MGK_VERIFY_ACCURACY) flag = 3;
+        s.done = 1;
+    }
     K[P.out0] = s.kval;
     if (P.out1 >= 0) K[P.out1] = s.kval;
     if (iters) { iters[P.out0] = s.iters; if (P.out1 >= 0) iters[P.out1] = s.iters; }
-    if (flags) { flags[P.out0] = s.flag; if (P.out1 >= 0) flags[P.out1] = s.flag; }
+    if (flags) { flags[P.out0] = flag; if (P.out1 >= 0) flags[P.out1] = flag; }
 }
 
 // ---- normalised Gram matrix: K_ij / sqrt(K_ii K_jj) --------------------------------------
@@ -833,14 +893,38 @@ hipError_t mgk_launch_large_init(const MgkBatchDev& X, const MgkBatchDev& Y, con
     return hipGetLastError();
 }
 
+static hipError_t launch_large_xmv(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkExpanded& EX,
+                                   const MgkExpanded& EY, const MgkLargePair* pairs,
+                                   MgkPairState* state, float* vec, const MgkParams& prm,
+                                   bool weighted, int n_pairs, int xmv_blocks, const MgkDenseTiles* DX,
+                                   const MgkDenseTiles* DY, int rows_threads, int rows_lds_bytes,
+                                   int rows_chunks, hipStream_t stream);
+
 hipError_t mgk_launch_large_iteration(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkExpanded& EX,
                                       const MgkExpanded& EY, const MgkLargePair* pairs,
                                       MgkPairState* state, float* vec, const MgkParams& prm,
                                       bool weighted, int n_pairs, int xmv_blocks, int vec_blocks,
-                                      int* n_active, bool first, const MgkDenseTiles* DX,
+                                      int* n_active, int it, const MgkDenseTiles* DX,
                                       const MgkDenseTiles* DY, int rows_threads, int rows_lds_bytes,
                                       int rows_chunks, hipStream_t stream) {
-    const dim3 gx(xmv_blocks, n_pairs), gv(vec_blocks, n_pairs), gs((n_pairs + 63) / 64);
+    const dim3 gv(vec_blocks, n_pairs);
+    hipError_t e = launch_large_xmv(X, Y, EX, EY, pairs, state, vec, prm, weighted, n_pairs, xmv_blocks, DX, DY,
+                                    rows_threads, rows_lds_bytes, rows_chunks, stream);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(mgk_large_dot_kernel, gv, dim3(256), 0, stream, pairs, state, vec, it);
+    hipLaunchKernelGGL(mgk_large_update_kernel, gv, dim3(256), 0, stream, pairs, state, vec, it);
+    hipLaunchKernelGGL(mgk_large_pupdate_kernel, gv, dim3(256), 0, stream, pairs, state, vec, it, prm.rtol2, n_active);
+    return hipGetLastError();
+}
+
+// The product y = XMV(p) for every pair that is marked as running.
+static hipError_t launch_large_xmv(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkExpanded& EX,
+                                   const MgkExpanded& EY, const MgkLargePair* pairs,
+                                   MgkPairState* state, float* vec, const MgkParams& prm,
+                                   bool weighted, int n_pairs, int xmv_blocks, const MgkDenseTiles* DX,
+                                   const MgkDenseTiles* DY, int rows_threads, int rows_lds_bytes,
+                                   int rows_chunks, hipStream_t stream) {
+    const dim3 gx(xmv_blocks, n_pairs);
     if (DX == nullptr && rows_threads > 0) {
         // xmv_blocks = largest number of outer rows of a pair
 #define MGK_ROWS_GO(WT, EKV, CBV, SLOT) \
@@ -889,19 +973,24 @@ hipError_t mgk_launch_large_iteration(const MgkBatchDev& X, const MgkBatchDev& Y
         }
 #undef MGK_XMV
     }
-    hipLaunchKernelGGL(mgk_large_dot_kernel, gv, dim3(256), 0, stream, pairs, state, vec);
-    hipLaunchKernelGGL(mgk_large_scalar1_kernel, gs, dim3(64), 0, stream, state, n_pairs, prm.rtol2, first ? 1 : 0);
-    hipLaunchKernelGGL(mgk_large_update_kernel, gv, dim3(256), 0, stream, pairs, state, vec);
-    hipLaunchKernelGGL(mgk_large_scalar2_kernel, gs, dim3(64), 0, stream, pairs, state, n_pairs, n_active);
-    hipLaunchKernelGGL(mgk_large_pupdate_kernel, gv, dim3(256), 0, stream, pairs, state, vec);
     return hipGetLastError();
 }
 
-hipError_t mgk_launch_large_final(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkLargePair* pairs,
-                                  MgkPairState* state, const float* vec, int n_pairs, int vec_blocks,
-                                  const MgkOutputs& out, hipStream_t stream) {
-    hipLaunchKernelGGL(mgk_large_final_kernel, dim3(vec_blocks, n_pairs), dim3(256), 0, stream, X, Y, pairs,
-                       state, vec, out);
+hipError_t mgk_launch_large_final(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkExpanded& EX,
+                                  const MgkExpanded& EY, const MgkLargePair* pairs, MgkPairState* state,
+                                  float* vec, const MgkParams& prm, bool weighted, int n_pairs, int xmv_blocks,
+                                  int vec_blocks, const MgkDenseTiles* DX, const MgkDenseTiles* DY,
+                                  int rows_threads, int rows_lds_bytes, int rows_chunks, const MgkOutputs& out,
+                                  hipStream_t stream) {
+    const dim3 gv(vec_blocks, n_pairs);
+    hipLaunchKernelGGL(mgk_large_final_kernel, gv, dim3(256), 0, stream, X, Y, pairs, state, vec, out, prm);
+    // one more product and the true residual for the pairs whose solution grew far beyond the
+    // Jacobi guess (none on well-conditioned workloads: these launches then return at once)
+    hipLaunchKernelGGL(mgk_large_verify_prepare_kernel, gv, dim3(256), 0, stream, pairs, state, vec);
+    hipError_t e = launch_large_xmv(X, Y, EX, EY, pairs, state, vec, prm, weighted, n_pairs, xmv_blocks, DX, DY,
+                                    rows_threads, rows_lds_bytes, rows_chunks, stream);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(mgk_large_verify_residual_kernel, gv, dim3(256), 0, stream, X, Y, pairs, state, vec, prm);
     hipLaunchKernelGGL(mgk_large_store_kernel, dim3((n_pairs + 63) / 64), dim3(64), 0, stream, pairs, state,
                        n_pairs, out);
     return hipGetLastError();

@@ -125,8 +125,10 @@ hipError_t mgk_launch_expand_dense(const MgkBatchDev& B, const MgkParams& prm, f
 hipError_t mgk_launch_large_init(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkLargePair* pairs,
                                  MgkPairState* state, float* vec, const MgkParams& prm, int n_pairs,
                                  int vec_blocks, hipStream_t stream);
-// One iteration of Alg. 1 for all pairs that have not stopped; *n_active is
-// decremented for every pair that stops.  DX/DY non-null: dense tile-pair XMV
+// Iteration `it` (0, 1, ...) of Alg. 1 for all pairs that have not stopped: the product, then
+// three kernels over the vectors that also do the scalar steps and the stop test.  n_active[0]
+// is decremented for every pair that stops, n_active[1] raised to the number of iterations
+// it took.  DX/DY non-null: dense tile-pair XMV
 // (xmv_blocks = workgroups of 4 output blocks); else the sparse XMV on the
 // expanded lists: with rows_threads > 0 the one that stages rows of p in
 // rows_lds_bytes of LDS (xmv_blocks = outer rows, one workgroup of rows_threads
@@ -137,13 +139,18 @@ hipError_t mgk_launch_large_iteration(const MgkBatchDev& X, const MgkBatchDev& Y
                                       const MgkExpanded& EY, const MgkLargePair* pairs,
                                       MgkPairState* state, float* vec, const MgkParams& prm,
                                       bool weighted, int n_pairs, int xmv_blocks, int vec_blocks,
-                                      int* n_active, bool first, const MgkDenseTiles* DX,
+                                      int* n_active, int it, const MgkDenseTiles* DX,
                                       const MgkDenseTiles* DY, int rows_threads, int rows_lds_bytes,
                                       int rows_chunks, hipStream_t stream);
-// K = p_x^T x and the per-pair outputs.
-hipError_t mgk_launch_large_final(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkLargePair* pairs,
-                                  MgkPairState* state, const float* vec, int n_pairs, int vec_blocks,
-                                  const MgkOutputs& out, hipStream_t stream);
+// K = p_x^T x, the nodal solution, a check of the true residual for pairs whose solution grew
+// far beyond the Jacobi guess (one more product, arguments as for an iteration), and the
+// per-pair outputs.
+hipError_t mgk_launch_large_final(const MgkBatchDev& X, const MgkBatchDev& Y, const MgkExpanded& EX,
+                                  const MgkExpanded& EY, const MgkLargePair* pairs, MgkPairState* state,
+                                  float* vec, const MgkParams& prm, bool weighted, int n_pairs, int xmv_blocks,
+                                  int vec_blocks, const MgkDenseTiles* DX, const MgkDenseTiles* DY,
+                                  int rows_threads, int rows_lds_bytes, int rows_chunks, const MgkOutputs& out,
+                                  hipStream_t stream);
 // In-place normalisation K[i][j] /= sqrt(K[i][i] K[j][j]) of an n x n matrix; diag holds n floats.
 hipError_t mgk_launch_normalize(float* K, float* diag, int n, hipStream_t stream);
 
