@@ -163,6 +163,9 @@ def main() -> int:
     ap.add_argument("--ablation", action="store_true",
                     help="instead of the benchmark line: time the optimisation levels of the paper's "
                          "incremental study and a workgroup-size sweep, one JSON line each")
+    ap.add_argument("--on-the-fly", type=int, default=1,
+                    help="1: after the timed steps also time the step with the entries regenerated in "
+                         "every product and report it beside the default (0 for counter runs)")
     ap.add_argument("--cpu-sample", type=int, default=64, help="pairs timed on the CPU oracle (0 = skip)")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="also run one device-to-device copy of this many MiB before the timed region; "
@@ -352,15 +355,12 @@ def main() -> int:
     # count per element pair and iteration.  Entries cached in registers: one multiply-add
     # (2 flop) per element pair and iteration, plus the one-off generation of each entry.
     zz = float((z[pi] * z[pj]).sum())
-    if entries_cached and cached_pairs == n_pairs:
-        executed_flops = 2.0 * element_pairs + (flops_per_element_pair - 2) * zz
-        executed_per_pair_iter = 2
-    elif not entries_cached:
-        executed_flops = alg_flops
-        executed_per_pair_iter = flops_per_element_pair
-    else:
-        executed_flops = None       # mixed launch: no single figure
-        executed_per_pair_iter = None
+    # (A few pairs of a cached launch may not fit the entry-keeping kernel; they are counted
+    # by their share of the pairs.)
+    cached_share = cached_pairs / n_pairs if n_pairs else 0.0
+    executed_per_pair_iter = 2 * cached_share + flops_per_element_pair * (1.0 - cached_share)
+    executed_flops = (executed_per_pair_iter * element_pairs
+                      + cached_share * (flops_per_element_pair - 2) * zz)
     traffic = hbm_traffic(wl, args)
     cflops = counted_flops(wl, args)
     out["roofline"] = {
@@ -369,6 +369,7 @@ def main() -> int:
         "kernel_families": families,
         "launch_shapes": len(launches),
         "entries_cached": entries_cached,
+        "entries_cached_share_of_pairs": cached_share,
         "achieved": achieved_tflops,
         "peak": FP32_VECTOR_PEAK_TFLOPS,
         "unit": "TFLOP/s",
@@ -386,6 +387,32 @@ def main() -> int:
         "element_pairs_per_step": element_pairs,
         "kernel_ms_per_step": kernel_s * 1e3,
     }
+
+    # The same step with the entries regenerated in every product (Alg. 2 as printed), so that
+    # the rate of flops actually executed by the on-the-fly product stands beside the default.
+    if entries_cached and pair_list is None and args.product_cache == 1 and args.on_the_fly:
+        solver.set_product_cache(0)
+        step()
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(2)]
+        for a, b in evs:
+            a.record()
+            step()
+            b.record()
+        torch.cuda.synchronize()
+        otf_s = float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e-3
+        it2 = iters.cpu().numpy().astype(np.float64)[pi, pj]
+        ep2 = float((it2 * z[pi] * z[pj]).sum())
+        out["roofline"]["on_the_fly"] = {
+            "kernel_ms_per_step": otf_s * 1e3,
+            "pairs_per_s": n_pairs / otf_s,
+            "frac": flops_per_element_pair * ep2 / otf_s / 1e12 / FP32_VECTOR_PEAK_TFLOPS,
+            "note": "mgk_set_product_cache(0): every entry regenerated in every product, "
+                    "%d flop per element pair executed" % flops_per_element_pair,
+        }
+        solver.set_product_cache(1)
+        step()   # leave K, iters, flags as the default path wrote them
+        torch.cuda.synchronize()
 
     if args.cpu_sample > 0:
         from oracle import c_oracle as C

@@ -68,7 +68,8 @@ typedef enum {
 } mgk_status;
 
 /* vertex reordering applied when a batch is loaded (Section IV-A) */
-enum { MGK_REORDER_NONE = 0, MGK_REORDER_PBR = 1, MGK_REORDER_RCM = 2 };
+enum { MGK_REORDER_NONE = 0, MGK_REORDER_PBR = 1, MGK_REORDER_RCM = 2,
+       MGK_REORDER_MORTON = 3 /* only through mgk_load_graphs_embedded */ };
 /* tile-pair primitive selection (Section IV-B, "hybrid dense-sparse") */
 enum { MGK_TILE_AUTO = 0, MGK_TILE_SPARSE = 1, MGK_TILE_DENSE = 2, MGK_TILE_SPARSE_GATHER = 3 };
 
@@ -184,6 +185,16 @@ mgk_status mgk_load_graphs_attr(mgk_ctx* ctx, int32_t n_graphs,
                                 const int64_t* edge_off, const int32_t* src, const int32_t* dst,
                                 const float* weight, int32_t label_dim, const float* edge_label,
                                 int32_t reorder, mgk_batch** out);
+/* Graphs whose vertices come with coordinates (coords[(sum n) * coord_dim], coord_dim
+ * 1..3, finite): as mgk_load_graphs, with the vertices of every graph numbered along the
+ * Morton (Z-order) curve through the graph's bounding box, the space-filling-curve
+ * ordering of Section IV-A (10 bits per coordinate in 2 and 3 dimensions). */
+mgk_status mgk_load_graphs_embedded(mgk_ctx* ctx, int32_t n_graphs,
+                                    const int64_t* vtx_off, const int32_t* vtx_label,
+                                    const float* start_prob,
+                                    const int64_t* edge_off, const int32_t* src, const int32_t* dst,
+                                    const float* weight, const float* edge_label,
+                                    int32_t coord_dim, const float* coords, mgk_batch** out);
 void mgk_free_batch(mgk_ctx* ctx, mgk_batch* batch);
 
 /* Totals over the batch (any pointer may be NULL): graphs, vertices, stored

@@ -253,6 +253,7 @@ def geometric_batch(rng, n_graphs, n, mean_degree, n_vlabels, params, name="geo"
     the space-filling-curve ordering for graphs that come with an embedding.
     Both give the same graphs up to the numbering."""
     graphs = []
+    coords = []
     rc = (3.0 * mean_degree / (4.0 * np.pi * n)) ** (1.0 / 3.0)
     calibrated = False
     for _ in range(n_graphs):
@@ -273,11 +274,16 @@ def geometric_batch(rng, n_graphs, n, mean_degree, n_vlabels, params, name="geo"
             new_lab[rank] = lab
             a, b = rank[lo], rank[hi]
             lab, lo, hi = new_lab, np.minimum(a, b), np.maximum(a, b)
+            moved = np.empty_like(pts)
+            moved[rank] = pts
+            pts = moved
         elif order != "random":
             raise ValueError("order must be random or morton")
         graphs.append((n, lab, lo, hi, np.exp(-dist), dist))
+        coords.append(pts.astype(np.float32))
     b = _assemble(graphs, params, name)
     b.cutoff = rc  # type: ignore[attr-defined]
+    b.coords = np.concatenate(coords)  # type: ignore[attr-defined]   # [sum n, 3], in the numbering of the batch
     return b
 
 

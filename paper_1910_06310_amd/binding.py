@@ -27,7 +27,7 @@ EXPORTS = [
     "mgk_load_graphs_attr",
     "mgk_set_stop_prob", "mgk_set_solver", "mgk_set_tile_path", "mgk_set_launch",
     "mgk_set_onchip_limit", "mgk_set_product_cache", "mgk_set_schedule",
-    "mgk_load_graphs", "mgk_free_batch", "mgk_batch_stats", "mgk_batch_permutation",
+    "mgk_load_graphs", "mgk_load_graphs_embedded", "mgk_free_batch", "mgk_batch_stats", "mgk_batch_permutation",
     "mgk_batch_get_tiles", "mgk_gram", "mgk_pairs", "mgk_pairs_dev", "mgk_pairs_noalloc", "mgk_pairs_nodal", "mgk_normalize_gram", "mgk_launch_log",
 ]
 
@@ -72,6 +72,7 @@ def load_library(path: Optional[str] = None):
     lib.mgk_set_product_cache.argtypes = [vp, i32]
     lib.mgk_set_schedule.argtypes = [vp, i32]
     lib.mgk_load_graphs.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, c.POINTER(vp)]
+    lib.mgk_load_graphs_embedded.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, c.POINTER(vp)]
     lib.mgk_free_batch.argtypes = [vp, vp]
     lib.mgk_free_batch.restype = None
     lib.mgk_batch_stats.argtypes = [vp] + [c.POINTER(i64)] * 5
@@ -247,6 +248,27 @@ class Solver:
         h = ctypes.c_void_p()
         self._check(lib.mgk_load_graphs_attr(self._h, len(vo) - 1, pvo, pvl, psp, peo, ps, pd, pw, dim, pe,
                                              reorder, ctypes.byref(h)))
+        return Batch(self, h, vo.copy())
+
+    def load_graphs_embedded(self, vtx_off, vtx_label, edge_off, src, dst, coords, weight=None,
+                             edge_label=None, start_prob=None) -> Batch:
+        """Graphs with vertex coordinates ([sum n, dim]), numbered along the Morton curve."""
+        lib = load_library()
+        vo, pvo = _host(vtx_off, np.int64)
+        vl, pvl = _host(vtx_label, np.int32)
+        sp, psp = _host(start_prob, np.float32)
+        eo, peo = _host(edge_off, np.int64)
+        s, ps = _host(src, np.int32)
+        d, pd = _host(dst, np.int32)
+        w, pw = _host(weight, np.float32)
+        e, pe = _host(edge_label, np.float32)
+        xy = np.ascontiguousarray(coords, dtype=np.float32)
+        if xy.ndim != 2 or xy.shape[0] != int(vo[-1]):
+            raise ValueError("coords must be [total vertices, dim]")
+        h = ctypes.c_void_p()
+        self._check(lib.mgk_load_graphs_embedded(self._h, len(vo) - 1, pvo, pvl, psp, peo, ps, pd, pw, pe,
+                                                 int(xy.shape[1]), xy.ctypes.data_as(ctypes.c_void_p),
+                                                 ctypes.byref(h)))
         return Batch(self, h, vo.copy())
 
     def load_batch(self, batch, reorder: int = REORDER_PBR, start_prob=None) -> Batch:

@@ -959,7 +959,7 @@ static mgk_status load_graphs_body(mgk_ctx* ctx, int32_t n_graphs, const int64_t
                                    const int32_t* vtx_label, const float* start_prob,
                                    const int64_t* edge_off, const int32_t* src, const int32_t* dst,
                                    const float* weight, int32_t label_dim, const float* edge_label,
-                                   int32_t reorder, mgk_batch** out);
+                                   int32_t reorder, int32_t coord_dim, const float* coords, mgk_batch** out);
 
 mgk_status mgk_load_graphs_attr(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_off,
                                 const int32_t* vtx_label, const float* start_prob,
@@ -968,7 +968,21 @@ mgk_status mgk_load_graphs_attr(mgk_ctx* ctx, int32_t n_graphs, const int64_t* v
                                 int32_t reorder, mgk_batch** out) {
     return guarded(ctx, [&] {
         return load_graphs_body(ctx, n_graphs, vtx_off, vtx_label, start_prob, edge_off, src, dst, weight,
-                                label_dim, edge_label, reorder, out);
+                                label_dim, edge_label, reorder, 0, nullptr, out);
+    });
+}
+
+mgk_status mgk_load_graphs_embedded(mgk_ctx* ctx, int32_t n_graphs, const int64_t* vtx_off,
+                                    const int32_t* vtx_label, const float* start_prob,
+                                    const int64_t* edge_off, const int32_t* src, const int32_t* dst,
+                                    const float* weight, const float* edge_label, int32_t coord_dim,
+                                    const float* coords, mgk_batch** out) {
+    return guarded(ctx, [&]() -> mgk_status {
+        if (!ctx) return MGK_EINVAL;
+        if (coord_dim < 1 || coord_dim > 3) return fail(ctx, MGK_EINVAL, "coordinates must have 1 to 3 dimensions, got %d", coord_dim);
+        if (!coords) return fail(ctx, MGK_EINVAL, "coords is null");
+        return load_graphs_body(ctx, n_graphs, vtx_off, vtx_label, start_prob, edge_off, src, dst, weight, 1,
+                                edge_label, MGK_REORDER_MORTON, coord_dim, coords, out);
     });
 }
 
@@ -976,15 +990,15 @@ static mgk_status load_graphs_body(mgk_ctx* ctx, int32_t n_graphs, const int64_t
                                    const int32_t* vtx_label, const float* start_prob,
                                    const int64_t* edge_off, const int32_t* src, const int32_t* dst,
                                    const float* weight, int32_t label_dim, const float* edge_label,
-                                   int32_t reorder, mgk_batch** out) {
+                                   int32_t reorder, int32_t coord_dim, const float* coords, mgk_batch** out) {
     if (!ctx || !out) return MGK_EINVAL;
     *out = nullptr;
     if (label_dim < 1 || label_dim > MGK_MAX_LABEL_DIM)
         return fail(ctx, MGK_EINVAL, "label attributes must be 1 to %d, got %d", MGK_MAX_LABEL_DIM, label_dim);
     const int D = label_dim;
     if (n_graphs < 0 || !vtx_off || !edge_off) return fail(ctx, MGK_EINVAL, "null offsets or negative graph count");
-    if (reorder < MGK_REORDER_NONE || reorder > MGK_REORDER_RCM)
-        return fail(ctx, MGK_EINVAL, "unknown reorder mode %d", reorder);
+    if (reorder < MGK_REORDER_NONE || reorder > MGK_REORDER_MORTON || (reorder == MGK_REORDER_MORTON && !coords))
+        return fail(ctx, MGK_EINVAL, "unknown reorder mode %d (the space-filling-curve order needs mgk_load_graphs_embedded)", reorder);
     if (vtx_off[0] != 0 || edge_off[0] != 0) return fail(ctx, MGK_EINVAL, "offset arrays must start at 0");
     // every array below is sized by the last offsets: they must bound all the others
     for (int32_t g = 0; g < n_graphs; ++g) {
@@ -1036,7 +1050,7 @@ static mgk_status load_graphs_body(mgk_ctx* ctx, int32_t n_graphs, const int64_t
     // sound.  The loop below validates each graph in full (so errors are reported as before,
     // for the first bad graph) and only then takes the order computed here.
     std::vector<std::vector<int32_t>> pre_perm((size_t)n_graphs);
-    if (reorder != MGK_REORDER_NONE && n_graphs >= 8) {
+    if ((reorder == MGK_REORDER_PBR || reorder == MGK_REORDER_RCM) && n_graphs >= 8) {
         const int T = (int)std::max(1u, std::min({std::thread::hardware_concurrency(), 16u, (unsigned)n_graphs / 4u}));
         auto order_worker = [&](int t) {
           try {   // a worker that runs out of memory stops; the loop below orders what it left
@@ -1123,7 +1137,11 @@ static mgk_status load_graphs_body(mgk_ctx* ctx, int32_t n_graphs, const int64_t
         if (!pre_perm[(size_t)g].empty()) perm = std::move(pre_perm[(size_t)g]);
         else if (reorder == MGK_REORDER_PBR) perm = mgk_order_pbr(adj, kTile);
         else if (reorder == MGK_REORDER_RCM) perm = mgk_order_rcm(adj);
-        else perm = mgk_order_identity(n);
+        else if (reorder == MGK_REORDER_MORTON) {
+            for (int64_t k = v0 * coord_dim; k < v1 * coord_dim; ++k)
+                if (!std::isfinite(coords[k])) return fail(ctx, MGK_EINVAL, "graph %d: coordinate is not finite", g);
+            perm = mgk_order_morton(n, coord_dim, coords + v0 * coord_dim);
+        } else perm = mgk_order_identity(n);
         std::copy(perm.begin(), perm.end(), B->perm.begin() + v0);
 
         // ---- per-vertex data in stored order; a1: row sums for d_i = sum_j A_ij + q

@@ -21,6 +21,36 @@ std::vector<int32_t> mgk_order_identity(int n) {
     return p;
 }
 
+// ---------------------------------------------------------------- Morton curve
+std::vector<int32_t> mgk_order_morton(int n, int dim, const float* coords) {
+    const int bits = 21 / dim;   // 21, 10 or 7 bits per coordinate
+    std::vector<float> lo(dim, 0.f), hi(dim, 0.f);
+    for (int a = 0; a < dim; ++a) {
+        lo[a] = hi[a] = n ? coords[a] : 0.f;
+        for (int v = 1; v < n; ++v) {
+            lo[a] = std::min(lo[a], coords[(size_t)v * dim + a]);
+            hi[a] = std::max(hi[a], coords[(size_t)v * dim + a]);
+        }
+    }
+    std::vector<std::pair<uint64_t, int32_t>> key(n);
+    const double cells = (double)(1u << bits);
+    for (int v = 0; v < n; ++v) {
+        uint64_t k = 0;
+        for (int a = 0; a < dim; ++a) {
+            const double span = (double)hi[a] - (double)lo[a];
+            const double u = span > 0.0 ? ((double)coords[(size_t)v * dim + a] - lo[a]) / span : 0.0;
+            const uint64_t q = (uint64_t)std::min(cells - 1.0, std::max(0.0, u * cells));
+            for (int b = 0; b < bits; ++b) k |= ((q >> b) & 1ull) << (dim * b + a);
+        }
+        key[v] = {k, v};
+    }
+    std::stable_sort(key.begin(), key.end(),
+                     [](const std::pair<uint64_t, int32_t>& x, const std::pair<uint64_t, int32_t>& y) { return x.first < y.first; });
+    std::vector<int32_t> perm(n);
+    for (int r = 0; r < n; ++r) perm[key[r].second] = r;
+    return perm;
+}
+
 // ---------------------------------------------------------------- RCM
 namespace {
 

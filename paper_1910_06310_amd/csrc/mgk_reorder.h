@@ -24,6 +24,13 @@ std::vector<int32_t> mgk_order_rcm(const MgkAdj& g);
 // [k t, (k+1) t).
 std::vector<int32_t> mgk_order_pbr(const MgkAdj& g, int t);
 
+// Space-filling-curve order for vertices with coordinates (Section IV-A): each of the
+// `dim` (1..3) coordinates is scaled to the graph's bounding box and quantised to 10
+// bits (21 / dim bits), the bits of the coordinates are interleaved (Morton, Z-order),
+// and the vertices are numbered by that key (ties in the given order).
+// coords[v * dim + a], all finite.
+std::vector<int32_t> mgk_order_morton(int n, int dim, const float* coords);
+
 // Number of ordered pairs (k, l), k != l, of t-blocks of the new numbering
 // that are joined by at least one edge: the non-empty off-diagonal tiles.
 int64_t mgk_count_offdiag_tiles(const MgkAdj& g, const std::vector<int32_t>& perm, int t);

@@ -179,3 +179,40 @@ def test_offsets_are_validated_before_anything_is_sized_by_them(solver):
     # the context is still usable
     b = W.config0()
     assert solver.load_batch(b).stats()["n_graphs"] == 4
+
+
+def test_space_filling_curve_order_of_embedded_graphs(solver):
+    """mgk_load_graphs_embedded numbers the vertices of graphs that come with coordinates
+    along the Morton curve (Section IV-A).  On points in the unit cube the numbering must be
+    the one obtained by sorting the interleaved 10-bit cell indices (computed here from the
+    definition), the packed form must still be the same graph, and the tile count must
+    fall well below that of the random numbering."""
+    rng = np.random.default_rng(5)
+    b = W.geometric_batch(rng, 3, 300, 12, 4, W.KernelParams(), order="random")
+    B = solver.load_graphs_embedded(b.vtx_off, b.vtx_label, b.edge_off, b.src, b.dst, b.coords,
+                                    weight=b.weight, edge_label=b.edge_label)
+    perm = B.permutation()
+    for g in range(3):
+        v0, v1 = int(b.vtx_off[g]), int(b.vtx_off[g + 1])
+        pts = b.coords[v0:v1].astype(np.float64)
+        lo, hi = pts.min(0), pts.max(0)
+        cell = np.minimum(((pts - lo) / (hi - lo) * 1024).astype(np.int64), 1023)
+        key = np.zeros(len(pts), np.int64)
+        for bit in range(10):
+            for axis in range(3):
+                key |= ((cell[:, axis] >> bit) & 1) << (3 * bit + axis)
+        expect = np.empty(len(pts), np.int64)
+        expect[np.argsort(key, kind="stable")] = np.arange(len(pts))
+        p = perm[v0:v1]
+        assert sorted(p) == list(range(len(pts)))
+        # cells are computed in float32 there and float64 here: allow the few points that sit
+        # on a cell boundary to differ
+        assert (p == expect).mean() > 0.97
+        A, E = dense_from_batch(b, g)
+        Ap, Ep = unpack(B.get_tiles(g), len(pts))
+        np.testing.assert_array_equal(Ap[np.ix_(p, p)], A)
+        np.testing.assert_array_equal(Ep[np.ix_(p, p)], E)
+    random_tiles = solver.load_batch(b, reorder=M.REORDER_NONE).stats()["n_tiles"]
+    assert B.stats()["n_tiles"] < 0.5 * random_tiles
+    with pytest.raises(M.MgkError):
+        solver.load_batch(b, reorder=3)   # the curve order needs coordinates
