@@ -150,7 +150,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--graphs", type=int, default=2000, help="graphs in the batch (2000 = the named workload)")
     ap.add_argument("--workload", default="config4",
-                    help="config4 (default, the benchmark line), config0, config1, config2:<density>, config3, nws, ba")
+                    help="config4 (default, the benchmark line), config0, config1, config2:<density>, "
+                         "mixed:<density>:<density>, config3, nws, ba")
     ap.add_argument("--waves", type=int, default=0, help="wavefronts per pair (0 = library default)")
     ap.add_argument("--reorder", type=int, default=1, help="0 none, 1 PBR, 2 RCM")
     ap.add_argument("--tile-path", type=int, default=0, help="global-memory solver: 0 auto, 1 sparse, 2 dense, 3 sparse with p gathered from global memory")
@@ -203,6 +204,14 @@ def main() -> int:
         wb = W.config2(rho)
         pair_list = (np.arange(0, 128, 2, dtype=np.int32), np.arange(1, 128, 2, dtype=np.int32))
         wl_name = "config2: 64 pairs of ER graphs, n=256, edge density %g" % rho
+    elif wl.startswith("mixed:"):
+        # 64 pairs of one graph of each of two densities (n = 256): the cross-density study of
+        # the tile-pair primitives (Section IV-B)
+        _, da, db = wl.split(":")
+        wb = W.concat_batches([W.config2(float(da), 64), W.config2(float(db), 64)],
+                              name="mixed[%s x %s]" % (da, db))
+        pair_list = (np.arange(0, 64, dtype=np.int32), np.arange(64, 128, dtype=np.int32))
+        wl_name = "64 pairs of ER graphs, n=256, edge densities %s against %s" % (da, db)
     elif wl in ("nws", "ba"):
         wb = W.paper_synthetic(wl)
         wl_name = "paper synthetic set %s: Gram of 160 graphs of 96 nodes" % wl.upper()

@@ -250,3 +250,39 @@ def test_geometric_graphs_with_rows_of_p_not_a_multiple_of_four(torch, solver):
     K, it, fl = run_pairs(torch, solver, B, pi, pj)
     np.testing.assert_allclose(K, C.pairs(wb, pi, pj, tier=1), rtol=RTOL)
     assert (fl == 0).all()
+
+
+def test_mixed_density_pairs(torch, solver):
+    """Pairs of one complete and one sparse graph (the middle band of the paper's
+    dense / sparse primitive study, Section IV-B): n = 256 at densities 1.0 x 0.05 with both
+    tile paths by the a-posteriori residual, and n = 64 against the dense fp64 oracle."""
+    wb = W.concat_batches([W.config2(1.0, 4), W.config2(0.05, 4)], name="mixed")
+    solver.configure(wb.params)
+    solver.set_solver(1e-6, 0)
+    B = solver.load_batch(wb)
+    pi = np.arange(0, 4, dtype=np.int32)
+    pj = pi + 4
+    values = {}
+    try:
+        for path in (M.TILE_AUTO, M.TILE_SPARSE, M.TILE_DENSE):
+            solver.set_tile_path(path)
+            K, xs, it, fl = run_pairs_nodal(torch, solver, B, wb, pi, pj)
+            assert (fl == 0).all() and (it > 0).all()
+            assert_all_pairs_by_residual(wb, pi[:2], pj[:2], K[:2], xs[:2])
+            values[path] = K
+        np.testing.assert_allclose(values[M.TILE_SPARSE], values[M.TILE_DENSE], rtol=2e-5)
+        np.testing.assert_allclose(values[M.TILE_AUTO], values[M.TILE_SPARSE], rtol=2e-5)
+        B.free()
+        ws = W.concat_batches([W.config2(1.0, 2, 64), W.config2(0.05, 2, 64)], name="mixed small")
+        solver.set_onchip_limit(0)   # the same kernels at a size the dense oracle can take
+        Bs = solver.load_batch(ws)
+        pi = np.array([0, 1, 0], np.int32); pj = np.array([2, 3, 3], np.int32)
+        ref = C.pairs(ws, pi, pj, tier=0)
+        for path in (M.TILE_SPARSE, M.TILE_DENSE):
+            solver.set_tile_path(path)
+            K, it, fl = run_pairs(torch, solver, Bs, pi, pj)
+            np.testing.assert_allclose(K, ref, rtol=RTOL)
+            assert (fl == 0).all()
+    finally:
+        solver.set_tile_path(M.TILE_AUTO)
+        solver.set_onchip_limit(16384)
