@@ -299,6 +299,7 @@ __global__ __launch_bounds__(W * 64) void mgk_pcg_regs(MgkBatchDev X, MgkBatchDe
     }
 #pragma unroll
     for (int m = 0; m < EPT; ++m) y[tid + m * NT] = 0.f;
+    if (tid == 0) red[63] = 0.f;
 
     // ---- this wave's outer rows: whole rows, divided at load so that the most loaded
     //      wavefront is as light as possible
@@ -308,10 +309,12 @@ __global__ __launch_bounds__(W * 64) void mgk_pcg_regs(MgkBatchDev X, MgkBatchDe
     int kend = rend < n1 ? X.rowptr[g1.voff + rend] : z1;
     kbeg = __builtin_amdgcn_readfirstlane(kbeg);
     kend = __builtin_amdgcn_readfirstlane(kend);
-    // The host only sends pairs whose runs fit the unrolled loop; every wavefront reports
-    // whether its run does, and the workgroup checks after the next barrier.
-    if (lane == 0) red[56 + wave] = kend - kbeg > SMAX ? 1.f : 0.f;
-    const int S = kend - kbeg;
+    // The host only sends pairs whose runs fit the unrolled loop.  Should one not fit, the
+    // solve goes on with the part that does (so that every loop stays in bounds) and the
+    // pair's outputs are replaced at the end: value NaN, flag 2, never a value computed
+    // with part of the matrix.  red[63] is cleared before the staging barrier below.
+    const bool misfit = kend - kbeg > SMAX;
+    const int S = min(kend - kbeg, SMAX);
 
     // lane l < S holds the wave's l-th outer nonzero
     const bool live1 = lane < S;
@@ -381,22 +384,7 @@ __global__ __launch_bounds__(W * 64) void mgk_pcg_regs(MgkBatchDev X, MgkBatchDe
         }
     }
     __syncthreads();   // per-vertex data staged
-    {
-        // A pair that does not fit is not solved with part of its matrix: value NaN, flag 2.
-        float misfit = 0.f;
-#pragma unroll
-        for (int w = 0; w < W; ++w) misfit += red[56 + w];
-        if (misfit != 0.f) {   // the same in every thread
-            if (tid == 0) {
-                const float bad = __builtin_nanf("");
-                out.K[job.out0] = bad;
-                if (job.out1 >= 0) out.K[job.out1] = bad;
-                if (out.iters) { out.iters[job.out0] = 0; if (job.out1 >= 0) out.iters[job.out1] = 0; }
-                if (out.flags) { out.flags[job.out0] = 2; if (job.out1 >= 0) out.flags[job.out1] = 2; }
-            }
-            return;
-        }
-    }
+    if (misfit && lane == 0) red[63] = 1.f;   // wave-uniform, after the barrier that follows the clearing
 
     // ---- Alg. 1 set-up: M = D_x V_x^{-1}, x = 0, r = b = D_x q_x, z = M^{-1} r,
     //      p = z, rho = r^T z ----------------------------------------------------
@@ -511,8 +499,12 @@ __global__ __launch_bounds__(W * 64) void mgk_pcg_regs(MgkBatchDev X, MgkBatchDe
             s_k = __builtin_fmaf(st1[i] * st2[i2], x[idx], s_k);  // x is 0 beyond N
         }
     }
-    const float Kval = block_sum<W>(s_k, red + 48, wave, lane);
+    float Kval = block_sum<W>(s_k, red + 48, wave, lane);
     if (tid == 0) {
+        if (red[63] != 0.f) {   // some wavefront's run did not fit
+            Kval = __builtin_nanf("");
+            flag = 2;
+        }
         out.K[job.out0] = Kval;
         if (job.out1 >= 0) out.K[job.out1] = Kval;
         if (out.iters) {
