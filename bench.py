@@ -9,8 +9,16 @@ the paper argues for its own measurements: reordering is done once, the Gram
 matrix is evaluated many times); launch -> values on the device is timed.
 
 Prints ONE JSON line with the throughput in graph pairs/s, the matvec
-element-pair rate, the ALU roofline fraction of the solver kernel (timed with
-HIP events on the launch stream) and the CPU oracle timed on a bounded sample.
+element-pair rate, the ALU roofline of the solver kernels (timed with HIP events
+on the launch stream) and the CPU oracle timed on a bounded sample.  The
+`roofline` object says which kernels ran (from the library's launch record),
+whether they keep the matrix entries in registers, and gives three fractions of
+the fp32 vector peak: `frac` (algorithmic flops of the paper's cost model),
+`frac_executed` (flops the product really executes: 2 per element pair and
+iteration when the entries are cached) and `frac_executed_counters` (all fp32
+vector flops, from the committed rocprofv3 counter summary of this command),
+the same step with the entries regenerated in every product (`on_the_fly`),
+and the HBM traffic from the committed FETCH_SIZE / WRITE_SIZE summary.
 """
 from __future__ import annotations
 
